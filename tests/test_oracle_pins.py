@@ -1,0 +1,402 @@
+"""Pins for the CPU oracle: everything here runs without a GPU.
+
+The oracle is the yardstick of every GPU parity test, so it is tied to things
+other than itself: a hand-derived closed-form case, invariants the paper
+states (Sec. 3.2, 3.3.1, App. A.3), special cases that reduce to textbook or
+library routines (torch.topk, scipy softmax, a dense SwiGLU FFN), and brute
+force over every mask pattern of a small case.
+"""
+import itertools
+import json
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+import oracle
+from paper_2605_14438_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand_layer(seed, T, H, N, K, I, keep_bias=0.0, mask_scale=1.0):
+    rng = np.random.default_rng(seed)
+    d = dict(
+        x=rng.standard_normal((T, H)).astype(np.float32),
+        w_router=(0.3 * rng.standard_normal((N, H))).astype(np.float32),
+        w_mask=(mask_scale * 0.3 * rng.standard_normal((N, H))).astype(np.float32),
+        w_gate_up=(0.2 * rng.standard_normal((N, 2 * I, H))).astype(np.float32),
+        w_down=(0.2 * rng.standard_normal((N, H, I))).astype(np.float32),
+        b_router=None,
+        b_mask=None if keep_bias == 0.0 else np.full((N,), keep_bias, np.float32),
+    )
+    return d
+
+
+def _fwd(d, K, **over):
+    a = dict(d)
+    a.update(over)
+    return oracle.moe_forward(a["x"], a["w_router"], a["b_router"], a["w_mask"], a["b_mask"],
+                              a["w_gate_up"], a["w_down"], K)
+
+
+def _dense_topk_moe(d, K):
+    """Textbook Top-K MoE (Eq. 1-3), structured differently from the oracle:
+    every expert evaluated for every token with library matmuls, routing weights
+    from torch.topk + a library softmax over the -inf filled logit vector."""
+    x = torch.from_numpy(d["x"]).double()
+    r = x @ torch.from_numpy(d["w_router"]).double().T
+    if d["b_router"] is not None:
+        r = r + torch.from_numpy(d["b_router"]).double()
+    r = r.float().double()        # logits are fp32 quantities
+    N = r.shape[1]
+    I = d["w_down"].shape[2]
+    _, idx = torch.topk(r, K, dim=1)
+    filled = torch.full_like(r, -float("inf"))
+    filled.scatter_(1, idx, r.gather(1, idx))
+    g = torch.from_numpy(scipy.special.softmax(filled.numpy(), axis=1))
+    y = torch.zeros_like(x)
+    for e in range(N):
+        wgu = torch.from_numpy(d["w_gate_up"][e]).double()
+        wd = torch.from_numpy(d["w_down"][e]).double()
+        gate = x @ wgu[:I].T
+        up = x @ wgu[I:].T
+        y += g[:, e:e + 1] * ((torch.nn.functional.silu(gate) * up) @ wd.T)
+    return y.numpy(), g.numpy()
+
+
+# --------------------------------------------------------------------------
+# closed form
+# --------------------------------------------------------------------------
+def test_micro_case_closed_form():
+    with open(os.path.join(GOLDEN, "micro_case.json")) as fh:
+        c = json.load(fh)
+    K = c["shape"]["K"]
+    N = c["shape"]["N"]
+    res = oracle.moe_forward(np.array(c["x"]), np.array(c["w_router"]), None,
+                             np.array(c["w_mask"]), None, np.array(c["w_gate_up"]),
+                             np.array(c["w_down"]), K)
+    exp = c["expected"]
+    tol = c["tolerance"]
+    assert res["topk_ids"].tolist() == exp["topk_ids"]
+    assert res["masked_ids"].tolist() == exp["masked_ids"]
+    np.testing.assert_allclose(res["topk_weights"], exp["topk_weights"], atol=tol, rtol=0)
+    np.testing.assert_allclose(res["out"], exp["out"], atol=tol, rtol=0)
+    assert res["pair_evals"] == exp["pair_evals"]
+    counts, offsets, perm, inv, P = oracle.permute(res["masked_ids"], N)
+    assert counts.tolist() == exp["expert_counts"]
+    assert offsets.tolist() == exp["expert_offsets"]
+    assert perm.tolist() == exp["perm"]
+    assert inv.tolist() == exp["inv_perm"]
+    assert P == exp["num_pairs"]
+
+
+# --------------------------------------------------------------------------
+# all-ones mask == standard Top-K MoE (zero-initialised mask router, Sec. 3.3.1)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("T,H,N,K,I", [(9, 24, 5, 3, 10), (6, 16, 8, 2, 40), (4, 40, 4, 4, 12)])
+def test_zero_mask_router_is_topk_moe(T, H, N, K, I):
+    d = _rand_layer(1, T, H, N, K, I)
+    res = _fwd(d, K, w_mask=np.zeros_like(d["w_mask"]))
+    assert (res["masked_ids"] == res["topk_ids"]).all()      # a == 0 keeps
+    assert res["pair_evals"] == T * K
+    ref, g_dense = _dense_topk_moe(d, K)
+    scale = np.sqrt((ref ** 2).mean())
+    assert np.abs(res["out"] - ref).max() <= 1e-9 * scale
+    g_sel = np.take_along_axis(g_dense, res["topk_ids"].astype(np.int64), axis=1)
+    np.testing.assert_allclose(res["topk_weights"], g_sel, atol=1e-12, rtol=0)
+    # same with a huge positive bias instead of zero weights
+    res2 = _fwd(d, K, b_mask=np.full((N,), 1e4, np.float32))
+    assert np.array_equal(res2["out"], res["out"])
+
+
+def test_router_bias_enters_logits():
+    d = _rand_layer(2, 7, 12, 6, 2, 8)
+    d["b_router"] = np.linspace(-2, 2, 6).astype(np.float32)
+    res = _fwd(d, 2, w_mask=np.zeros_like(d["w_mask"]))
+    ref, _ = _dense_topk_moe(d, 2)
+    assert np.abs(res["out"] - ref).max() <= 1e-9 * np.sqrt((ref ** 2).mean())
+
+
+# --------------------------------------------------------------------------
+# all-zero mask: layer contributes nothing (Sec. 3.2 Step 3, App. A.3)
+# --------------------------------------------------------------------------
+def test_all_dropped_is_exact_zero():
+    d = _rand_layer(3, 5, 16, 6, 3, 8)
+    res = _fwd(d, 3, b_mask=np.full((6,), -1e4, np.float32))
+    assert (res["masked_ids"] == -1).all()
+    assert res["pair_evals"] == 0
+    assert (res["out"] == 0.0).all() and not np.signbit(res["out"]).any()
+    counts, offsets, perm, inv, P = oracle.permute(res["masked_ids"], 6)
+    assert P == 0 and (counts == 0).all() and (perm == -1).all() and (inv == -1).all()
+
+
+# --------------------------------------------------------------------------
+# routing weights (Eq. 4)
+# --------------------------------------------------------------------------
+def test_routing_weights_invariants_and_softmax_scope():
+    rng = np.random.default_rng(4)
+    T, N, K = 50, 16, 5
+    r = rng.standard_normal((T, N)).astype(np.float32) * 2
+    a = rng.standard_normal((T, N)).astype(np.float32)
+    ids, g, msk = oracle.route_mask(r, a, K)
+    np.testing.assert_allclose(g.sum(axis=1), 1.0, atol=1e-14)
+    assert (g > 0).all()
+    assert (np.diff(g, axis=1) <= 0).all()                    # slot k = rank k+1
+    # the selected set is the Top-K set of a library routine
+    ref_idx = torch.topk(torch.from_numpy(r), K, dim=1).indices.numpy()
+    assert np.array_equal(np.sort(ids, axis=1), np.sort(ref_idx, axis=1))
+    assert np.array_equal(ids, ref_idx)                        # and in rank order
+    # softmax over the K survivors == full softmax renormalised over them
+    full = scipy.special.softmax(r.astype(np.float64), axis=1)
+    sel = np.take_along_axis(full, ids.astype(np.int64), axis=1)
+    np.testing.assert_allclose(g, sel / sel.sum(axis=1, keepdims=True), rtol=1e-12)
+    # the mask never touches g; it only rewrites ids
+    ids2, g2, _ = oracle.route_mask(r, -np.abs(a) - 1, K)
+    assert np.array_equal(ids, ids2) and np.array_equal(g, g2)
+    a_sel = np.take_along_axis(a, ids.astype(np.int64), axis=1)
+    assert np.array_equal(msk, np.where(a_sel >= 0, ids, -1))
+
+
+def test_topk_tie_break_lower_index_first():
+    r = np.array([[1.0, 3.0, 3.0, 0.5, 3.0, 1.0]], dtype=np.float32)
+    a = np.ones_like(r)
+    ids, g, _ = oracle.route_mask(r, a, 4)
+    assert ids.tolist() == [[1, 2, 4, 0]]
+    np.testing.assert_allclose(g[0, :3], g[0, 0])
+
+
+def test_mask_threshold_boundary():
+    """Eq. 6 keeps at sigma(a) >= 0.5, i.e. a >= 0: zero and negative zero keep,
+    the smallest negative number drops (sigma of it still rounds to 0.5 in
+    fp32, which is why the comparison is on a)."""
+    r = np.array([[3.0, 2.0, 1.0, 0.0]], dtype=np.float32)
+    tiny = np.float32(-1e-45)
+    a = np.array([[0.0, -0.0, tiny, 1e-45]], dtype=np.float32)
+    assert tiny < 0
+    _, _, msk = oracle.route_mask(r, a, 4)
+    assert msk.tolist() == [[0, 1, -1, 3]]
+
+
+# --------------------------------------------------------------------------
+# masked aggregation: brute force over every mask pattern (Eq. 7-8)
+# --------------------------------------------------------------------------
+def _swiglu_textbook(x, wgu, wd):
+    I = wd.shape[1]
+    x = x.astype(np.float64)
+    gate = wgu[:I].astype(np.float64) @ x
+    up = wgu[I:].astype(np.float64) @ x
+    return wd.astype(np.float64) @ (gate / (1.0 + np.exp(-gate)) * up)
+
+
+@pytest.mark.parametrize("N,K", [(4, 3), (8, 2)])
+def test_every_mask_pattern_is_the_masked_sum(N, K):
+    """Fig. 3's setting (4 experts, K=3) and the tiny config's (8, 2): for each
+    of the 2^K patterns, forced through the mask bias on a single token, the
+    layer output is sum_k m_k g_k E_k(x) with g not renormalised."""
+    H, I = 12, 20
+    d = _rand_layer(5, 1, H, N, K, I)
+    base = _fwd(d, K, w_mask=np.zeros_like(d["w_mask"]))
+    ids = base["topk_ids"][0]
+    g = base["topk_weights"][0]
+    contrib = [g[k] * _swiglu_textbook(d["x"][0], d["w_gate_up"][ids[k]], d["w_down"][ids[k]])
+               for k in range(K)]
+    for pattern in itertools.product([0, 1], repeat=K):
+        bias = np.full((N,), -1e4, np.float32)
+        for k, m in enumerate(pattern):
+            if m:
+                bias[ids[k]] = 1e4
+        res = _fwd(d, K, w_mask=np.zeros_like(d["w_mask"]), b_mask=bias)
+        want = np.zeros(H)
+        for k, m in enumerate(pattern):
+            if m:
+                want = want + contrib[k]
+        assert res["masked_ids"][0].tolist() == [int(ids[k]) if m else -1
+                                                 for k, m in enumerate(pattern)]
+        np.testing.assert_allclose(res["topk_weights"][0], g, rtol=0, atol=0)
+        np.testing.assert_allclose(res["out"][0], want, atol=1e-12)
+        assert res["pair_evals"] == sum(pattern)
+
+
+def test_expert_ffn_is_textbook_swiglu_and_not_transposed():
+    rng = np.random.default_rng(6)
+    H, I = 10, 28                     # H != I and 2I != H: a transposed operand cannot fit
+    x = rng.standard_normal(H).astype(np.float32)
+    wgu = rng.standard_normal((2 * I, H)).astype(np.float32)
+    wd = rng.standard_normal((H, I)).astype(np.float32)
+    y = oracle.expert_ffn(x, wgu, wd)
+    lin = torch.nn.functional.linear
+    xt = torch.from_numpy(x).double()
+    gate = lin(xt, torch.from_numpy(wgu[:I]).double())
+    up = lin(xt, torch.from_numpy(wgu[I:]).double())
+    ref = lin(torch.nn.functional.silu(gate) * up, torch.from_numpy(wd).double()).numpy()
+    np.testing.assert_allclose(y, ref, rtol=1e-12, atol=1e-12)
+    # gate and up are not interchangeable
+    swapped = np.concatenate([wgu[I:], wgu[:I]])
+    assert np.abs(oracle.expert_ffn(x, swapped, wd) - y).max() > 1e-3
+
+
+# --------------------------------------------------------------------------
+# special cases
+# --------------------------------------------------------------------------
+def test_k_equals_1():
+    d = _rand_layer(7, 8, 12, 5, 1, 6, mask_scale=1.0)
+    res = _fwd(d, 1)
+    assert (res["topk_weights"] == 1.0).all()
+    for t in range(8):
+        e = res["masked_ids"][t, 0]
+        want = np.zeros(12) if e < 0 else _swiglu_textbook(d["x"][t], d["w_gate_up"][e],
+                                                           d["w_down"][e])
+        np.testing.assert_allclose(res["out"][t], want, atol=1e-12)
+    assert (res["masked_ids"] < 0).any() and (res["masked_ids"] >= 0).any()
+
+
+def test_k_equals_n_is_plain_softmax():
+    d = _rand_layer(8, 6, 10, 4, 4, 6)
+    res = _fwd(d, 4, w_mask=np.zeros_like(d["w_mask"]))
+    r = oracle.logits(d["x"], d["w_router"]).astype(np.float64)
+    full = scipy.special.softmax(r, axis=1)
+    got = np.zeros_like(full)
+    np.put_along_axis(got, res["topk_ids"].astype(np.int64), res["topk_weights"], axis=1)
+    np.testing.assert_allclose(got, full, rtol=1e-12)
+
+
+def test_single_expert_is_a_dense_ffn():
+    d = _rand_layer(9, 5, 14, 1, 1, 9)
+    res = _fwd(d, 1, w_mask=np.zeros_like(d["w_mask"]))
+    for t in range(5):
+        np.testing.assert_allclose(res["out"][t], _swiglu_textbook(d["x"][t], d["w_gate_up"][0],
+                                                                   d["w_down"][0]), atol=1e-12)
+
+
+def test_logits_match_library_matmul():
+    rng = np.random.default_rng(10)
+    x = rng.standard_normal((7, 33)).astype(np.float32)
+    w = rng.standard_normal((5, 33)).astype(np.float32)
+    b = rng.standard_normal(5).astype(np.float32)
+    ref = (x.astype(np.float64) @ w.astype(np.float64).T + b).astype(np.float32)
+    assert np.array_equal(oracle.logits(x, w, b), ref) or \
+        np.abs(oracle.logits(x, w, b) - ref).max() <= 1e-6
+    assert oracle.logits(x, w).shape == (7, 5)
+
+
+def test_token_permutation_equivariance():
+    d = _rand_layer(11, 12, 16, 6, 3, 8)
+    res = _fwd(d, 3)
+    p = np.random.default_rng(0).permutation(12)
+    res_p = _fwd(d, 3, x=d["x"][p])
+    assert np.array_equal(res_p["topk_ids"], res["topk_ids"][p])
+    assert np.array_equal(res_p["masked_ids"], res["masked_ids"][p])
+    assert np.array_equal(res_p["out"], res["out"][p])
+
+
+# --------------------------------------------------------------------------
+# compute proportional to the kept pairs (Sec. 4.3)
+# --------------------------------------------------------------------------
+def test_expert_evaluations_equal_kept_pairs():
+    cfg = synth.CONFIGS["tiny"].with_(T=96)
+    d = synth.make_layer(cfg)
+    res = _fwd(d, cfg.K)
+    counts, offsets, perm, inv, P = oracle.permute(res["masked_ids"], cfg.N)
+    assert res["pair_evals"] == P == counts.sum() == offsets[-1] == (res["masked_ids"] >= 0).sum()
+    keep = P / (cfg.T * cfg.K)
+    assert 0.35 < keep < 0.65                      # ~50% of Top-K pairs kept
+    per_token = (res["masked_ids"] >= 0).sum(axis=1)
+    assert per_token.min() == 0 and per_token.max() == cfg.K
+    zero_rows = per_token == 0
+    assert (res["out"][zero_rows] == 0).all()
+    # pair_outputs agrees with the fused loop: out = sum_k g_k * y_slot
+    y_slots, n = oracle.pair_outputs(d["x"], d["w_gate_up"], d["w_down"], res["masked_ids"])
+    assert n == P
+    comb = (res["topk_weights"][:, :, None] * y_slots.reshape(cfg.T, cfg.K, cfg.H))
+    want = np.zeros((cfg.T, cfg.H))
+    for k in range(cfg.K):
+        want += comb[:, k]
+    np.testing.assert_allclose(res["out"], want, atol=1e-15)
+
+
+# --------------------------------------------------------------------------
+# grouping by expert (App. A.4)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_permutation_against_library_stable_sort(seed):
+    rng = np.random.default_rng(seed)
+    T, K, N = 37, 4, 9
+    m = rng.integers(-1, N, size=(T, K)).astype(np.int32)
+    m[rng.random((T, K)) < 0.3] = -1
+    if seed == 2:
+        m[0, 0] = N + 3          # out-of-range ids are dropped too
+        m[1, 1] = -7
+    counts, offsets, perm, inv, P = oracle.permute(m, N)
+    flat = m.reshape(-1)
+    valid = (flat >= 0) & (flat < N)
+    kept = np.flatnonzero(valid)
+    order = kept[np.argsort(flat[kept], kind="stable")]
+    assert P == kept.size
+    assert np.array_equal(perm[:P], order) and (perm[P:] == -1).all()
+    assert np.array_equal(counts, np.bincount(flat[valid], minlength=N))
+    assert np.array_equal(offsets, np.concatenate([[0], np.cumsum(counts)]))
+    assert (inv[~valid] == -1).all()
+    assert np.array_equal(inv[perm[:P]], np.arange(P))
+    for e in range(N):
+        seg = perm[offsets[e]:offsets[e + 1]]
+        assert (flat[seg] == e).all() and (np.diff(seg) > 0).all()
+
+
+# --------------------------------------------------------------------------
+# input generator (no method arithmetic in it; the keep-rate is checked here)
+# --------------------------------------------------------------------------
+def test_bf16_rounding_matches_library():
+    rng = np.random.default_rng(12)
+    a = (rng.standard_normal(20000) * np.exp(rng.uniform(-20, 20, 20000))).astype(np.float32)
+    a[:4] = [0.0, -0.0, 1.00390625, 1.01171875]       # exact ties: round to even
+    ref = torch.from_numpy(a).to(torch.bfloat16).float().numpy()
+    assert np.array_equal(synth.bf16_round(a), ref)
+    bits = synth.bf16_bits(a)
+    assert np.array_equal(bits, torch.from_numpy(a).to(torch.bfloat16).view(torch.int16).numpy()
+                          .view(np.uint16))
+
+
+@pytest.mark.parametrize("keep", [0.15, 0.5, 1.0])
+def test_synthetic_keep_rate_and_spread(keep):
+    cfg = synth.LayerConfig("probe", 1, T=512, H=512, N=32, K=8, I=64, dtype="bf16", keep=keep)
+    d = synth.make_layer(cfg, with_experts=False)
+    r = oracle.logits(d["x"], d["w_router"], d["b_router"])
+    a = oracle.logits(d["x"], d["w_mask"], d["b_mask"])
+    _, _, msk = oracle.route_mask(r, a, cfg.K)
+    rate = (msk >= 0).mean()
+    assert abs(rate - keep) < 0.03
+    if keep < 1.0:
+        per_token = (msk >= 0).sum(axis=1)
+        assert per_token.min() == 0 or keep >= 0.5
+        assert per_token.max() > per_token.min()
+
+
+def test_synthetic_zipf_skew_and_beta_keep():
+    cfg = synth.LayerConfig("probe", 2, T=1024, H=256, N=64, K=4, I=64, dtype="bf16", keep=1.0,
+                            router_skew="zipf")
+    d = synth.make_layer(cfg, with_experts=False)
+    r = oracle.logits(d["x"], d["w_router"], d["b_router"])
+    ids, _, _ = oracle.route_mask(r, np.ones_like(r), cfg.K)
+    load = np.bincount(ids.reshape(-1), minlength=cfg.N)
+    assert load.max() > 8 * np.median(load)                   # a few experts dominate
+    cfg = synth.LayerConfig("probe", 4, T=2048, H=256, N=32, K=8, I=64, dtype="bf16", keep=0.2,
+                            keep_mode="beta")
+    d = synth.make_layer(cfg, with_experts=False)
+    r = oracle.logits(d["x"], d["w_router"], d["b_router"])
+    a = oracle.logits(d["x"], d["w_mask"], d["b_mask"])
+    _, _, msk = oracle.route_mask(r, a, cfg.K)
+    per_token = (msk >= 0).sum(axis=1)
+    assert abs(per_token.mean() / cfg.K - 0.2) < 0.04        # Beta(2,8) mean
+    assert per_token.min() == 0 and per_token.max() >= 6     # heavy tail
+
+
+def test_decision_margin_flags_near_ties():
+    r = np.array([[3.0, 2.0, 2.0 - 1e-6, 0.0], [3.0, 2.0, 1.0, 0.0]], dtype=np.float32)
+    a = np.array([[1.0, 1.0, 1.0, 1.0], [1.0, 1e-7, 1.0, 1.0]], dtype=np.float32)
+    m = oracle.decision_margin(r, a, 2)
+    assert m[0] < 1e-5 and m[1] < 1e-5
+    m = oracle.decision_margin(r[1:], np.ones((1, 4), np.float32), 2)
+    assert m[0] == 1.0
