@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the binary-masked MoE layer forward (beam_moe_forward) on one
+MI355X.
+
+A step is one pass of the whole hot path -- router + mask logits, Top-K,
+binary mask, grouping by expert, gate/up GEMM + SiLU, down GEMM, masked
+aggregation -- over one batch of synthetic tokens, inputs resident in HBM.
+
+The headline workload is the Qwen3-30B-A3B-shaped decode layer (64 tokens,
+hidden 2048, 128 experts, top-8, intermediate 768, bf16, ~15% of the Top-K
+pairs kept).  Consecutive steps rotate over several copies of the expert
+weights so that no step finds its weights in the 256 MB last-level cache.
+
+Prints ONE JSON line.  `roofline` describes the dominant kernel (gate/up
+GEMM): algorithmic bytes per launch / its mean duration measured with HIP
+events on the launch stream.  `cpu_baseline` is the plain CPU oracle timed on
+the host cores.  `points` holds further workload points (decode batch sizes,
+prefill) measured the same way.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=int(os.environ.get("WORLD_SIZE", "1")))
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="qwen3_decode")
+    ap.add_argument("--tokens", type=int, default=None)
+    ap.add_argument("--keep", type=float, default=None)
+    ap.add_argument("--weight-sets", type=int, default=4)
+    ap.add_argument("--no-points", action="store_true", help="skip the extra workload points")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp):
+    """Time `steps` forwards of one workload point; returns a dict of results."""
+    import numpy as np
+    s = hp.shape_of(cfg)
+    ws, nb = hp.workspace(s)
+    out = hp.out_tensor(cfg)
+    mids = torch.empty((cfg.T, cfg.K), dtype=torch.int32, device="cuda")
+    npairs = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    stream = hp.stream_ptr()
+    nsets = len(weight_sets)
+
+    def step(i, want_ids=False):
+        wgu, wd = weight_sets[i % nsets]
+        beam.beam_moe_forward(s, g["x"], g["w_router"], g["b_router"], g["w_mask"], g["b_mask"],
+                              wgu, wd, out, None, None, mids if want_ids else None,
+                              npairs if want_ids else None, ws, nb, stream)
+
+    step(0, want_ids=True)
+    torch.cuda.synchronize()
+    m = mids.cpu().numpy()
+    P = int(npairs.item())
+    U = int(np.unique(m[m >= 0]).size)
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms = elapsed * 1e3 / steps
+
+    # per-stage durations, HIP events on the launch stream (same weight rotation)
+    nprof = max(10, min(steps, 50))
+    acc = [0.0] * beam.binding.BEAM_NUM_STAGES
+    for i in range(nprof):
+        wgu, wd = weight_sets[i % nsets]
+        _, st = beam.beam_moe_forward_timed(s, g["x"], g["w_router"], g["b_router"], g["w_mask"],
+                                            g["b_mask"], wgu, wd, out, ws, nb, stream)
+        acc = [a + b for a, b in zip(acc, st)]
+    stage_us = {n: 1e3 * a / nprof for n, a in zip(beam.binding.STAGE_NAMES, acc)}
+
+    esz = 2 if cfg.dtype == "bf16" else 4
+    H, I, N, T = cfg.H, cfg.I, cfg.N, cfg.T
+    layer_bytes = U * 6 * H * I * esz + 2 * N * H * esz + 2 * T * H * esz
+    layer_flops = P * 6 * H * I + 4 * T * H * N
+    gate_up_bytes = U * 4 * H * I * esz + T * H * esz
+    gate_up_flops = P * 4 * H * I
+    t_roof_us = max(layer_bytes / (HBM_PEAK_GBS * 1e3), layer_flops / (MFMA_BF16_PEAK_TFLOPS * 1e6))
+    return {
+        "workload": f"{cfg.name} T={T} keep={cfg.keep}", "T": T, "P": P, "U": U,
+        "us_per_layer": ms * 1e3, "tokens_per_s": T / (ms * 1e-3), "stage_us": stage_us,
+        "layer_GBs": layer_bytes / (ms * 1e-3) / 1e9,
+        "layer_TFLOPs": layer_flops / (ms * 1e-3) / 1e12,
+        "frac_hbm": layer_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "frac_mfma": layer_flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "frac_of_roofline": t_roof_us / (ms * 1e3),
+        "gate_up": {"bytes": gate_up_bytes, "flops": gate_up_flops, "us": stage_us["gate_up"]},
+        "ms_per_step": ms,
+    }
+
+
+def roofline_of(pt):
+    """Roofline record of the dominant kernel (gate/up) of a point: HBM bound
+    when its byte time exceeds its flop time at the peaks, else MFMA bound."""
+    gu = pt["gate_up"]
+    sec = gu["us"] * 1e-6
+    t_b = gu["bytes"] / (HBM_PEAK_GBS * 1e9)
+    t_f = gu["flops"] / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if t_b >= t_f:
+        a = gu["bytes"] / sec / 1e9
+        return {"bound": "hbm", "kernel": "gate_up", "achieved": a, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": a / HBM_PEAK_GBS, "traffic": None}
+    a = gu["flops"] / sec / 1e12
+    return {"bound": "mfma", "kernel": "gate_up", "achieved": a, "peak": MFMA_BF16_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": a / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the layer fits one MI355X and tokens are "
+              "independent); --gpus N with N > 1 is not supported.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2605_14438_amd as beam
+    from paper_2605_14438_amd import build as beam_build, runtime as hp, synth
+
+    if not os.path.exists(beam_build.LIB):
+        beam_build.build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    cfg = synth.CONFIGS[args.workload]
+    if args.tokens is not None:
+        cfg = cfg.with_(T=args.tokens)
+    if args.keep is not None:
+        cfg = cfg.with_(keep=args.keep)
+
+    t_gen = time.perf_counter()
+    d = synth.make_layer(cfg)
+    g = hp.upload(cfg, d)
+    sets = [(g["w_gate_up"], g["w_down"])]
+    for _ in range(max(1, args.weight_sets) - 1):
+        sets.append((g["w_gate_up"].clone(), g["w_down"].clone()))
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+
+    main_pt = measure_point(cfg, d, g, sets, args.steps, args.warmup, torch, beam, hp)
+
+    points = []
+    if not args.no_points and args.workload == "qwen3_decode":
+        psteps = max(20, args.steps // 4)
+        for T in (1, 8, 32):
+            c = cfg.with_(T=T)
+            dd = synth.make_layer(c, with_experts=False)
+            gg = {**hp.upload(c, dd), "w_gate_up": g["w_gate_up"], "w_down": g["w_down"]}
+            points.append(measure_point(c, dd, gg, sets, psteps, 10, torch, beam, hp))
+        pre = synth.CONFIGS["qwen3_prefill"]
+        for T, keep, n in ((4096, 0.15, 30), (16384, 0.15, 20), (16384, 1.0, 10)):
+            c = pre.with_(T=T, keep=keep)
+            dd = synth.make_layer(c, with_experts=False)
+            gg = {**hp.upload(c, dd), "w_gate_up": g["w_gate_up"], "w_down": g["w_down"]}
+            points.append(measure_point(c, dd, gg, sets, n, 3, torch, beam, hp))
+    for p in points:
+        p["roofline"] = roofline_of(p)
+        p.pop("gate_up")
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle      # the oracle is timed here and nowhere else in this file
+        nthreads = min(oracle.max_threads(), 16)
+        Ts = min(cfg.T, 256)
+        xs = d["x"][:Ts]
+
+        def run():
+            return oracle.moe_forward(xs, d["w_router"], d["b_router"], d["w_mask"], d["b_mask"],
+                                      d["w_gate_up"], d["w_down"], cfg.K, nthreads=nthreads)
+        run()
+        t0 = time.perf_counter()
+        reps = 0
+        while reps < 3 or (time.perf_counter() - t0 < 5.0 and reps < 50):
+            run()
+            reps += 1
+        dt = (time.perf_counter() - t0) / reps
+        cpu = {"value": Ts / dt, "unit": "tokens/s", "cores": nthreads, "kind": "oracle",
+               "sample": f"first {Ts} tokens of the step, mean of {reps} runs after 1 warm-up, "
+                         f"{dt * 1e3:.1f} ms each"}
+
+    rec = {
+        "metric": "masked_moe_layer_tokens_per_s", "value": main_pt["tokens_per_s"],
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_pt["ms_per_step"], "us_per_layer": main_pt["us_per_layer"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={cfg.T} H={cfg.H} N={cfg.N} K={cfg.K} I={cfg.I} "
+                               f"keep~{cfg.keep}", "kept_pairs": main_pt["P"],
+                   "experts_touched": main_pt["U"], "weight_sets_rotated": len(sets),
+                   "input_setup_s": round(t_gen, 1)},
+        "layer": {k: main_pt[k] for k in ("layer_GBs", "layer_TFLOPs", "frac_hbm", "frac_mfma",
+                                          "frac_of_roofline", "stage_us")},
+        "roofline": roofline_of(main_pt),
+        "cpu_baseline": cpu,
+        "points": points,
+    }
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,183 @@
+/*
+ * beam.h -- C ABI of libbeam: the binary-masked Mixture-of-Experts layer
+ * forward of BEAM (Binary Expert Activation Masking) as hand-written HIP
+ * kernels for AMD MI355X (gfx950).
+ *
+ * The layer (paper Sec. 3.2, Steps 1-4, one token x in R^H at a time):
+ *   r = x W_r                      router logits over N experts
+ *   T_K = the K largest entries of r;  g = softmax over those K        (Eq. 4)
+ *   a = x W_m ;  m_i = 1 iff sigma(a_i) >= 0.5  iff  a_i >= 0          (Eq. 5-6)
+ *   g^ = g (.) m    -- not renormalised                                (Eq. 7)
+ *   y = sum_i g^_i E_i(x),  E_i(x) = (SiLU(x W_gate) (.) (x W_up)) W_down
+ *                                                                  (Eq. 3, 8)
+ * A token may keep 0..K experts; with 0 its output row is exactly +0.
+ * Dropped (token, expert) pairs are marked with expert id -1 and never reach
+ * the expert GEMMs (paper App. A.4).
+ *
+ * Conventions for every entry point
+ *   - All pointers except the beam_shape are DEVICE pointers (HBM) unless
+ *     stated otherwise.  The caller owns every buffer, including the
+ *     workspace; the library never allocates, frees, copies to the host or
+ *     synchronises.  Work is enqueued on `hip_stream` (a hipStream_t passed
+ *     as void*; NULL = the default stream) and the call returns at once.
+ *   - Row-major, last index contiguous.  Weights are "output-feature major,
+ *     reduction dimension contiguous": the paper's x W with W stored
+ *     transposed.
+ *       x          [T, H]       dtype
+ *       w_router   [N, H]       dtype      W_r^T
+ *       w_mask     [N, H]       dtype      W_m^T
+ *       w_gate_up  [N, 2I, H]   dtype      rows 0..I-1 = W_gate^T, I..2I-1 = W_up^T
+ *       w_down     [N, H, I]    dtype      W_down^T
+ *       out        [T, H]       dtype
+ *     dtype is BEAM_F32 (4-byte IEEE) or BEAM_BF16 (2-byte bfloat16).  Logits,
+ *     routing weights and y_pairs are always fp32; indices are int32.
+ *   - Biases are optional fp32 [N] vectors added to the logits (NULL = none,
+ *     which is the paper's parametrisation).  They exist so synthetic
+ *     workloads can set a keep rate and an expert-popularity skew.
+ *   - Inputs must be finite.  Top-K order is logit descending, equal logits
+ *     by ascending expert index; slot k holds rank k+1.
+ *   - Errors are return codes only.  Argument checks happen on the host
+ *     before anything is enqueued:
+ *       BEAM_ERR_INVALID_ARG  NULL required pointer, T < 0, K < 1, K > N,
+ *                             H/N/I < 1, unknown dtype, misaligned pointer
+ *                             (16 bytes for x, weights, out, y_pairs, workspace)
+ *       BEAM_ERR_UNSUPPORTED  outside the envelope: N <= 256, K <= 64,
+ *                             H % 8 == 0, I % 8 == 0, T*K < 2^24
+ *       BEAM_ERR_WORKSPACE    workspace smaller than beam_workspace_bytes()
+ *       BEAM_ERR_HIP          a launch failed (hipGetLastError() != success)
+ *     T == 0 returns BEAM_OK without launching anything.
+ *   - Calls that share a workspace must be ordered on one stream.
+ */
+#ifndef BEAM_H
+#define BEAM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BEAM_OK = 0,
+    BEAM_ERR_INVALID_ARG = 1,
+    BEAM_ERR_UNSUPPORTED = 2,
+    BEAM_ERR_WORKSPACE = 3,
+    BEAM_ERR_HIP = 4
+} beam_status;
+
+typedef enum { BEAM_F32 = 0, BEAM_BF16 = 1 } beam_dtype;
+
+/* T tokens, H hidden size (d_h), N experts, K experts per token, I expert
+ * intermediate size; dtype of x, of every weight and of out.  Host struct. */
+typedef struct {
+    int32_t T, H, N, K, I;
+    int32_t dtype; /* beam_dtype */
+} beam_shape;
+
+/* Bytes of device workspace sufficient for any entry point at this shape
+ * (worst case: every Top-K pair kept).  Pure host function; returns 0 for an
+ * invalid or unsupported shape. */
+size_t beam_workspace_bytes(const beam_shape *shape);
+
+/* Static description of a status code (host string, never NULL). */
+const char *beam_status_string(beam_status status);
+
+/* Library ABI version (bumped when a signature changes). */
+int32_t beam_abi_version(void);
+
+/*
+ * Steps 1-3 of Sec. 3.2: router logits, Top-K + softmax (Eq. 4), mask
+ * pre-activation (Eq. 5) and binarisation (Eq. 6) written as the -1 sentinel
+ * (App. A.4).
+ *   out  topk_ids     [T,K] int32  expert of rank k+1
+ *   out  topk_weights [T,K] fp32   g over the K survivors; NOT touched by the mask
+ *   out  masked_ids   [T,K] int32  topk_ids where a >= 0, else -1
+ *   out  router_logits_dbg, mask_logits_dbg  [T,N] fp32, each may be NULL
+ * Logits are accumulated and compared in fp32 (never rounded to bf16).
+ */
+beam_status beam_route_mask(const beam_shape *shape, const void *x, const void *w_router,
+                            const float *router_bias, const void *w_mask, const float *mask_bias,
+                            int32_t *topk_ids, float *topk_weights, int32_t *masked_ids,
+                            float *router_logits_dbg, float *mask_logits_dbg, void *workspace,
+                            size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Expert-wise grouping of the kept pairs (App. A.4): a stable counting sort of
+ * the flat pair indices f = t*K + k by expert.  Any id outside [0,N) is treated
+ * as dropped.  Deterministic: placement uses prefix sums only.
+ *   in   masked_ids     [T,K]
+ *   out  expert_counts  [N]     kept pairs per expert
+ *   out  expert_offsets [N+1]   exclusive prefix sums; [N] = P
+ *   out  perm           [T*K]   perm[i] = f of grouped row i for i < P (f ascending
+ *                               inside an expert), -1 for i >= P
+ *   out  inv_perm       [T*K]   grouped row of pair f, or -1 if dropped
+ *   out  num_pairs      [1]     P (stays on the device)
+ */
+beam_status beam_permute(const beam_shape *shape, const int32_t *masked_ids, int32_t *expert_counts,
+                         int32_t *expert_offsets, int32_t *perm, int32_t *inv_perm,
+                         int32_t *num_pairs, void *workspace, size_t workspace_bytes,
+                         void *hip_stream);
+
+/*
+ * The GLU experts of Eq. 3 on the kept pairs only: for grouped row i with
+ * pair f = perm[i], token t = f / K and expert e (the segment of
+ * expert_offsets that holds i),
+ *   y_pairs[i,:] = (SiLU(x_t W_gate^e) (.) (x_t W_up^e)) W_down^e.
+ *   out  y_pairs [T*K, H] fp32; rows 0..P-1 are written, the rest untouched.
+ * bf16 shapes multiply bf16 operands on the matrix cores with fp32
+ * accumulation; the hidden activation is rounded once to bf16 between the two
+ * GEMMs.  P is read on the device; the host never learns it.
+ */
+beam_status beam_expert_ffn(const beam_shape *shape, const void *x, const void *w_gate_up,
+                            const void *w_down, const int32_t *expert_offsets, const int32_t *perm,
+                            const int32_t *num_pairs, float *y_pairs, void *workspace,
+                            size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Masked aggregation (Eq. 7-8):
+ *   out[t,:] = sum over slots k with masked_ids[t,k] >= 0, in slot order, of
+ *              topk_weights[t,k] * y_pairs[inv_perm[t*K+k], :]
+ * accumulated in fp32 and rounded once to dtype.  A token with no kept expert
+ * gets an exactly +0 row (App. A.3: the layer contributes nothing).
+ */
+beam_status beam_combine(const beam_shape *shape, const float *y_pairs, const float *topk_weights,
+                         const int32_t *masked_ids, const int32_t *inv_perm, void *out,
+                         void *hip_stream);
+
+/*
+ * The whole layer, Eq. 4-8, in one call: route + mask, group, expert FFNs on
+ * the kept pairs, combine.  Intermediates live in the workspace.  The four
+ * *_opt outputs may each be NULL: topk_ids_opt [T,K], topk_weights_opt [T,K],
+ * masked_ids_opt [T,K], num_pairs_opt [1] (device).
+ */
+beam_status beam_moe_forward(const beam_shape *shape, const void *x, const void *w_router,
+                             const float *router_bias, const void *w_mask, const float *mask_bias,
+                             const void *w_gate_up, const void *w_down, void *out,
+                             int32_t *topk_ids_opt, float *topk_weights_opt,
+                             int32_t *masked_ids_opt, int32_t *num_pairs_opt, void *workspace,
+                             size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Measurement aid, not part of the layer: beam_moe_forward with a HIP event
+ * recorded on `hip_stream` before and after every stage.  Unlike every other
+ * entry point this one creates and destroys events and WAITS for the stream;
+ * it then writes the elapsed milliseconds of the BEAM_NUM_STAGES stages to the
+ * HOST array stage_ms_host, in this order:
+ *   0 router + mask logits (Step 1-2)     1 Top-K / softmax / mask (Step 1, 3)
+ *   2 grouping by expert (App. A.4)       3 gate/up GEMM + SiLU (Eq. 3)
+ *   4 down GEMM (Eq. 3)                   5 masked aggregation (Eq. 7-8)
+ * Each figure includes that stage's launch gaps.
+ */
+#define BEAM_NUM_STAGES 6
+beam_status beam_moe_forward_timed(const beam_shape *shape, const void *x, const void *w_router,
+                                   const float *router_bias, const void *w_mask,
+                                   const float *mask_bias, const void *w_gate_up,
+                                   const void *w_down, void *out, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream,
+                                   float *stage_ms_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BEAM_H */

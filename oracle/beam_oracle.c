@@ -59,6 +59,9 @@ int beam_oracle_max_threads(void)
 void beam_oracle_logits(int T, int H, int N, const float *x, const float *w,
                         const float *bias, float *out)
 {
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) if (T >= 64)
+#endif
     for (int t = 0; t < T; ++t) {
         for (int e = 0; e < N; ++e) {
             double acc = 0.0;

@@ -1,0 +1,9 @@
+"""BEAM binary-masked MoE layer forward for MI355X (gfx950).
+
+`binding` exposes the C ABI of libbeam.so (include/beam.h) under the same
+names; `synth` draws seeded synthetic layers; `build` compiles the library.
+"""
+from . import binding, synth  # noqa: F401
+from .binding import (BEAM_BF16, BEAM_F32, BeamError, beam_abi_version, beam_combine,  # noqa: F401
+                      beam_expert_ffn, beam_moe_forward, beam_moe_forward_timed, beam_permute, beam_route_mask,
+                      beam_status_string, beam_workspace_bytes, make_shape)

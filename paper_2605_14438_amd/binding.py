@@ -1,0 +1,178 @@
+"""Thin ctypes binding of libbeam.so: same names and argument order as
+include/beam.h.  Argument marshalling only; every step of the layer runs in
+the HIP kernels.  Pointers may be given as torch tensors (their data_ptr() is
+taken; the caller keeps them alive and on the right device), as ints, or as
+None for the optional ones.
+
+There is no fallback: if the library has not been built, importing the
+functions raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbeam.so")
+
+BEAM_OK = 0
+BEAM_ERR_INVALID_ARG = 1
+BEAM_ERR_UNSUPPORTED = 2
+BEAM_ERR_WORKSPACE = 3
+BEAM_ERR_HIP = 4
+BEAM_F32 = 0
+BEAM_BF16 = 1
+
+EXPORTS = ("beam_abi_version", "beam_status_string", "beam_workspace_bytes", "beam_route_mask",
+           "beam_permute", "beam_expert_ffn", "beam_combine", "beam_moe_forward",
+           "beam_moe_forward_timed")
+BEAM_NUM_STAGES = 6
+STAGE_NAMES = ("logits", "topk_mask", "permute", "gate_up", "down", "combine")
+
+
+class beam_shape(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32),
+                ("K", ctypes.c_int32), ("I", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class BeamError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__(f"{fn}: {beam_status_string(status)} (status {status})")
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def load() -> ctypes.CDLL:
+    """dlopen the in-tree library; raises if it was never built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with "
+                "`python -m paper_2605_14438_amd.build` (there is no fallback path)")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        sp = ctypes.POINTER(beam_shape)
+        lib.beam_abi_version.restype = ctypes.c_int32
+        lib.beam_abi_version.argtypes = []
+        lib.beam_status_string.restype = ctypes.c_char_p
+        lib.beam_status_string.argtypes = [ctypes.c_int]
+        lib.beam_workspace_bytes.restype = sz
+        lib.beam_workspace_bytes.argtypes = [sp]
+        lib.beam_route_mask.restype = ctypes.c_int
+        lib.beam_route_mask.argtypes = [sp] + [vp] * 11 + [sz, vp]
+        lib.beam_permute.restype = ctypes.c_int
+        lib.beam_permute.argtypes = [sp] + [vp] * 7 + [sz, vp]
+        lib.beam_expert_ffn.restype = ctypes.c_int
+        lib.beam_expert_ffn.argtypes = [sp] + [vp] * 8 + [sz, vp]
+        lib.beam_combine.restype = ctypes.c_int
+        lib.beam_combine.argtypes = [sp] + [vp] * 6
+        lib.beam_moe_forward.restype = ctypes.c_int
+        lib.beam_moe_forward.argtypes = [sp] + [vp] * 13 + [sz, vp]
+        lib.beam_moe_forward_timed.restype = ctypes.c_int
+        lib.beam_moe_forward_timed.argtypes = [sp] + [vp] * 9 + [sz, vp,
+                                                                 ctypes.POINTER(ctypes.c_float)]
+        _lib = lib
+    return _lib
+
+
+def _p(a) -> Optional[int]:
+    if a is None:
+        return None
+    if isinstance(a, int):
+        return a
+    return a.data_ptr()
+
+
+def _shape(s) -> beam_shape:
+    if isinstance(s, beam_shape):
+        return s
+    T, H, N, K, I, dtype = s
+    return beam_shape(T, H, N, K, I, dtype)
+
+
+def make_shape(T: int, H: int, N: int, K: int, I: int, dtype: int) -> beam_shape:
+    return beam_shape(T, H, N, K, I, dtype)
+
+
+def _check(fn: str, status: int, check: bool) -> int:
+    if check and status != BEAM_OK:
+        raise BeamError(fn, status)
+    return status
+
+
+def beam_abi_version() -> int:
+    return int(load().beam_abi_version())
+
+
+def beam_status_string(status: int) -> str:
+    return load().beam_status_string(int(status)).decode()
+
+
+def beam_workspace_bytes(shape) -> int:
+    s = _shape(shape)
+    return int(load().beam_workspace_bytes(ctypes.byref(s)))
+
+
+def beam_route_mask(shape, x, w_router, router_bias, w_mask, mask_bias, topk_ids, topk_weights,
+                    masked_ids, router_logits_dbg, mask_logits_dbg, workspace, workspace_bytes,
+                    hip_stream=None, check: bool = True) -> int:
+    s = _shape(shape)
+    st = load().beam_route_mask(ctypes.byref(s), _p(x), _p(w_router), _p(router_bias), _p(w_mask),
+                                _p(mask_bias), _p(topk_ids), _p(topk_weights), _p(masked_ids),
+                                _p(router_logits_dbg), _p(mask_logits_dbg), _p(workspace),
+                                int(workspace_bytes), _p(hip_stream))
+    return _check("beam_route_mask", st, check)
+
+
+def beam_permute(shape, masked_ids, expert_counts, expert_offsets, perm, inv_perm, num_pairs,
+                 workspace, workspace_bytes, hip_stream=None, check: bool = True) -> int:
+    s = _shape(shape)
+    st = load().beam_permute(ctypes.byref(s), _p(masked_ids), _p(expert_counts),
+                             _p(expert_offsets), _p(perm), _p(inv_perm), _p(num_pairs),
+                             _p(workspace), int(workspace_bytes), _p(hip_stream))
+    return _check("beam_permute", st, check)
+
+
+def beam_expert_ffn(shape, x, w_gate_up, w_down, expert_offsets, perm, num_pairs, y_pairs,
+                    workspace, workspace_bytes, hip_stream=None, check: bool = True) -> int:
+    s = _shape(shape)
+    st = load().beam_expert_ffn(ctypes.byref(s), _p(x), _p(w_gate_up), _p(w_down),
+                                _p(expert_offsets), _p(perm), _p(num_pairs), _p(y_pairs),
+                                _p(workspace), int(workspace_bytes), _p(hip_stream))
+    return _check("beam_expert_ffn", st, check)
+
+
+def beam_combine(shape, y_pairs, topk_weights, masked_ids, inv_perm, out, hip_stream=None,
+                 check: bool = True) -> int:
+    s = _shape(shape)
+    st = load().beam_combine(ctypes.byref(s), _p(y_pairs), _p(topk_weights), _p(masked_ids),
+                             _p(inv_perm), _p(out), _p(hip_stream))
+    return _check("beam_combine", st, check)
+
+
+def beam_moe_forward(shape, x, w_router, router_bias, w_mask, mask_bias, w_gate_up, w_down, out,
+                     topk_ids_opt, topk_weights_opt, masked_ids_opt, num_pairs_opt, workspace,
+                     workspace_bytes, hip_stream=None, check: bool = True) -> int:
+    s = _shape(shape)
+    st = load().beam_moe_forward(ctypes.byref(s), _p(x), _p(w_router), _p(router_bias),
+                                 _p(w_mask), _p(mask_bias), _p(w_gate_up), _p(w_down), _p(out),
+                                 _p(topk_ids_opt), _p(topk_weights_opt), _p(masked_ids_opt),
+                                 _p(num_pairs_opt), _p(workspace), int(workspace_bytes),
+                                 _p(hip_stream))
+    return _check("beam_moe_forward", st, check)
+
+
+def beam_moe_forward_timed(shape, x, w_router, router_bias, w_mask, mask_bias, w_gate_up, w_down,
+                           out, workspace, workspace_bytes, hip_stream=None, check: bool = True):
+    """-> (status, [ms per stage]); synchronises the stream (measurement aid)."""
+    s = _shape(shape)
+    ms = (ctypes.c_float * BEAM_NUM_STAGES)()
+    st = load().beam_moe_forward_timed(ctypes.byref(s), _p(x), _p(w_router), _p(router_bias),
+                                       _p(w_mask), _p(mask_bias), _p(w_gate_up), _p(w_down),
+                                       _p(out), _p(workspace), int(workspace_bytes),
+                                       _p(hip_stream), ms)
+    return _check("beam_moe_forward_timed", st, check), [float(v) for v in ms]

@@ -1,0 +1,323 @@
+// The C ABI of libbeam (include/beam.h): argument checks on the host, the
+// workspace carve-up, and the order in which the stage kernels are enqueued.
+// Nothing here allocates, copies to the host or synchronises.
+#include "common.hpp"
+
+namespace beam {
+
+bool stream_ffn_supported(const beam_shape &s);
+bool tiled_ffn_supported(const beam_shape &s);
+hipError_t launch_gate_up_generic(const beam_shape &s, const void *x, const void *w_gate_up,
+                                  const int32_t *offsets, const int32_t *perm,
+                                  const int32_t *num_pairs, void *hidden, hipStream_t st);
+hipError_t launch_down_generic(const beam_shape &s, const void *hidden, const void *w_down,
+                               const int32_t *offsets, const int32_t *num_pairs, float *y_pairs,
+                               hipStream_t st);
+hipError_t launch_gate_up_stream(const beam_shape &s, const void *x, const void *w_gate_up,
+                                 const int32_t *offsets, const int32_t *perm, const WorkList &wl,
+                                 void *hidden, hipStream_t st);
+hipError_t launch_down_stream(const beam_shape &s, const void *hidden, const void *w_down,
+                              const int32_t *offsets, const WorkList &wl, float *y_pairs,
+                              hipStream_t st);
+hipError_t launch_gate_up_tiled(const beam_shape &s, const void *x, const void *w_gate_up,
+                                const int32_t *offsets, const int32_t *perm, const WorkList &wl,
+                                void *hidden, hipStream_t st);
+hipError_t launch_down_tiled(const beam_shape &s, const void *hidden, const void *w_down,
+                             const int32_t *offsets, const WorkList &wl, float *y_pairs,
+                             hipStream_t st);
+
+static inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+WsLayout ws_layout(const beam_shape &s) {
+    WsLayout L;
+    const size_t T = (size_t)s.T, N = (size_t)s.N, K = (size_t)s.K;
+    const size_t TK = T * K;
+    const size_t esz = s.dtype == BEAM_BF16 ? 2 : 4;
+    L.nchunk = (int)((TK + kChunk - 1) / kChunk);
+    if (L.nchunk < 1) L.nchunk = 1;
+    L.max_tiles = (int)(TK / kTileM + N);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off = align_up(off + bytes);
+        return at;
+    };
+    L.router_logits = take(T * N * 4);
+    L.mask_logits = take(T * N * 4);
+    L.topk_ids = take(TK * 4);
+    L.topk_w = take(TK * 4);
+    L.masked_ids = take(TK * 4);
+    L.blk_counts = take((size_t)L.nchunk * N * 4);
+    L.blk_base = take((size_t)L.nchunk * N * 4);
+    L.counts = take(N * 4);
+    L.offsets = take((N + 1) * 4);
+    L.num_pairs = take(4);
+    L.perm = take(TK * 4);
+    L.inv_perm = take(TK * 4);
+    L.work = take((16 + N + 2 * (size_t)L.max_tiles) * 4);
+    L.hidden = take(TK * (size_t)s.I * esz);
+    L.y_pairs = take(TK * (size_t)s.H * 4);
+    L.total = off;
+    return L;
+}
+
+WorkList work_list(void *base, const beam_shape &s, int max_tiles) {
+    WorkList wl;
+    int32_t *p = (int32_t *)base;
+    wl.hdr = p;
+    wl.active = p + 16;
+    wl.tile_expert = wl.active + s.N;
+    wl.tile_row0 = wl.tile_expert + max_tiles;
+    return wl;
+}
+
+// Row count per expert above which the tiled GEMM beats re-streaming the
+// weights once per 16 rows (worst case, every Top-K pair kept).
+static bool use_tiled(const beam_shape &s) {
+    return tiled_ffn_supported(s) && (long)s.T * s.K > 32L * s.N;
+}
+
+hipError_t launch_gate_up(const beam_shape &s, const void *x, const void *w_gate_up,
+                          const int32_t *offsets, const int32_t *perm, const int32_t *num_pairs,
+                          const WorkList &wl, void *hidden, hipStream_t st) {
+    if (use_tiled(s)) return launch_gate_up_tiled(s, x, w_gate_up, offsets, perm, wl, hidden, st);
+    if (stream_ffn_supported(s))
+        return launch_gate_up_stream(s, x, w_gate_up, offsets, perm, wl, hidden, st);
+    return launch_gate_up_generic(s, x, w_gate_up, offsets, perm, num_pairs, hidden, st);
+}
+
+hipError_t launch_down(const beam_shape &s, const void *hidden, const void *w_down,
+                       const int32_t *offsets, const int32_t *num_pairs, const WorkList &wl,
+                       float *y_pairs, hipStream_t st) {
+    if (use_tiled(s)) return launch_down_tiled(s, hidden, w_down, offsets, wl, y_pairs, st);
+    if (stream_ffn_supported(s))
+        return launch_down_stream(s, hidden, w_down, offsets, wl, y_pairs, st);
+    return launch_down_generic(s, hidden, w_down, offsets, num_pairs, y_pairs, st);
+}
+
+static beam_status check_shape(const beam_shape *s) {
+    if (!s) return BEAM_ERR_INVALID_ARG;
+    if (s->dtype != BEAM_F32 && s->dtype != BEAM_BF16) return BEAM_ERR_INVALID_ARG;
+    if (s->T < 0 || s->H < 1 || s->N < 1 || s->I < 1 || s->K < 1 || s->K > s->N)
+        return BEAM_ERR_INVALID_ARG;
+    if (s->N > 256 || s->K > 64 || s->H % 8 != 0 || s->I % 8 != 0) return BEAM_ERR_UNSUPPORTED;
+    if ((long)s->T * s->K >= (1L << 24)) return BEAM_ERR_UNSUPPORTED;
+    return BEAM_OK;
+}
+
+static inline bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
+
+static beam_status check_ws(const beam_shape &s, void *ws, size_t bytes, const WsLayout &L) {
+    (void)s;
+    if (!ws || misaligned(ws)) return BEAM_ERR_INVALID_ARG;
+    if (bytes < L.total) return BEAM_ERR_WORKSPACE;
+    return BEAM_OK;
+}
+
+}  // namespace beam
+
+using namespace beam;
+
+#define BEAM_TRY_HIP(expr)                          \
+    do {                                            \
+        if ((expr) != hipSuccess) return BEAM_ERR_HIP; \
+    } while (0)
+
+extern "C" {
+
+int32_t beam_abi_version(void) { return 1; }
+
+const char *beam_status_string(beam_status status) {
+    switch (status) {
+        case BEAM_OK: return "ok";
+        case BEAM_ERR_INVALID_ARG: return "invalid argument";
+        case BEAM_ERR_UNSUPPORTED: return "shape outside the supported envelope";
+        case BEAM_ERR_WORKSPACE: return "workspace too small";
+        case BEAM_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+size_t beam_workspace_bytes(const beam_shape *shape) {
+    if (check_shape(shape) != BEAM_OK) return 0;
+    return ws_layout(*shape).total;
+}
+
+beam_status beam_route_mask(const beam_shape *shape, const void *x, const void *w_router,
+                            const float *router_bias, const void *w_mask, const float *mask_bias,
+                            int32_t *topk_ids, float *topk_weights, int32_t *masked_ids,
+                            float *router_logits_dbg, float *mask_logits_dbg, void *workspace,
+                            size_t workspace_bytes, void *hip_stream) {
+    beam_status st = check_shape(shape);
+    if (st != BEAM_OK) return st;
+    const beam_shape &s = *shape;
+    if (!x || !w_router || !w_mask || !topk_ids || !topk_weights || !masked_ids)
+        return BEAM_ERR_INVALID_ARG;
+    if (misaligned(x) || misaligned(w_router) || misaligned(w_mask)) return BEAM_ERR_INVALID_ARG;
+    const WsLayout L = ws_layout(s);
+    st = check_ws(s, workspace, workspace_bytes, L);
+    if (st != BEAM_OK) return st;
+    if (s.T == 0) return BEAM_OK;
+    char *ws = (char *)workspace;
+    float *rl = router_logits_dbg ? router_logits_dbg : (float *)(ws + L.router_logits);
+    float *ml = mask_logits_dbg ? mask_logits_dbg : (float *)(ws + L.mask_logits);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    BEAM_TRY_HIP(launch_logits(s, x, w_router, router_bias, w_mask, mask_bias, rl, ml, stream));
+    BEAM_TRY_HIP(launch_topk_mask(s, rl, ml, topk_ids, topk_weights, masked_ids, stream));
+    return BEAM_OK;
+}
+
+beam_status beam_permute(const beam_shape *shape, const int32_t *masked_ids, int32_t *expert_counts,
+                         int32_t *expert_offsets, int32_t *perm, int32_t *inv_perm,
+                         int32_t *num_pairs, void *workspace, size_t workspace_bytes,
+                         void *hip_stream) {
+    beam_status st = check_shape(shape);
+    if (st != BEAM_OK) return st;
+    const beam_shape &s = *shape;
+    if (!masked_ids || !expert_counts || !expert_offsets || !perm || !inv_perm || !num_pairs)
+        return BEAM_ERR_INVALID_ARG;
+    const WsLayout L = ws_layout(s);
+    st = check_ws(s, workspace, workspace_bytes, L);
+    if (st != BEAM_OK) return st;
+    char *ws = (char *)workspace;
+    const WorkList wl = work_list(ws + L.work, s, L.max_tiles);
+    // T == 0 still defines the outputs: no pairs
+    BEAM_TRY_HIP(launch_permute(s, masked_ids, expert_counts, expert_offsets, perm, inv_perm,
+                                num_pairs, (int32_t *)(ws + L.blk_counts),
+                                (int32_t *)(ws + L.blk_base), L.nchunk, wl,
+                                (hipStream_t)hip_stream));
+    return BEAM_OK;
+}
+
+beam_status beam_expert_ffn(const beam_shape *shape, const void *x, const void *w_gate_up,
+                            const void *w_down, const int32_t *expert_offsets, const int32_t *perm,
+                            const int32_t *num_pairs, float *y_pairs, void *workspace,
+                            size_t workspace_bytes, void *hip_stream) {
+    beam_status st = check_shape(shape);
+    if (st != BEAM_OK) return st;
+    const beam_shape &s = *shape;
+    if (!x || !w_gate_up || !w_down || !expert_offsets || !perm || !num_pairs || !y_pairs)
+        return BEAM_ERR_INVALID_ARG;
+    if (misaligned(x) || misaligned(w_gate_up) || misaligned(w_down) || misaligned(y_pairs))
+        return BEAM_ERR_INVALID_ARG;
+    const WsLayout L = ws_layout(s);
+    st = check_ws(s, workspace, workspace_bytes, L);
+    if (st != BEAM_OK) return st;
+    if (s.T == 0) return BEAM_OK;
+    char *ws = (char *)workspace;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const WorkList wl = work_list(ws + L.work, s, L.max_tiles);
+    BEAM_TRY_HIP(launch_work_list(s, expert_offsets, wl, stream));
+    BEAM_TRY_HIP(launch_gate_up(s, x, w_gate_up, expert_offsets, perm, num_pairs, wl,
+                                ws + L.hidden, stream));
+    BEAM_TRY_HIP(launch_down(s, ws + L.hidden, w_down, expert_offsets, num_pairs, wl, y_pairs,
+                             stream));
+    return BEAM_OK;
+}
+
+beam_status beam_combine(const beam_shape *shape, const float *y_pairs, const float *topk_weights,
+                         const int32_t *masked_ids, const int32_t *inv_perm, void *out,
+                         void *hip_stream) {
+    beam_status st = check_shape(shape);
+    if (st != BEAM_OK) return st;
+    const beam_shape &s = *shape;
+    if (!y_pairs || !topk_weights || !masked_ids || !inv_perm || !out) return BEAM_ERR_INVALID_ARG;
+    if (misaligned(y_pairs) || misaligned(out)) return BEAM_ERR_INVALID_ARG;
+    if (s.T == 0) return BEAM_OK;
+    BEAM_TRY_HIP(launch_combine(s, y_pairs, topk_weights, masked_ids, inv_perm, out,
+                                (hipStream_t)hip_stream));
+    return BEAM_OK;
+}
+
+static beam_status moe_forward_impl(const beam_shape *shape, const void *x, const void *w_router,
+                                    const float *router_bias, const void *w_mask,
+                                    const float *mask_bias, const void *w_gate_up,
+                                    const void *w_down, void *out, int32_t *topk_ids_opt,
+                                    float *topk_weights_opt, int32_t *masked_ids_opt,
+                                    int32_t *num_pairs_opt, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream, hipEvent_t *ev) {
+    beam_status st = check_shape(shape);
+    if (st != BEAM_OK) return st;
+    const beam_shape &s = *shape;
+    if (!x || !w_router || !w_mask || !w_gate_up || !w_down || !out) return BEAM_ERR_INVALID_ARG;
+    if (misaligned(x) || misaligned(w_router) || misaligned(w_mask) || misaligned(w_gate_up) ||
+        misaligned(w_down) || misaligned(out))
+        return BEAM_ERR_INVALID_ARG;
+    const WsLayout L = ws_layout(s);
+    st = check_ws(s, workspace, workspace_bytes, L);
+    if (st != BEAM_OK) return st;
+    if (s.T == 0) return BEAM_OK;
+    char *ws = (char *)workspace;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    float *rl = (float *)(ws + L.router_logits);
+    float *ml = (float *)(ws + L.mask_logits);
+    int32_t *ids = topk_ids_opt ? topk_ids_opt : (int32_t *)(ws + L.topk_ids);
+    float *gw = topk_weights_opt ? topk_weights_opt : (float *)(ws + L.topk_w);
+    int32_t *mids = masked_ids_opt ? masked_ids_opt : (int32_t *)(ws + L.masked_ids);
+    int32_t *np = num_pairs_opt ? num_pairs_opt : (int32_t *)(ws + L.num_pairs);
+    int32_t *counts = (int32_t *)(ws + L.counts);
+    int32_t *offsets = (int32_t *)(ws + L.offsets);
+    int32_t *perm = (int32_t *)(ws + L.perm);
+    int32_t *inv = (int32_t *)(ws + L.inv_perm);
+    float *y_pairs = (float *)(ws + L.y_pairs);
+    const WorkList wl = work_list(ws + L.work, s, L.max_tiles);
+
+#define BEAM_STAGE_MARK(i)                                      \
+    do {                                                        \
+        if (ev) BEAM_TRY_HIP(hipEventRecord(ev[i], stream));    \
+    } while (0)
+    BEAM_STAGE_MARK(0);
+    BEAM_TRY_HIP(launch_logits(s, x, w_router, router_bias, w_mask, mask_bias, rl, ml, stream));
+    BEAM_STAGE_MARK(1);
+    BEAM_TRY_HIP(launch_topk_mask(s, rl, ml, ids, gw, mids, stream));
+    BEAM_STAGE_MARK(2);
+    BEAM_TRY_HIP(launch_permute(s, mids, counts, offsets, perm, inv, np,
+                                (int32_t *)(ws + L.blk_counts), (int32_t *)(ws + L.blk_base),
+                                L.nchunk, wl, stream));
+    BEAM_STAGE_MARK(3);
+    BEAM_TRY_HIP(launch_gate_up(s, x, w_gate_up, offsets, perm, np, wl, ws + L.hidden, stream));
+    BEAM_STAGE_MARK(4);
+    BEAM_TRY_HIP(launch_down(s, ws + L.hidden, w_down, offsets, np, wl, y_pairs, stream));
+    BEAM_STAGE_MARK(5);
+    BEAM_TRY_HIP(launch_combine(s, y_pairs, gw, mids, inv, out, stream));
+    BEAM_STAGE_MARK(6);
+#undef BEAM_STAGE_MARK
+    return BEAM_OK;
+}
+
+beam_status beam_moe_forward(const beam_shape *shape, const void *x, const void *w_router,
+                             const float *router_bias, const void *w_mask, const float *mask_bias,
+                             const void *w_gate_up, const void *w_down, void *out,
+                             int32_t *topk_ids_opt, float *topk_weights_opt,
+                             int32_t *masked_ids_opt, int32_t *num_pairs_opt, void *workspace,
+                             size_t workspace_bytes, void *hip_stream) {
+    return moe_forward_impl(shape, x, w_router, router_bias, w_mask, mask_bias, w_gate_up, w_down,
+                            out, topk_ids_opt, topk_weights_opt, masked_ids_opt, num_pairs_opt,
+                            workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+beam_status beam_moe_forward_timed(const beam_shape *shape, const void *x, const void *w_router,
+                                   const float *router_bias, const void *w_mask,
+                                   const float *mask_bias, const void *w_gate_up,
+                                   const void *w_down, void *out, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream,
+                                   float *stage_ms_host) {
+    if (!stage_ms_host) return BEAM_ERR_INVALID_ARG;
+    hipEvent_t ev[BEAM_NUM_STAGES + 1];
+    for (int i = 0; i <= BEAM_NUM_STAGES; ++i) BEAM_TRY_HIP(hipEventCreate(&ev[i]));
+    beam_status st = moe_forward_impl(shape, x, w_router, router_bias, w_mask, mask_bias,
+                                      w_gate_up, w_down, out, nullptr, nullptr, nullptr, nullptr,
+                                      workspace, workspace_bytes, hip_stream, ev);
+    if (st == BEAM_OK && shape->T > 0) {
+        if (hipEventSynchronize(ev[BEAM_NUM_STAGES]) != hipSuccess) st = BEAM_ERR_HIP;
+        for (int i = 0; st == BEAM_OK && i < BEAM_NUM_STAGES; ++i)
+            if (hipEventElapsedTime(&stage_ms_host[i], ev[i], ev[i + 1]) != hipSuccess)
+                st = BEAM_ERR_HIP;
+    } else {
+        for (int i = 0; i < BEAM_NUM_STAGES; ++i) stage_ms_host[i] = 0.0f;
+    }
+    for (int i = 0; i <= BEAM_NUM_STAGES; ++i) (void)hipEventDestroy(ev[i]);
+    return st;
+}
+
+}  // extern "C"

@@ -1,0 +1,112 @@
+// Internal declarations shared by the HIP translation units of libbeam.
+// gfx950 only: 64-wide wavefronts, bf16 MFMA with fp32 accumulation.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "beam.h"
+
+namespace beam {
+
+constexpr int kWave = 64;
+
+// Pairs handled by one workgroup of the grouping kernels (one wavefront walks
+// kGroupsPerChunk groups of 64 flat pair indices in order).
+constexpr int kGroupsPerChunk = 8;
+constexpr int kChunk = kWave * kGroupsPerChunk;
+
+// Row tile of the prefill grouped GEMM: every expert segment is cut into tiles
+// of this many grouped rows (the paper's "block alignment", App. A.4, done with
+// a tile list instead of padding the index array).
+constexpr int kTileM = 128;
+
+typedef uint16_t bf16_t;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) {
+    return __uint_as_float(((uint32_t)v) << 16);
+}
+// Round-to-nearest-even; inputs are finite.
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float load_f32(const float *p) { return *p; }
+__device__ __forceinline__ float load_f32(const bf16_t *p) { return bf16_to_f32(*p); }
+__device__ __forceinline__ void store_from_f32(float *p, float v) { *p = v; }
+__device__ __forceinline__ void store_from_f32(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+
+__device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g)); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+// Device workspace carve-up.  Every offset is a multiple of 256 bytes.
+struct WsLayout {
+    size_t router_logits;  // [T,N] f32
+    size_t mask_logits;    // [T,N] f32
+    size_t topk_ids;       // [T,K] i32
+    size_t topk_w;         // [T,K] f32
+    size_t masked_ids;     // [T,K] i32
+    size_t blk_counts;     // [nchunk,N] i32 : kept pairs per (chunk, expert)
+    size_t blk_base;       // [nchunk,N] i32 : exclusive prefix over chunks
+    size_t counts;         // [N] i32
+    size_t offsets;        // [N+1] i32
+    size_t num_pairs;      // [1] i32
+    size_t perm;           // [T*K] i32
+    size_t inv_perm;       // [T*K] i32
+    size_t work;           // work list, see WorkList
+    size_t hidden;         // [T*K, I] dtype : SiLU(gate)*up of every grouped row
+    size_t y_pairs;        // [T*K, H] f32
+    size_t total;
+    int nchunk;
+    int max_tiles;
+};
+WsLayout ws_layout(const beam_shape &s);
+
+// Work list written on the device after the prefix sums:
+//   hdr[0] = number of experts with at least one kept pair (U)
+//   hdr[1] = number of row tiles of kTileM grouped rows
+//   active[u]      expert id of the u-th non-empty expert (ascending)
+//   tile_expert[i] expert of row tile i,  tile_row0[i] its first grouped row
+struct WorkList {
+    int32_t *hdr;
+    int32_t *active;
+    int32_t *tile_expert;
+    int32_t *tile_row0;
+};
+WorkList work_list(void *base, const beam_shape &s, int max_tiles);
+
+// ---- launchers (each returns hipGetLastError() after enqueueing) ----------
+hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_router,
+                         const float *b_router, const void *w_mask, const float *b_mask,
+                         float *router_logits, float *mask_logits, hipStream_t st);
+hipError_t launch_topk_mask(const beam_shape &s, const float *router_logits,
+                            const float *mask_logits, int32_t *topk_ids, float *topk_w,
+                            int32_t *masked_ids, hipStream_t st);
+hipError_t launch_permute(const beam_shape &s, const int32_t *masked_ids, int32_t *counts,
+                          int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *num_pairs,
+                          int32_t *blk_counts, int32_t *blk_base, int nchunk, const WorkList &wl,
+                          hipStream_t st);
+hipError_t launch_work_list(const beam_shape &s, const int32_t *offsets, const WorkList &wl,
+                            hipStream_t st);
+hipError_t launch_gate_up(const beam_shape &s, const void *x, const void *w_gate_up,
+                          const int32_t *offsets, const int32_t *perm, const int32_t *num_pairs,
+                          const WorkList &wl, void *hidden, hipStream_t st);
+hipError_t launch_down(const beam_shape &s, const void *hidden, const void *w_down,
+                       const int32_t *offsets, const int32_t *num_pairs, const WorkList &wl,
+                       float *y_pairs, hipStream_t st);
+hipError_t launch_combine(const beam_shape &s, const float *y_pairs, const float *topk_w,
+                          const int32_t *masked_ids, const int32_t *inv_perm, void *out,
+                          hipStream_t st);
+
+}  // namespace beam

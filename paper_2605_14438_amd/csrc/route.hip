@@ -1,0 +1,264 @@
+// Steps 1-3 of the masked-MoE layer (paper Sec. 3.2): router logits r = x W_r,
+// mask pre-activations a = x W_m (Eq. 5), Top-K with softmax over the K
+// survivors (Eq. 4) and the binary mask a >= 0 (Eq. 6) written as the -1
+// sentinel (App. A.4).
+//
+// Both heads are one [T,H] x [H,2N] product.  Logits are accumulated in fp32
+// and stay fp32: rounding them to bf16 would change the Top-K order.
+#include "common.hpp"
+
+namespace beam {
+
+// ---------------------------------------------------------------------------
+// Logits, any dtype: one wavefront per (token, column), lanes stride over H
+// four elements at a time.  Used for fp32 inputs and for shapes the MFMA
+// kernel does not take.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void logits_generic_kernel(
+    const T *__restrict__ x, const T *__restrict__ w_router, const float *__restrict__ b_router,
+    const T *__restrict__ w_mask, const float *__restrict__ b_mask,
+    float *__restrict__ router_logits, float *__restrict__ mask_logits, int Tn, int H, int N) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x;
+    const int c = blockIdx.y * 4 + (threadIdx.x >> 6);
+    if (c >= 2 * N) return;
+    const bool is_router = c < N;
+    const int e = is_router ? c : c - N;
+    const T *xr = x + (size_t)t * H;
+    const T *wr = (is_router ? w_router : w_mask) + (size_t)e * H;
+    float acc = 0.0f;
+    for (int h = lane * 4; h < H; h += 256) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc = fmaf(load_f32(xr + h + j), load_f32(wr + h + j), acc);
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) {
+        const float *b = is_router ? b_router : b_mask;
+        if (b) acc += b[e];
+        (is_router ? router_logits : mask_logits)[(size_t)t * N + e] = acc;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Logits, bf16 on the matrix cores.  v_mfma_f32_16x16x32_bf16: A = 16 tokens
+// x 32 k, B = 32 k x 16 logit columns, D = 16x16 fp32.  Operands go straight
+// from global memory into the MFMA registers: lane l owns row/column (l & 15)
+// and the 8 reduction indices 8*(l >> 4).. of every 32-wide MFMA step (one
+// 16-byte load; the four lanes of a row read 64 contiguous bytes).
+//
+// A workgroup is 4 wavefronts.  KSPLIT of them share one output tile and split
+// the reduction (decode: few tokens, latency matters); the others tile the
+// columns.  MT x NT MFMA tiles per wavefront.
+// ---------------------------------------------------------------------------
+template <int MT, int NT, int KSPLIT>
+__global__ __launch_bounds__(256) void logits_mfma_kernel(
+    const bf16_t *__restrict__ x, const bf16_t *__restrict__ w_router,
+    const float *__restrict__ b_router, const bf16_t *__restrict__ w_mask,
+    const float *__restrict__ b_mask, float *__restrict__ router_logits,
+    float *__restrict__ mask_logits, int Tn, int H, int N) {
+    constexpr int WAVES_N = 4 / KSPLIT;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int wn = wave % WAVES_N;
+    const int ks = wave / WAVES_N;
+    const int l16 = lane & 15;
+    const int g = lane >> 4;
+    const int t0 = blockIdx.x * (MT * 16);
+    const int c0 = blockIdx.y * (WAVES_N * NT * 16) + wn * (NT * 16);
+    const int klen = H / KSPLIT;
+    const int kbeg = ks * klen + g * 8;
+
+    const bf16_t *arow[MT];
+    const bf16_t *brow[NT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        int t = t0 + m * 16 + l16;
+        t = t < Tn ? t : Tn - 1;
+        arow[m] = x + (size_t)t * H + kbeg;
+    }
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+        int c = c0 + n * 16 + l16;
+        c = c < 2 * N ? c : 2 * N - 1;
+        brow[n] = (c < N ? w_router + (size_t)c * H : w_mask + (size_t)(c - N) * H) + kbeg;
+    }
+
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int n = 0; n < NT; ++n) acc[m][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int k = 0; k < klen; k += 128) {
+        uint4 a[MT][4], b[NT][4];
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a[m][j] = *(const uint4 *)(arow[m] + k + j * 32);
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[n][j] = *(const uint4 *)(brow[n] + k + j * 32);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int n = 0; n < NT; ++n)
+                    acc[m][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8, a[m][j]), __builtin_bit_cast(bf16x8, b[n][j]),
+                        acc[m][n], 0, 0, 0);
+    }
+
+    if constexpr (KSPLIT > 1) {
+        __shared__ float red[KSPLIT - 1][WAVES_N][MT * NT * 4][64];
+        if (ks > 0) {
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int n = 0; n < NT; ++n)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        red[ks - 1][wn][(m * NT + n) * 4 + r][lane] = acc[m][n][r];
+        }
+        __syncthreads();
+        if (ks > 0) return;
+#pragma unroll
+        for (int s = 0; s < KSPLIT - 1; ++s)
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int n = 0; n < NT; ++n)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        acc[m][n][r] += red[s][wn][(m * NT + n) * 4 + r][lane];
+    }
+
+    // D layout: lane l, register r -> token row 4*(l>>4)+r, column l&15.
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+        const int c = c0 + n * 16 + l16;
+        if (c >= 2 * N) continue;
+        const bool is_router = c < N;
+        const int e = is_router ? c : c - N;
+        const float *bp = is_router ? b_router : b_mask;
+        const float bias = bp ? bp[e] : 0.0f;
+        float *dst = is_router ? router_logits : mask_logits;
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int t = t0 + m * 16 + g * 4 + r;
+                if (t < Tn) dst[(size_t)t * N + e] = acc[m][n][r] + bias;
+            }
+    }
+}
+
+hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_router,
+                         const float *b_router, const void *w_mask, const float *b_mask,
+                         float *router_logits, float *mask_logits, hipStream_t st) {
+    const int T = s.T, H = s.H, N = s.N;
+    if (s.dtype == BEAM_BF16 && H % 128 == 0) {
+        const bf16_t *xb = (const bf16_t *)x;
+        const bf16_t *wr = (const bf16_t *)w_router;
+        const bf16_t *wm = (const bf16_t *)w_mask;
+        if (T <= 512 && H % 512 == 0) {
+            dim3 grid((T + 15) / 16, (2 * N + 15) / 16);
+            logits_mfma_kernel<1, 1, 4><<<grid, 256, 0, st>>>(xb, wr, b_router, wm, b_mask,
+                                                              router_logits, mask_logits, T, H, N);
+        } else {
+            dim3 grid((T + 31) / 32, (2 * N + 255) / 256);
+            logits_mfma_kernel<2, 4, 1><<<grid, 256, 0, st>>>(xb, wr, b_router, wm, b_mask,
+                                                              router_logits, mask_logits, T, H, N);
+        }
+    } else {
+        dim3 grid(T, (2 * N + 3) / 4);
+        if (s.dtype == BEAM_BF16)
+            logits_generic_kernel<bf16_t><<<grid, 256, 0, st>>>(
+                (const bf16_t *)x, (const bf16_t *)w_router, b_router, (const bf16_t *)w_mask,
+                b_mask, router_logits, mask_logits, T, H, N);
+        else
+            logits_generic_kernel<float><<<grid, 256, 0, st>>>(
+                (const float *)x, (const float *)w_router, b_router, (const float *)w_mask, b_mask,
+                router_logits, mask_logits, T, H, N);
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Top-K, softmax over the K survivors, binary mask.  One wavefront per token;
+// lane l holds logits l, l+64, l+128, l+192 (N <= 256).  K rounds of a
+// wave-wide arg-max under the total order (logit descending, expert index
+// ascending); after round k lane k keeps the winner, so slot k = rank k+1.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void topk_mask_kernel(
+    const float *__restrict__ router_logits, const float *__restrict__ mask_logits,
+    int32_t *__restrict__ topk_ids, float *__restrict__ topk_w, int32_t *__restrict__ masked_ids,
+    int Tn, int N, int K) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= Tn) return;  // wave-uniform
+    const float *r = router_logits + (size_t)t * N;
+    constexpr int kNone = 0x7fffffff;
+    float v[4];
+    unsigned avail = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e = lane + 64 * i;
+        v[i] = 0.0f;
+        if (e < N) {
+            v[i] = r[e];
+            avail |= 1u << i;
+        }
+    }
+    int my_id = 0;
+    float my_r = 0.0f;
+    for (int k = 0; k < K; ++k) {
+        float bv = 0.0f;
+        int bi = kNone;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (((avail >> i) & 1u) && (bi == kNone || v[i] > bv)) {
+                bv = v[i];
+                bi = lane + 64 * i;
+            }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float ov = __shfl_xor(bv, off);
+            const int oi = __shfl_xor(bi, off);
+            const bool take = (oi != kNone) && (bi == kNone || ov > bv || (ov == bv && oi < bi));
+            if (take) {
+                bv = ov;
+                bi = oi;
+            }
+        }
+        if ((bi & 63) == lane) avail &= ~(1u << (bi >> 6));
+        if (lane == k) {
+            my_id = bi;
+            my_r = bv;
+        }
+    }
+    const float top = __shfl(my_r, 0);
+    const float ex = lane < K ? expf(my_r - top) : 0.0f;
+    const float denom = wave_sum(ex);
+    if (lane < K) {
+        const float a = mask_logits[(size_t)t * N + my_id];
+        const size_t f = (size_t)t * K + lane;
+        topk_ids[f] = my_id;
+        topk_w[f] = ex / denom;
+        masked_ids[f] = (a >= 0.0f) ? my_id : -1;
+    }
+}
+
+hipError_t launch_topk_mask(const beam_shape &s, const float *router_logits,
+                            const float *mask_logits, int32_t *topk_ids, float *topk_w,
+                            int32_t *masked_ids, hipStream_t st) {
+    dim3 grid((s.T + 3) / 4);
+    topk_mask_kernel<<<grid, 256, 0, st>>>(router_logits, mask_logits, topk_ids, topk_w,
+                                           masked_ids, s.T, s.N, s.K);
+    return hipGetLastError();
+}
+
+}  // namespace beam

@@ -1,0 +1,85 @@
+"""Shared plumbing of the GPU parity tests: upload of synthetic layers, the
+guard-band redraw that makes index comparisons well posed, and the output
+tolerance.  Uses the oracle (test infrastructure) and the binding; no method
+arithmetic of its own."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+import paper_2605_14438_amd as beam
+from paper_2605_14438_amd import synth
+from paper_2605_14438_amd.runtime import (dev, dev_f32, out_tensor, shape_of, stream_ptr,  # noqa: F401
+                                         upload, workspace)
+
+# Any routing / mask decision closer than this (in logit units) could flip
+# under a different fp32 summation order; such tokens are redrawn.  fp32
+# accumulation noise at H = 4096 is ~1e-6, so 1e-4 is a wide band.
+GUARD = 1e-4
+
+
+def gpu_available() -> bool:
+    return torch.cuda.is_available()
+
+
+def oracle_logits(d):
+    r = oracle.logits(d["x"], d["w_router"], d["b_router"])
+    a = oracle.logits(d["x"], d["w_mask"], d["b_mask"])
+    return r, a
+
+
+def make_tie_free(cfg, sweep: int = 0, with_experts: bool = True, max_rounds: int = 8):
+    """Draw a layer and redraw every hidden row whose decisions sit inside the
+    guard band, so that indices can be demanded bit-exact on ALL tokens."""
+    d = synth.make_layer(cfg, sweep=sweep, with_experts=with_experts)
+    r, a = oracle_logits(d)
+    for attempt in range(1, max_rounds + 1):
+        bad = np.flatnonzero(oracle.decision_margin(r, a, cfg.K) < GUARD)
+        if bad.size == 0:
+            break
+        synth.redraw_rows(cfg, d, bad, sweep=sweep, attempt=attempt)
+        sub = {**d, "x": d["x"][bad]}
+        rb, ab = oracle_logits(sub)
+        r[bad], a[bad] = rb, ab
+    else:
+        raise AssertionError("guard-band redraw did not converge")
+    d["router_logits"], d["mask_logits"] = r, a
+    return d
+
+
+def forward(cfg, g, T=None):
+    """beam_moe_forward with all optional outputs; returns host arrays."""
+    T = cfg.T if T is None else T
+    s = shape_of(cfg, T)
+    ws, nb = workspace(s)
+    out = out_tensor(cfg, T)
+    ids = torch.full((T, cfg.K), -7, dtype=torch.int32, device="cuda")
+    gw = torch.full((T, cfg.K), float("nan"), dtype=torch.float32, device="cuda")
+    mids = torch.full((T, cfg.K), -7, dtype=torch.int32, device="cuda")
+    npairs = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    beam.beam_moe_forward(s, g["x"], g["w_router"], g["b_router"], g["w_mask"], g["b_mask"],
+                          g["w_gate_up"], g["w_down"], out, ids, gw, mids, npairs, ws, nb,
+                          stream_ptr())
+    torch.cuda.synchronize()
+    return {"out": out.float().cpu().numpy().astype(np.float64), "out_raw": out,
+            "topk_ids": ids.cpu().numpy(), "topk_weights": gw.cpu().numpy(),
+            "masked_ids": mids.cpu().numpy(), "num_pairs": int(npairs.item())}
+
+
+def output_error(got, ref, dtype: str):
+    """Return (literal metric, worst ratio to the element-wise bound).
+
+    literal metric: max|got-ref| / RMS(ref over all T*H elements).
+    bound, bf16:  |got-ref| <= 2e-2*RMS + 2^-8*|ref|  (the stated budget plus the
+                  half-ulp no bf16 output can avoid);  fp32: 1e-4*RMS."""
+    rms = float(np.sqrt(np.mean(ref ** 2)))
+    err = np.abs(got - ref)
+    if rms == 0.0:
+        return float(err.max()), (0.0 if err.max() == 0 else np.inf)
+    literal = float(err.max() / rms)
+    if dtype == "bf16":
+        bound = 2e-2 * rms + 2.0 ** -8 * np.abs(ref)
+    else:
+        bound = np.full_like(ref, 1e-4 * rms)
+    return literal, float((err / bound).max())

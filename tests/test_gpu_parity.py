@@ -1,0 +1,294 @@
+"""GPU parity: every entry point of libbeam, called through the C ABI, against
+the CPU oracle on the same seeded inputs.  Indices must match bit for bit;
+floating-point outputs within the stated tolerances."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_14438_amd as beam
+from paper_2605_14438_amd import synth
+
+import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+CFG = synth.CONFIGS
+SMALL_BF16 = synth.LayerConfig("small_bf16", 1, T=40, H=512, N=32, K=4, I=256, dtype="bf16",
+                               keep=0.4)
+ODD_BF16 = synth.LayerConfig("odd_bf16", 1, T=21, H=320, N=60, K=4, I=136, dtype="bf16",
+                             keep=0.5)            # N, H, I outside every MFMA envelope
+PREFILL_SMALL = synth.LayerConfig("prefill_small", 2, T=700, H=512, N=16, K=4, I=256,
+                                  dtype="bf16", keep=0.5, router_skew="zipf")
+
+
+def _log(msg):
+    print(msg, flush=True)
+
+
+# ---------------------------------------------------------------------------
+# beam_route_mask
+# ---------------------------------------------------------------------------
+ROUTE_CASES = [
+    CFG["tiny"], CFG["tiny"].with_(T=1), SMALL_BF16, ODD_BF16,
+    CFG["qwen3_decode"].with_(T=1), CFG["qwen3_decode"].with_(T=8),
+    CFG["qwen3_decode"].with_(T=37), CFG["qwen3_decode"].with_(T=64),
+    CFG["qwen3_prefill"].with_(T=1500),          # large-T logits kernel, ragged tail
+    synth.LayerConfig("mixtral_router", 3, T=33, H=4096, N=8, K=2, I=64, dtype="bf16", keep=0.6),
+]
+
+
+@pytest.mark.parametrize("cfg", ROUTE_CASES, ids=lambda c: f"{c.name}-T{c.T}")
+def test_route_mask(cfg):
+    _log(f"route_mask {cfg}")
+    d = hp.make_tie_free(cfg, with_experts=False)
+    ids_o, g_o, msk_o = oracle.route_mask(d["router_logits"], d["mask_logits"], cfg.K)
+    g = hp.upload(cfg, d)
+    s = hp.shape_of(cfg)
+    ws, nb = hp.workspace(s)
+    T, K, N = cfg.T, cfg.K, cfg.N
+    ids = torch.full((T, K), -7, dtype=torch.int32, device="cuda")
+    gw = torch.zeros((T, K), dtype=torch.float32, device="cuda")
+    mids = torch.full((T, K), -7, dtype=torch.int32, device="cuda")
+    rl = torch.zeros((T, N), dtype=torch.float32, device="cuda")
+    ml = torch.zeros((T, N), dtype=torch.float32, device="cuda")
+    beam.beam_route_mask(s, g["x"], g["w_router"], g["b_router"], g["w_mask"], g["b_mask"], ids,
+                         gw, mids, rl, ml, ws, nb, hp.stream_ptr())
+    torch.cuda.synchronize()
+    # logits: fp32 accumulation of exact products
+    assert np.abs(rl.cpu().numpy() - d["router_logits"]).max() < 2e-5
+    assert np.abs(ml.cpu().numpy() - d["mask_logits"]).max() < 2e-5 + 1e-6 * abs(
+        synth.mask_bias_value(cfg))
+    assert np.array_equal(ids.cpu().numpy(), ids_o)
+    assert np.array_equal(mids.cpu().numpy(), msk_o)
+    np.testing.assert_allclose(gw.cpu().numpy(), g_o, atol=2e-6, rtol=0)
+    # same call without debug outputs gives the same indices
+    ids2 = torch.empty_like(ids)
+    mids2 = torch.empty_like(mids)
+    beam.beam_route_mask(s, g["x"], g["w_router"], g["b_router"], g["w_mask"], g["b_mask"], ids2,
+                         gw, mids2, None, None, ws, nb, hp.stream_ptr())
+    torch.cuda.synchronize()
+    assert torch.equal(ids, ids2) and torch.equal(mids, mids2)
+
+
+def test_route_mask_integer_logic_without_guard_band():
+    """No input filtering: feed the GPU's own fp32 logits through the oracle's
+    select / softmax / mask and demand identical indices (ties included)."""
+    cfg = CFG["qwen3_prefill"].with_(T=3000)
+    d = synth.make_layer(cfg, with_experts=False)
+    # plant exact ties and exact zeros: duplicate router rows, zero mask rows
+    d["w_router"][5] = d["w_router"][4]
+    d["w_router"][77] = d["w_router"][4]
+    d["b_router"][[4, 5, 77]] = d["b_router"][4]
+    d["w_mask"][9] = 0.0
+    d["b_mask"][9] = 0.0
+    g = hp.upload(cfg, d)
+    s = hp.shape_of(cfg)
+    ws, nb = hp.workspace(s)
+    T, K, N = cfg.T, cfg.K, cfg.N
+    ids = torch.empty((T, K), dtype=torch.int32, device="cuda")
+    gw = torch.empty((T, K), dtype=torch.float32, device="cuda")
+    mids = torch.empty((T, K), dtype=torch.int32, device="cuda")
+    rl = torch.empty((T, N), dtype=torch.float32, device="cuda")
+    ml = torch.empty((T, N), dtype=torch.float32, device="cuda")
+    beam.beam_route_mask(s, g["x"], g["w_router"], g["b_router"], g["w_mask"], g["b_mask"], ids,
+                         gw, mids, rl, ml, ws, nb, hp.stream_ptr())
+    torch.cuda.synchronize()
+    rl_h, ml_h = rl.cpu().numpy(), ml.cpu().numpy()
+    assert (rl_h[:, 4] == rl_h[:, 5]).all() and (ml_h[:, 9] == 0).all()
+    ids_o, g_o, msk_o = oracle.route_mask(rl_h, ml_h, K)
+    assert np.array_equal(ids.cpu().numpy(), ids_o)
+    assert np.array_equal(mids.cpu().numpy(), msk_o)
+    np.testing.assert_allclose(gw.cpu().numpy(), g_o, atol=2e-6, rtol=0)
+    # expert 9 has a == 0 everywhere: kept whenever selected (Eq. 6 uses >=)
+    sel9 = ids_o == 9
+    assert sel9.any() and (msk_o[sel9] == 9).all()
+
+
+# ---------------------------------------------------------------------------
+# beam_permute
+# ---------------------------------------------------------------------------
+def _run_permute(m_host, N, K):
+    T = m_host.shape[0]
+    s = beam.make_shape(T, 512, N, K, 256, beam.BEAM_BF16)
+    ws, nb = hp.workspace(s)
+    TK = T * K
+    m = torch.from_numpy(m_host).cuda()
+    counts = torch.full((N,), -7, dtype=torch.int32, device="cuda")
+    offsets = torch.full((N + 1,), -7, dtype=torch.int32, device="cuda")
+    perm = torch.full((max(TK, 1),), -7, dtype=torch.int32, device="cuda")
+    inv = torch.full((max(TK, 1),), -7, dtype=torch.int32, device="cuda")
+    P = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    beam.beam_permute(s, m, counts, offsets, perm, inv, P, ws, nb, hp.stream_ptr())
+    torch.cuda.synchronize()
+    return (counts.cpu().numpy(), offsets.cpu().numpy(), perm.cpu().numpy()[:TK],
+            inv.cpu().numpy()[:TK], int(P.item()))
+
+
+@pytest.mark.parametrize("T,K,N,keep", [
+    (1, 8, 128, 0.15), (8, 8, 128, 0.15), (64, 8, 128, 0.15), (64, 8, 128, 1.0),
+    (65, 8, 128, 0.5), (8, 1, 8, 0.6), (63, 2, 8, 0.5), (257, 2, 8, 0.5), (1000, 8, 128, 0.15),
+    (4096, 8, 128, 0.25), (16384, 8, 128, 1.0), (16384, 8, 128, 0.15), (300, 4, 60, 0.0),
+    (777, 6, 256, 0.7),
+])
+def test_permute(T, K, N, keep):
+    _log(f"permute T={T} K={K} N={N} keep={keep}")
+    rng = np.random.default_rng(T * 131 + K * 7 + N)
+    # skewed expert popularity, like routed ids
+    pop = 1.0 / np.arange(1, N + 1) ** 1.1
+    m = rng.choice(N, size=(T, K), p=pop / pop.sum()).astype(np.int32)
+    m[rng.random((T, K)) >= keep] = -1
+    if T >= 63:
+        m[3, 0] = N + 5      # out-of-range ids count as dropped
+        m[7, K - 1] = -9
+    ref = oracle.permute(m, N)
+    got = _run_permute(m, N, K)
+    for name, a, b in zip(("counts", "offsets", "perm", "inv_perm"), got[:4], ref[:4]):
+        assert np.array_equal(a, b), name
+    assert got[4] == ref[4]
+    again = _run_permute(m, N, K)
+    for a, b in zip(got[:4], again[:4]):
+        assert np.array_equal(a, b)      # deterministic
+
+
+def test_permute_single_expert_takes_everything():
+    m = np.full((700, 4), 3, dtype=np.int32)
+    ref = oracle.permute(m, 16)
+    got = _run_permute(m, 16, 4)
+    for a, b in zip(got[:4], ref[:4]):
+        assert np.array_equal(a, b)
+    assert got[4] == 2800 and np.array_equal(got[2], np.arange(2800))
+
+
+# ---------------------------------------------------------------------------
+# beam_expert_ffn and beam_combine (stage by stage, oracle indices as input)
+# ---------------------------------------------------------------------------
+FFN_CASES = [
+    CFG["tiny"],                                     # fp32 generic kernels
+    SMALL_BF16,                                      # weight-streaming MFMA kernels
+    ODD_BF16,                                        # bf16 generic kernels
+    SMALL_BF16.with_(T=200, keep=1.0),               # streaming with > 16 rows per expert
+    PREFILL_SMALL,                                   # tiled grouped GEMM, ragged tiles
+    PREFILL_SMALL.with_(T=1100, keep=1.0),
+]
+
+
+@pytest.mark.parametrize("cfg", FFN_CASES, ids=lambda c: f"{c.name}-T{c.T}-keep{c.keep}")
+def test_expert_ffn_and_combine(cfg):
+    _log(f"expert_ffn {cfg}")
+    d = hp.make_tie_free(cfg)
+    ids_o, g_o, msk_o = oracle.route_mask(d["router_logits"], d["mask_logits"], cfg.K)
+    counts, offsets, perm, inv, P = oracle.permute(msk_o, cfg.N)
+    y_slots, evals = oracle.pair_outputs(d["x"], d["w_gate_up"], d["w_down"], msk_o)
+    assert evals == P
+    g = hp.upload(cfg, d)
+    s = hp.shape_of(cfg)
+    ws, nb = hp.workspace(s)
+    TK = cfg.T * cfg.K
+    y_pairs = torch.full((TK, cfg.H), float("nan"), dtype=torch.float32, device="cuda")
+    off_d = torch.from_numpy(offsets).cuda()
+    perm_d = torch.from_numpy(perm).cuda()
+    inv_d = torch.from_numpy(inv).cuda()
+    P_d = torch.tensor([P], dtype=torch.int32, device="cuda")
+    beam.beam_expert_ffn(s, g["x"], g["w_gate_up"], g["w_down"], off_d, perm_d, P_d, y_pairs, ws,
+                         nb, hp.stream_ptr())
+    torch.cuda.synchronize()
+    y_h = y_pairs.cpu().numpy().astype(np.float64)
+    assert np.isnan(y_h[P:]).all()                    # rows >= P untouched
+    ref_rows = y_slots[perm[:P]]                      # grouped order
+    rms = np.sqrt(np.mean(ref_rows ** 2))
+    err = np.abs(y_h[:P] - ref_rows).max() / rms
+    _log(f"  P={P} y_pairs max err / rms = {err:.3e}")
+    assert err < (1e-5 if cfg.dtype == "f32" else 1.5e-2)
+
+    # combine on the GPU's y_pairs vs fp64 sum of the same rows
+    out = hp.out_tensor(cfg)
+    beam.beam_combine(s, y_pairs, torch.from_numpy(g_o.astype(np.float32)).cuda(),
+                      torch.from_numpy(msk_o).cuda(), inv_d, out, hp.stream_ptr())
+    torch.cuda.synchronize()
+    want = np.zeros((cfg.T, cfg.H))
+    gw32 = g_o.astype(np.float32).astype(np.float64)
+    for k in range(cfg.K):
+        kept = msk_o[:, k] >= 0
+        rows = inv[np.arange(cfg.T) * cfg.K + k]
+        want[kept] += gw32[kept, k, None] * y_h[rows[kept]]
+    got = out.float().cpu().numpy().astype(np.float64)
+    if cfg.dtype == "f32":
+        assert np.abs(got - want).max() <= 1e-6 * np.abs(want).max()
+    else:
+        assert (np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-6 * np.abs(want).max()).all()
+    zero_rows = (msk_o < 0).all(axis=1)
+    raw = out[torch.from_numpy(zero_rows).cuda()]
+    assert (raw.view(torch.int16 if cfg.dtype == "bf16" else torch.int32) == 0).all()  # +0 bits
+
+
+# ---------------------------------------------------------------------------
+# beam_moe_forward, whole layer
+# ---------------------------------------------------------------------------
+def _check_forward(cfg, d, res, ref, token_subset=None):
+    assert np.array_equal(res["topk_ids"], ref["topk_ids"])
+    assert np.array_equal(res["masked_ids"], ref["masked_ids"])
+    np.testing.assert_allclose(res["topk_weights"], ref["topk_weights"], atol=2e-6, rtol=0)
+    assert res["num_pairs"] == int((ref["masked_ids"] >= 0).sum())
+    got = res["out"] if token_subset is None else res["out"][token_subset]
+    literal, ratio = hp.output_error(got, ref["out"], cfg.dtype)
+    floor, _ = hp.output_error(synth.bf16_round(ref["out"].astype(np.float32)).astype(np.float64),
+                               ref["out"], cfg.dtype)
+    _log(f"  {cfg.name} T={cfg.T} keep={cfg.keep}: P={res['num_pairs']} max|err|/RMS={literal:.4f} "
+         f"(bf16 floor {floor:.4f}) worst/bound={ratio:.3f}")
+    assert ratio <= 1.0
+    zero_rows = (ref["masked_ids"] >= 0).sum(axis=1) == 0
+    if token_subset is None and zero_rows.any():
+        raw = res["out_raw"][torch.from_numpy(zero_rows).cuda()]
+        assert (raw.view(torch.int16 if cfg.dtype == "bf16" else torch.int32) == 0).all()
+    return literal, ratio
+
+
+FWD_CASES = [
+    CFG["tiny"], CFG["tiny"].with_(T=1), CFG["tiny"].with_(T=130, keep=1.0), SMALL_BF16, ODD_BF16,
+    SMALL_BF16.with_(keep=0.0), SMALL_BF16.with_(keep=1.0),
+    PREFILL_SMALL, PREFILL_SMALL.with_(T=1100, keep=1.0),
+]
+
+
+@pytest.mark.parametrize("cfg", FWD_CASES, ids=lambda c: f"{c.name}-T{c.T}-keep{c.keep}")
+def test_moe_forward_small(cfg):
+    _log(f"moe_forward {cfg}")
+    d = hp.make_tie_free(cfg)
+    ref = oracle.moe_forward(d["x"], d["w_router"], d["b_router"], d["w_mask"], d["b_mask"],
+                             d["w_gate_up"], d["w_down"], cfg.K)
+    res = hp.forward(cfg, hp.upload(cfg, d))
+    _check_forward(cfg, d, res, ref)
+    if cfg.keep == 0.0:
+        assert res["num_pairs"] == 0 and (res["out"] == 0).all()
+
+
+def test_moe_forward_all_ones_mask_is_topk_moe():
+    """Zero-initialised mask router (Sec. 3.3.1): every Top-K pair kept."""
+    cfg = SMALL_BF16
+    d = hp.make_tie_free(cfg.with_(keep=1.0))
+    d["w_mask"][:] = 0.0
+    d["b_mask"] = None
+    ref = oracle.moe_forward(d["x"], d["w_router"], None, d["w_mask"], None, d["w_gate_up"],
+                             d["w_down"], cfg.K)
+    res = hp.forward(cfg, hp.upload(cfg, d))
+    assert np.array_equal(res["masked_ids"], res["topk_ids"])
+    assert res["num_pairs"] == cfg.T * cfg.K
+    _check_forward(cfg, d, res, ref)
+
+
+@pytest.mark.parametrize("T", [1, 8, 32, 64])
+def test_moe_forward_qwen3_decode_full_size(T):
+    cfg = CFG["qwen3_decode"].with_(T=T)
+    _log(f"moe_forward full size {cfg}")
+    d = hp.make_tie_free(cfg)
+    ref = oracle.moe_forward(d["x"], d["w_router"], d["b_router"], d["w_mask"], d["b_mask"],
+                             d["w_gate_up"], d["w_down"], cfg.K)
+    res = hp.forward(cfg, hp.upload(cfg, d))
+    _check_forward(cfg, d, res, ref)
+    if T == 64:
+        per_token = (ref["masked_ids"] >= 0).sum(axis=1)
+        assert per_token.min() == 0 and per_token.max() >= 3
+        # run it again into the same buffers: identical bits
+        res2 = hp.forward(cfg, hp.upload(cfg, d))
+        assert torch.equal(res["out_raw"], res2["out_raw"])
