@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--weight-sets", type=int, default=4)
     ap.add_argument("--no-points", action="store_true", help="skip the extra workload points")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
+                    help="also run a plain device copy of this many MiB a few times (a kernel of "
+                         "known traffic, to calibrate rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -89,9 +92,11 @@ def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp):
 
     esz = 2 if cfg.dtype == "bf16" else 4
     H, I, N, T = cfg.H, cfg.I, cfg.N, cfg.T
-    layer_bytes = U * 6 * H * I * esz + 2 * N * H * esz + 2 * T * H * esz
+    # algorithmic traffic: each touched expert's weights once (3*H*I elements:
+    # 2I x H gate/up + H x I down), both routing heads, x in, out out
+    layer_bytes = U * 3 * H * I * esz + 2 * N * H * esz + 2 * T * H * esz
     layer_flops = P * 6 * H * I + 4 * T * H * N
-    gate_up_bytes = U * 4 * H * I * esz + T * H * esz
+    gate_up_bytes = U * 2 * H * I * esz + T * H * esz
     gate_up_flops = P * 4 * H * I
     t_roof_us = max(layer_bytes / (HBM_PEAK_GBS * 1e3), layer_flops / (MFMA_BF16_PEAK_TFLOPS * 1e6))
     return {
@@ -154,6 +159,14 @@ def main():
         sets.append((g["w_gate_up"].clone(), g["w_down"].clone()))
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
+
+    if args.copy_probe > 0:
+        src = torch.empty(args.copy_probe << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     main_pt = measure_point(cfg, d, g, sets, args.steps, args.warmup, torch, beam, hp)
 
