@@ -54,7 +54,7 @@ WsLayout ws_layout(const beam_shape &s) {
     L.num_pairs = take(4);
     L.perm = take(TK * 4);
     L.inv_perm = take(TK * 4);
-    L.work = take((16 + N + 2 * (size_t)L.max_tiles) * 4);
+    L.work = take((16 + 3 * N + 2 * (size_t)L.max_tiles) * 4);
     L.hidden = take(TK * (size_t)s.I * esz);
     L.y_pairs = take(TK * (size_t)s.H * 4);
     L.total = off;
@@ -66,7 +66,9 @@ WorkList work_list(void *base, const beam_shape &s, int max_tiles) {
     int32_t *p = (int32_t *)base;
     wl.hdr = p;
     wl.active = p + 16;
-    wl.tile_expert = wl.active + s.N;
+    wl.active_beg = wl.active + s.N;
+    wl.active_end = wl.active_beg + s.N;
+    wl.tile_expert = wl.active_end + s.N;
     wl.tile_row0 = wl.tile_expert + max_tiles;
     return wl;
 }

@@ -77,10 +77,15 @@ WsLayout ws_layout(const beam_shape &s);
 //   hdr[0] = number of experts with at least one kept pair (U)
 //   hdr[1] = number of row tiles of kTileM grouped rows
 //   active[u]      expert id of the u-th non-empty expert (ascending)
+//   active_beg[u], active_end[u]  its grouped rows [beg, end)
 //   tile_expert[i] expert of row tile i,  tile_row0[i] its first grouped row
+// A workgroup that serves active expert u fetches all four words in one round
+// trip instead of chasing hdr -> active -> offsets.
 struct WorkList {
     int32_t *hdr;
     int32_t *active;
+    int32_t *active_beg;
+    int32_t *active_end;
     int32_t *tile_expert;
     int32_t *tile_row0;
 };

@@ -22,14 +22,15 @@ namespace beam {
 // grid (I/16, max active experts); 4 wavefronts split the reduction over H.
 __global__ __launch_bounds__(256) void gate_up_stream_kernel(
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ w_gate_up,
-    const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm,
-    const int32_t *__restrict__ wl_hdr, const int32_t *__restrict__ wl_active,
-    bf16_t *__restrict__ hidden, int H, int K, int I) {
+    const int32_t *__restrict__ perm, WorkList wl, bf16_t *__restrict__ hidden, int H, int K,
+    int I) {
     const int u = blockIdx.y;
-    if (u >= wl_hdr[0]) return;
-    const int e = wl_active[u];
-    const int row_beg = offsets[e];
-    const int row_end = offsets[e + 1];
+    // one round trip: the four words are independent loads
+    const int n_active = wl.hdr[0];
+    const int e = wl.active[u];
+    const int row_beg = wl.active_beg[u];
+    const int row_end = wl.active_end[u];
+    if (u >= n_active) return;
     const int lane = threadIdx.x & 63;
     const int ks = threadIdx.x >> 6;
     const int l16 = lane & 15;
@@ -48,23 +49,52 @@ __global__ __launch_bounds__(256) void gate_up_stream_kernel(
         const bf16_t *xp = x + (size_t)t * H + kbeg;
         f32x4 ag = {0.f, 0.f, 0.f, 0.f};
         f32x4 au = {0.f, 0.f, 0.f, 0.f};
-        for (int k = 0; k < klen; k += 128) {
-            uint4 wg[4], wu[4], xv[4];
+        // Software pipeline over chunks of 128 reduction indices: the loads of
+        // chunk c+1 are issued before the MFMAs of chunk c, so a wavefront always
+        // has 12 KB in flight.  sched_barrier keeps the compiler from sinking the
+        // loads back behind the MFMAs to save registers.
+        uint4 wg[2][4], wu[2][4], xv[2][4];
+        auto load = [&](int b, int k) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                wg[j] = *(const uint4 *)(gp + k + j * 32);
-                wu[j] = *(const uint4 *)(up + k + j * 32);
-                xv[j] = *(const uint4 *)(xp + k + j * 32);
+                wg[b][j] = *(const uint4 *)(gp + k + j * 32);
+                wu[b][j] = *(const uint4 *)(up + k + j * 32);
             }
 #pragma unroll
+            for (int j = 0; j < 4; ++j) xv[b][j] = *(const uint4 *)(xp + k + j * 32);
+        };
+        auto mma = [&](int b) {
+#pragma unroll
             for (int j = 0; j < 4; ++j) {
-                ag = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wg[j]),
-                                                             __builtin_bit_cast(bf16x8, xv[j]), ag,
-                                                             0, 0, 0);
-                au = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wu[j]),
-                                                             __builtin_bit_cast(bf16x8, xv[j]), au,
-                                                             0, 0, 0);
+                ag = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wg[b][j]),
+                                                             __builtin_bit_cast(bf16x8, xv[b][j]),
+                                                             ag, 0, 0, 0);
+                au = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wu[b][j]),
+                                                             __builtin_bit_cast(bf16x8, xv[b][j]),
+                                                             au, 0, 0, 0);
             }
+        };
+        // steady state without conditionals, so the wait before each MFMA group
+        // counts only the older chunk's loads; the last one or two chunks are peeled
+        load(0, 0);
+        int k = 0;
+        for (; k + 256 < klen; k += 256) {
+            load(1, k + 128);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(0);
+            __builtin_amdgcn_sched_barrier(0);
+            load(0, k + 256);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (k + 128 < klen) {
+            load(1, k + 128);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(0);
+            mma(1);
+        } else {
+            mma(0);
         }
         if (ks > 0) {
 #pragma unroll
@@ -99,14 +129,14 @@ __global__ __launch_bounds__(256) void gate_up_stream_kernel(
 // output features and runs the whole reduction over I.
 template <int FT>
 __global__ __launch_bounds__(256) void down_stream_kernel(
-    const bf16_t *__restrict__ hidden, const bf16_t *__restrict__ w_down,
-    const int32_t *__restrict__ offsets, const int32_t *__restrict__ wl_hdr,
-    const int32_t *__restrict__ wl_active, float *__restrict__ y_pairs, int H, int I) {
+    const bf16_t *__restrict__ hidden, const bf16_t *__restrict__ w_down, WorkList wl,
+    float *__restrict__ y_pairs, int H, int I) {
     const int u = blockIdx.y;
-    if (u >= wl_hdr[0]) return;
-    const int e = wl_active[u];
-    const int row_beg = offsets[e];
-    const int row_end = offsets[e + 1];
+    const int n_active = wl.hdr[0];
+    const int e = wl.active[u];
+    const int row_beg = wl.active_beg[u];
+    const int row_end = wl.active_end[u];
+    if (u >= n_active) return;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int l16 = lane & 15;
@@ -128,21 +158,46 @@ __global__ __launch_bounds__(256) void down_stream_kernel(
         f32x4 acc[FT];
 #pragma unroll
         for (int f = 0; f < FT; ++f) acc[f] = f32x4{0.f, 0.f, 0.f, 0.f};
-        for (int k = 0; k < I; k += 128) {
-            uint4 w[FT][4], hv[4];
+        // same two-deep software pipeline as the gate/up kernel
+        uint4 w[2][FT][4], hv[2][4];
+        auto load = [&](int b, int k) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
 #pragma unroll
-                for (int f = 0; f < FT; ++f) w[f][j] = *(const uint4 *)(wp[f] + k + j * 32);
-                hv[j] = *(const uint4 *)(hp + k + j * 32);
+                for (int f = 0; f < FT; ++f) w[b][f][j] = *(const uint4 *)(wp[f] + k + j * 32);
+                hv[b][j] = *(const uint4 *)(hp + k + j * 32);
             }
+        };
+        auto mma = [&](int b) {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int f = 0; f < FT; ++f)
                     acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                        __builtin_bit_cast(bf16x8, w[f][j]), __builtin_bit_cast(bf16x8, hv[j]),
+                        __builtin_bit_cast(bf16x8, w[b][f][j]), __builtin_bit_cast(bf16x8, hv[b][j]),
                         acc[f], 0, 0, 0);
+        };
+        // steady state without conditionals, so the wait before each MFMA group
+        // counts only the older chunk's loads; the last one or two chunks are peeled
+        load(0, 0);
+        int k = 0;
+        for (; k + 256 < I; k += 256) {
+            load(1, k + 128);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(0);
+            __builtin_amdgcn_sched_barrier(0);
+            load(0, k + 256);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (k + 128 < I) {
+            load(1, k + 128);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(0);
+            mma(1);
+        } else {
+            mma(0);
         }
         if (row0 + l16 < row_end) {
 #pragma unroll
@@ -169,9 +224,9 @@ hipError_t launch_gate_up_stream(const beam_shape &s, const void *x, const void 
                                  const int32_t *offsets, const int32_t *perm, const WorkList &wl,
                                  void *hidden, hipStream_t st) {
     dim3 grid(s.I / 16, max_active(s));
-    gate_up_stream_kernel<<<grid, 256, 0, st>>>((const bf16_t *)x, (const bf16_t *)w_gate_up,
-                                                offsets, perm, wl.hdr, wl.active,
-                                                (bf16_t *)hidden, s.H, s.K, s.I);
+    (void)offsets;
+    gate_up_stream_kernel<<<grid, 256, 0, st>>>((const bf16_t *)x, (const bf16_t *)w_gate_up, perm,
+                                                wl, (bf16_t *)hidden, s.H, s.K, s.I);
     return hipGetLastError();
 }
 
@@ -180,8 +235,9 @@ hipError_t launch_down_stream(const beam_shape &s, const void *hidden, const voi
                               hipStream_t st) {
     constexpr int FT = 2;
     dim3 grid((s.H + 64 * FT - 1) / (64 * FT), max_active(s));
-    down_stream_kernel<FT><<<grid, 256, 0, st>>>((const bf16_t *)hidden, (const bf16_t *)w_down,
-                                                 offsets, wl.hdr, wl.active, y_pairs, s.H, s.I);
+    (void)offsets;
+    down_stream_kernel<FT><<<grid, 256, 0, st>>>((const bf16_t *)hidden, (const bf16_t *)w_down, wl,
+                                                 y_pairs, s.H, s.I);
     return hipGetLastError();
 }
 

@@ -72,7 +72,11 @@ __device__ __forceinline__ void emit_work_list(int e, int N, int count, int offs
     int total;
     const int has = (e < N && count > 0) ? 1 : 0;
     const int slot = block_exclusive_scan_256(has, scratch, &total);
-    if (has) wl.active[slot] = e;
+    if (has) {
+        wl.active[slot] = e;
+        wl.active_beg[slot] = offset;
+        wl.active_end[slot] = offset + count;
+    }
     if (threadIdx.x == 0) wl.hdr[0] = total;
     const int ntile = (e < N) ? (count + kTileM - 1) / kTileM : 0;
     const int tbase = block_exclusive_scan_256(ntile, scratch, &total);
@@ -158,70 +162,141 @@ __global__ __launch_bounds__(64) void scatter_kernel(const int32_t *__restrict__
     }
 }
 
-// Decode batches: the whole pair list is one chunk.  One workgroup of 256
-// threads does count, scan, work list and scatter; wavefront 0 walks the ids.
-__global__ __launch_bounds__(256) void permute_single_chunk_kernel(
-    const int32_t *__restrict__ masked_ids, int32_t *__restrict__ counts,
-    int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm,
-    int32_t *__restrict__ num_pairs, int TK, int N, WorkList wl) {
-    __shared__ int hist[256];
-    __shared__ int run[256];
-    __shared__ int scratch[256];
+// Decode batches: the whole pair list is one chunk (T*K <= kChunk).  The first
+// 256 threads of the workgroup do count, scans, work list and scatter with
+// four barriers (every thread of the workgroup must call this; `ids` may live
+// in LDS or in global memory).  Wavefront w < 4 ranks the pairs of groups w and
+// w+4 (64 pairs each) with ballots; thread e < 256 then owns expert e.
+struct ChunkShared {
+    int grp[kGroupsPerChunk][256];  // kept pairs per (group, expert), then their prefix
+    int offs[256];
+    int wtot[4][3];
+};
+
+__device__ __forceinline__ void permute_chunk_body(const int32_t *ids, ChunkShared &sh,
+                                                   int32_t *__restrict__ counts,
+                                                   int32_t *__restrict__ offsets,
+                                                   int32_t *__restrict__ perm,
+                                                   int32_t *__restrict__ inv_perm,
+                                                   int32_t *__restrict__ num_pairs, int TK, int N,
+                                                   const WorkList &wl) {
+    static_assert(kGroupsPerChunk == 8, "two groups per wavefront");
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const bool walker = tid < 64;
-    hist[tid] = 0;
-    __syncthreads();
-    int ids[kGroupsPerChunk];
-    uint64_t peers[kGroupsPerChunk];
+    const int wave = tid >> 6;
+    const bool worker = tid < 256;  // wave-uniform
+    if (worker) {
 #pragma unroll
-    for (int gidx = 0; gidx < kGroupsPerChunk; ++gidx) {
-        ids[gidx] = -1;
-        peers[gidx] = 0;
-        if (walker) {
-            const int f = gidx * 64 + lane;
-            const int id = f < TK ? masked_ids[f] : -1;
+        for (int g = 0; g < kGroupsPerChunk; ++g) sh.grp[g][tid] = 0;
+    }
+    __syncthreads();
+    int id2[2] = {-1, -1}, rank2[2] = {0, 0};
+    if (worker) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int g = wave + 4 * q;
+            const int f = g * 64 + lane;
+            const int id = f < TK ? ids[f] : -1;
             const bool valid = id >= 0 && id < N;
-            ids[gidx] = valid ? id : -1;
-            peers[gidx] = match_id(id, valid);
-            if (valid && (peers[gidx] & ((1ull << lane) - 1ull)) == 0)
-                hist[id] += __popcll(peers[gidx]);
+            const uint64_t peers = match_id(id, valid);
+            id2[q] = valid ? id : -1;
+            rank2[q] = __popcll(peers & ((1ull << lane) - 1ull));
+            if (valid && rank2[q] == 0) sh.grp[g][id] = __popcll(peers);
         }
-        __syncthreads();
     }
-    const int cnt = tid < N ? hist[tid] : 0;
-    int total;
-    const int excl = block_exclusive_scan_256(cnt, scratch, &total);
-    if (tid < N) {
-        counts[tid] = cnt;
-        offsets[tid] = excl;
-    }
-    if (tid == 0) {
-        offsets[N] = total;
-        *num_pairs = total;
-    }
-    run[tid] = excl;
-    emit_work_list(tid, N, cnt, excl, wl, scratch);
     __syncthreads();
+    int cnt = 0, s_cnt = 0, s_has = 0, s_tile = 0;
+    if (worker) {  // thread tid owns expert tid
 #pragma unroll
-    for (int gidx = 0; gidx < kGroupsPerChunk; ++gidx) {
-        const int f = gidx * 64 + lane;
-        const bool valid = walker && ids[gidx] >= 0;
-        const int rank = __popcll(peers[gidx] & ((1ull << lane) - 1ull));
-        const int base = valid ? run[ids[gidx]] : 0;
-        __syncthreads();
-        if (valid && rank == 0) run[ids[gidx]] = base + __popcll(peers[gidx]);
-        __syncthreads();
-        if (walker && f < TK) {
-            if (valid) {
-                perm[base + rank] = f;
-                inv_perm[f] = base + rank;
+        for (int g = 0; g < kGroupsPerChunk; ++g) {
+            const int c = sh.grp[g][tid];
+            sh.grp[g][tid] = cnt;
+            cnt += c;
+        }
+        s_cnt = cnt;
+        s_has = cnt > 0 ? 1 : 0;
+        s_tile = (cnt + kTileM - 1) / kTileM;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int ta = __shfl_up(s_cnt, off);
+            const int tb = __shfl_up(s_has, off);
+            const int tc = __shfl_up(s_tile, off);
+            if (lane >= off) {
+                s_cnt += ta;
+                s_has += tb;
+                s_tile += tc;
+            }
+        }
+        if (lane == 63) {
+            sh.wtot[wave][0] = s_cnt;
+            sh.wtot[wave][1] = s_has;
+            sh.wtot[wave][2] = s_tile;
+        }
+    }
+    __syncthreads();
+    int total = 0;
+    if (worker) {
+        int t_has = 0, t_tile = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) {
+                s_cnt += sh.wtot[w][0];
+                s_has += sh.wtot[w][1];
+                s_tile += sh.wtot[w][2];
+            }
+            total += sh.wtot[w][0];
+            t_has += sh.wtot[w][1];
+            t_tile += sh.wtot[w][2];
+        }
+        const int has = cnt > 0 ? 1 : 0;
+        const int ntile = (cnt + kTileM - 1) / kTileM;
+        const int excl = s_cnt - cnt;
+        sh.offs[tid] = excl;
+        if (tid < N) {
+            counts[tid] = cnt;
+            offsets[tid] = excl;
+        }
+        if (tid == 0) {
+            offsets[N] = total;
+            *num_pairs = total;
+            wl.hdr[0] = t_has;
+            wl.hdr[1] = t_tile;
+        }
+        if (has) {
+            wl.active[s_has - 1] = tid;
+            wl.active_beg[s_has - 1] = excl;
+            wl.active_end[s_has - 1] = excl + cnt;
+        }
+        for (int i = 0; i < ntile; ++i) {
+            wl.tile_expert[s_tile - ntile + i] = tid;
+            wl.tile_row0[s_tile - ntile + i] = excl + i * kTileM;
+        }
+    }
+    __syncthreads();
+    if (worker) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int g = wave + 4 * q;
+            const int f = g * 64 + lane;
+            if (f >= TK) continue;
+            if (id2[q] >= 0) {
+                const int pos = sh.offs[id2[q]] + sh.grp[g][id2[q]] + rank2[q];
+                perm[pos] = f;
+                inv_perm[f] = pos;
             } else {
                 inv_perm[f] = -1;
             }
             if (f >= total) perm[f] = -1;
         }
     }
+}
+
+__global__ __launch_bounds__(256) void permute_single_chunk_kernel(
+    const int32_t *__restrict__ masked_ids, int32_t *__restrict__ counts,
+    int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm,
+    int32_t *__restrict__ num_pairs, int TK, int N, WorkList wl) {
+    __shared__ ChunkShared sh;
+    permute_chunk_body(masked_ids, sh, counts, offsets, perm, inv_perm, num_pairs, TK, N, wl);
 }
 
 hipError_t launch_permute(const beam_shape &s, const int32_t *masked_ids, int32_t *counts,

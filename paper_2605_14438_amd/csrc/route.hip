@@ -6,6 +6,7 @@
 // Both heads are one [T,H] x [H,2N] product.  Logits are accumulated in fp32
 // and stay fp32: rounding them to bf16 would change the Top-K order.
 #include "common.hpp"
+#include "topk.hpp"
 
 namespace beam {
 
@@ -47,17 +48,17 @@ __global__ __launch_bounds__(256) void logits_generic_kernel(
 // and the 8 reduction indices 8*(l >> 4).. of every 32-wide MFMA step (one
 // 16-byte load; the four lanes of a row read 64 contiguous bytes).
 //
-// A workgroup is 4 wavefronts.  KSPLIT of them share one output tile and split
-// the reduction (decode: few tokens, latency matters); the others tile the
-// columns.  MT x NT MFMA tiles per wavefront.
+// A workgroup is WAVES_N x KSPLIT wavefronts: KSPLIT of them share one output
+// tile and split the reduction (decode: few tokens, the kernel is one latency
+// chain, so the chain is cut short); WAVES_N tile the columns.  MT x NT MFMA
+// tiles per wavefront.
 // ---------------------------------------------------------------------------
-template <int MT, int NT, int KSPLIT>
-__global__ __launch_bounds__(256) void logits_mfma_kernel(
+template <int MT, int NT, int WAVES_N, int KSPLIT>
+__global__ __launch_bounds__(64 * WAVES_N * KSPLIT) void logits_mfma_kernel(
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ w_router,
     const float *__restrict__ b_router, const bf16_t *__restrict__ w_mask,
     const float *__restrict__ b_mask, float *__restrict__ router_logits,
     float *__restrict__ mask_logits, int Tn, int H, int N) {
-    constexpr int WAVES_N = 4 / KSPLIT;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int wn = wave % WAVES_N;
@@ -163,14 +164,18 @@ hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_route
         const bf16_t *xb = (const bf16_t *)x;
         const bf16_t *wr = (const bf16_t *)w_router;
         const bf16_t *wm = (const bf16_t *)w_mask;
-        if (T <= 512 && H % 512 == 0) {
+        if (T <= 512 && H % 2048 == 0) {
             dim3 grid((T + 15) / 16, (2 * N + 15) / 16);
-            logits_mfma_kernel<1, 1, 4><<<grid, 256, 0, st>>>(xb, wr, b_router, wm, b_mask,
-                                                              router_logits, mask_logits, T, H, N);
+            logits_mfma_kernel<1, 1, 1, 16><<<grid, 1024, 0, st>>>(
+                xb, wr, b_router, wm, b_mask, router_logits, mask_logits, T, H, N);
+        } else if (T <= 512 && H % 512 == 0) {
+            dim3 grid((T + 15) / 16, (2 * N + 15) / 16);
+            logits_mfma_kernel<1, 1, 1, 4><<<grid, 256, 0, st>>>(
+                xb, wr, b_router, wm, b_mask, router_logits, mask_logits, T, H, N);
         } else {
             dim3 grid((T + 31) / 32, (2 * N + 255) / 256);
-            logits_mfma_kernel<2, 4, 1><<<grid, 256, 0, st>>>(xb, wr, b_router, wm, b_mask,
-                                                              router_logits, mask_logits, T, H, N);
+            logits_mfma_kernel<2, 4, 4, 1><<<grid, 256, 0, st>>>(
+                xb, wr, b_router, wm, b_mask, router_logits, mask_logits, T, H, N);
         }
     } else {
         dim3 grid(T, (2 * N + 3) / 4);
@@ -187,69 +192,17 @@ hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_route
 }
 
 // ---------------------------------------------------------------------------
-// Top-K, softmax over the K survivors, binary mask.  One wavefront per token;
-// lane l holds logits l, l+64, l+128, l+192 (N <= 256).  K rounds of a
-// wave-wide arg-max under the total order (logit descending, expert index
-// ascending); after round k lane k keeps the winner, so slot k = rank k+1.
+// Top-K, softmax over the K survivors, binary mask: one wavefront per token.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void topk_mask_kernel(
     const float *__restrict__ router_logits, const float *__restrict__ mask_logits,
     int32_t *__restrict__ topk_ids, float *__restrict__ topk_w, int32_t *__restrict__ masked_ids,
     int Tn, int N, int K) {
-    const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= Tn) return;  // wave-uniform
-    const float *r = router_logits + (size_t)t * N;
-    constexpr int kNone = 0x7fffffff;
-    float v[4];
-    unsigned avail = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int e = lane + 64 * i;
-        v[i] = 0.0f;
-        if (e < N) {
-            v[i] = r[e];
-            avail |= 1u << i;
-        }
-    }
-    int my_id = 0;
-    float my_r = 0.0f;
-    for (int k = 0; k < K; ++k) {
-        float bv = 0.0f;
-        int bi = kNone;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (((avail >> i) & 1u) && (bi == kNone || v[i] > bv)) {
-                bv = v[i];
-                bi = lane + 64 * i;
-            }
-        }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            const float ov = __shfl_xor(bv, off);
-            const int oi = __shfl_xor(bi, off);
-            const bool take = (oi != kNone) && (bi == kNone || ov > bv || (ov == bv && oi < bi));
-            if (take) {
-                bv = ov;
-                bi = oi;
-            }
-        }
-        if ((bi & 63) == lane) avail &= ~(1u << (bi >> 6));
-        if (lane == k) {
-            my_id = bi;
-            my_r = bv;
-        }
-    }
-    const float top = __shfl(my_r, 0);
-    const float ex = lane < K ? expf(my_r - top) : 0.0f;
-    const float denom = wave_sum(ex);
-    if (lane < K) {
-        const float a = mask_logits[(size_t)t * N + my_id];
-        const size_t f = (size_t)t * K + lane;
-        topk_ids[f] = my_id;
-        topk_w[f] = ex / denom;
-        masked_ids[f] = (a >= 0.0f) ? my_id : -1;
-    }
+    const size_t f = (size_t)t * K;
+    wave_route_token(router_logits + (size_t)t * N, mask_logits + (size_t)t * N, N, K,
+                     topk_ids + f, topk_w + f, masked_ids + f);
 }
 
 hipError_t launch_topk_mask(const beam_shape &s, const float *router_logits,

@@ -1,0 +1,101 @@
+// Wave-level Top-K + softmax + binary mask for one token (paper Sec. 3.2 Step 1,
+// Eq. 4, Eq. 6), shared by the routing kernels.
+#pragma once
+
+#include "common.hpp"
+
+namespace beam {
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint64_t dpp_move_u64(uint64_t v) {
+    // lanes whose source lies outside the row / mask keep their own value
+    const int lo = __builtin_amdgcn_update_dpp((int)(uint32_t)v, (int)(uint32_t)v, CTRL, ROW_MASK,
+                                               0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp((int)(uint32_t)(v >> 32), (int)(uint32_t)(v >> 32),
+                                               CTRL, ROW_MASK, 0xf, false);
+    return ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo;
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ void max_step(uint64_t &key) {
+    const uint64_t other = dpp_move_u64<CTRL, ROW_MASK>(key);
+    key = other > key ? other : key;
+}
+
+// Largest key of the wavefront, returned in every lane.  DPP lane moves (quad
+// swaps, half-row and row mirrors, row broadcasts into lane 63) cost a cycle or
+// two each where an LDS-routed shuffle costs tens; routing is one latency chain.
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t key) {
+    max_step<0xB1, 0xf>(key);   // quad_perm [1,0,3,2]
+    max_step<0x4E, 0xf>(key);   // quad_perm [2,3,0,1]
+    max_step<0x141, 0xf>(key);  // row_half_mirror
+    max_step<0x140, 0xf>(key);  // row_mirror: every lane of a 16-lane row holds the row's best
+    max_step<0x142, 0xa>(key);  // row_bcast:15 into rows 1 and 3
+    max_step<0x143, 0xc>(key);  // row_bcast:31 into rows 2 and 3: lane 63 holds the best
+    const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)key, 63);
+    const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(key >> 32), 63);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// One sortable key per candidate: the logit mapped to an unsigned integer that
+// orders like the float, then the complemented expert index, so that a single
+// unsigned compare realises "logit descending, equal logits by ascending expert
+// index".  -0 is folded into +0 first (they compare equal as floats).  The
+// lowest bit carries the candidate's mask decision (a >= 0) along, so the
+// winner's mask needs no second, dependent memory access; it sits below the
+// index and cannot change the order.  Key 0 marks "no candidate".
+__device__ __forceinline__ uint64_t topk_key(float v, int e, bool keep) {
+    uint32_t u = __float_as_uint(v + 0.0f);
+    u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    const uint32_t low = ((0x7FFFFFFFu - (uint32_t)e) << 1) | (keep ? 1u : 0u);
+    return ((uint64_t)u << 32) | low;
+}
+__device__ __forceinline__ int key_expert(uint64_t key) {
+    return (int)(0x7FFFFFFFu - ((uint32_t)key >> 1));
+}
+__device__ __forceinline__ bool key_keep(uint64_t key) { return ((uint32_t)key & 1u) != 0; }
+__device__ __forceinline__ float key_logit(uint64_t key) {
+    uint32_t u = (uint32_t)(key >> 32);
+    u = (u & 0x80000000u) ? (u & 0x7FFFFFFFu) : ~u;
+    return __uint_as_float(u);
+}
+
+// Whole wavefront, one token: lane l holds logits l, l+64, l+128, l+192
+// (N <= 256) of both heads.  K rounds of wave arg-max; after round k lane k
+// keeps the winner, so slot k = rank k+1.  Lanes k < K then write ids, softmax
+// weights over the K survivors and the masked id (a >= 0 keeps, otherwise -1).
+__device__ __forceinline__ void wave_route_token(const float *__restrict__ r,
+                                                 const float *__restrict__ a, int N, int K,
+                                                 int32_t *__restrict__ ids_out,
+                                                 float *__restrict__ w_out,
+                                                 int32_t *__restrict__ masked_out) {
+    const int lane = threadIdx.x & 63;
+    uint64_t key[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e = lane + 64 * i;
+        key[i] = e < N ? topk_key(r[e], e, a[e] >= 0.0f) : 0ull;
+    }
+    uint64_t mine = 0;
+    for (int k = 0; k < K; ++k) {
+        uint64_t best = key[0];
+#pragma unroll
+        for (int i = 1; i < 4; ++i) best = key[i] > best ? key[i] : best;
+        best = wave_max_u64(best);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) key[i] = key[i] == best ? 0ull : key[i];
+        mine = lane == k ? best : mine;
+    }
+    const int my_id = key_expert(mine);
+    const float my_r = key_logit(mine);
+    const float top = __shfl(my_r, 0);
+    const float ex = lane < K ? expf(my_r - top) : 0.0f;
+    const float denom = wave_sum(ex);
+    if (lane < K) {
+        ids_out[lane] = my_id;
+        w_out[lane] = ex / denom;
+        masked_out[lane] = key_keep(mine) ? my_id : -1;
+    }
+}
+
+}  // namespace beam
