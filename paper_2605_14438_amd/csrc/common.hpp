@@ -17,10 +17,11 @@ constexpr int kWave = 64;
 constexpr int kGroupsPerChunk = 8;
 constexpr int kChunk = kWave * kGroupsPerChunk;
 
-// Row tile of the prefill grouped GEMM: every expert segment is cut into tiles
-// of this many grouped rows (the paper's "block alignment", App. A.4, done with
-// a tile list instead of padding the index array).
-constexpr int kTileM = 128;
+// Smallest row tile of the prefill grouped GEMM (it bounds the length of the
+// tile list).  Every expert segment is cut into tiles of WorkList::tile_m
+// grouped rows: the paper's "block alignment" (App. A.4), done with a tile list
+// instead of padding the index array.
+constexpr int kTileMMin = 128;
 
 typedef uint16_t bf16_t;
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -75,7 +76,7 @@ WsLayout ws_layout(const beam_shape &s);
 
 // Work list written on the device after the prefix sums:
 //   hdr[0] = number of experts with at least one kept pair (U)
-//   hdr[1] = number of row tiles of kTileM grouped rows
+//   hdr[1] = number of row tiles of tile_m grouped rows
 //   active[u]      expert id of the u-th non-empty expert (ascending)
 //   active_beg[u], active_end[u]  its grouped rows [beg, end)
 //   tile_expert[i] expert of row tile i,  tile_row0[i] its first grouped row
@@ -88,8 +89,10 @@ struct WorkList {
     int32_t *active_end;
     int32_t *tile_expert;
     int32_t *tile_row0;
+    int32_t tile_m;  // rows per tile, chosen on the host from the shape
 };
 WorkList work_list(void *base, const beam_shape &s, int max_tiles);
+int ffn_tile_m(const beam_shape &s);
 
 // ---- launchers (each returns hipGetLastError() after enqueueing) ----------
 hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_router,

@@ -78,11 +78,11 @@ __device__ __forceinline__ void emit_work_list(int e, int N, int count, int offs
         wl.active_end[slot] = offset + count;
     }
     if (threadIdx.x == 0) wl.hdr[0] = total;
-    const int ntile = (e < N) ? (count + kTileM - 1) / kTileM : 0;
+    const int ntile = (e < N) ? (count + wl.tile_m - 1) / wl.tile_m : 0;
     const int tbase = block_exclusive_scan_256(ntile, scratch, &total);
     for (int i = 0; i < ntile; ++i) {
         wl.tile_expert[tbase + i] = e;
-        wl.tile_row0[tbase + i] = offset + i * kTileM;
+        wl.tile_row0[tbase + i] = offset + i * wl.tile_m;
     }
     if (threadIdx.x == 0) wl.hdr[1] = total;
 }
@@ -215,7 +215,7 @@ __device__ __forceinline__ void permute_chunk_body(const int32_t *ids, ChunkShar
         }
         s_cnt = cnt;
         s_has = cnt > 0 ? 1 : 0;
-        s_tile = (cnt + kTileM - 1) / kTileM;
+        s_tile = (cnt + wl.tile_m - 1) / wl.tile_m;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const int ta = __shfl_up(s_cnt, off);
@@ -249,7 +249,7 @@ __device__ __forceinline__ void permute_chunk_body(const int32_t *ids, ChunkShar
             t_tile += sh.wtot[w][2];
         }
         const int has = cnt > 0 ? 1 : 0;
-        const int ntile = (cnt + kTileM - 1) / kTileM;
+        const int ntile = (cnt + wl.tile_m - 1) / wl.tile_m;
         const int excl = s_cnt - cnt;
         sh.offs[tid] = excl;
         if (tid < N) {
@@ -269,7 +269,7 @@ __device__ __forceinline__ void permute_chunk_body(const int32_t *ids, ChunkShar
         }
         for (int i = 0; i < ntile; ++i) {
             wl.tile_expert[s_tile - ntile + i] = tid;
-            wl.tile_row0[s_tile - ntile + i] = excl + i * kTileM;
+            wl.tile_row0[s_tile - ntile + i] = excl + i * wl.tile_m;
         }
     }
     __syncthreads();

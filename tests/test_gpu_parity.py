@@ -170,6 +170,7 @@ FFN_CASES = [
     SMALL_BF16.with_(T=200, keep=1.0),               # streaming with > 16 rows per expert
     PREFILL_SMALL,                                   # tiled grouped GEMM, ragged tiles
     PREFILL_SMALL.with_(T=1100, keep=1.0),
+    PREFILL_SMALL.with_(T=2200, keep=0.7),           # 256-row tiles (T*K >= 512*N)
 ]
 
 
@@ -247,7 +248,7 @@ def _check_forward(cfg, d, res, ref, token_subset=None):
 FWD_CASES = [
     CFG["tiny"], CFG["tiny"].with_(T=1), CFG["tiny"].with_(T=130, keep=1.0), SMALL_BF16, ODD_BF16,
     SMALL_BF16.with_(keep=0.0), SMALL_BF16.with_(keep=1.0),
-    PREFILL_SMALL, PREFILL_SMALL.with_(T=1100, keep=1.0),
+    PREFILL_SMALL, PREFILL_SMALL.with_(T=1100, keep=1.0), PREFILL_SMALL.with_(T=2200, keep=0.7),
 ]
 
 
