@@ -42,16 +42,20 @@ def parse_args():
     ap.add_argument("--weight-sets", type=int, default=4)
     ap.add_argument("--no-points", action="store_true", help="skip the extra workload points")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--packed", action="store_true",
+                    help="run the main workload from weights repacked once by beam_pack_weights "
+                         "(the prefill points always do)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="also run a plain device copy of this many MiB a few times (a kernel of "
                          "known traffic, to calibrate rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
-def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp):
-    """Time `steps` forwards of one workload point; returns a dict of results."""
+def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp, packed=False):
+    """Time `steps` forwards of one workload point; returns a dict of results.
+    packed: the weight sets are in matrix-core fragment order (beam_pack_weights)."""
     import numpy as np
-    s = hp.shape_of(cfg)
+    s = hp.shape_of(cfg, packed=packed)
     ws, nb = hp.workspace(s)
     out = hp.out_tensor(cfg)
     mids = torch.empty((cfg.T, cfg.K), dtype=torch.int32, device="cuda")
@@ -101,6 +105,7 @@ def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp):
     t_roof_us = max(layer_bytes / (HBM_PEAK_GBS * 1e3), layer_flops / (MFMA_BF16_PEAK_TFLOPS * 1e6))
     return {
         "workload": f"{cfg.name} T={T} keep={cfg.keep}", "T": T, "P": P, "U": U,
+        "weights": "packed" if packed else "plain",
         "us_per_layer": ms * 1e3, "tokens_per_s": T / (ms * 1e-3), "stage_us": stage_us,
         "layer_GBs": layer_bytes / (ms * 1e-3) / 1e9,
         "layer_TFLOPs": layer_flops / (ms * 1e-3) / 1e12,
@@ -168,7 +173,17 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    main_pt = measure_point(cfg, d, g, sets, args.steps, args.warmup, torch, beam, hp)
+    packed_sets = None
+
+    def get_packed_sets():
+        nonlocal packed_sets
+        if packed_sets is None:
+            packed_sets = [hp.pack_weights(cfg, a, b) for a, b in sets]
+            torch.cuda.synchronize()
+        return packed_sets
+
+    main_pt = measure_point(cfg, d, g, get_packed_sets() if args.packed else sets, args.steps,
+                            args.warmup, torch, beam, hp, packed=args.packed)
 
     points = []
     if not args.no_points and args.workload == "qwen3_decode":
@@ -183,7 +198,8 @@ def main():
             c = pre.with_(T=T, keep=keep)
             dd = synth.make_layer(c, with_experts=False)
             gg = {**hp.upload(c, dd), "w_gate_up": g["w_gate_up"], "w_down": g["w_down"]}
-            points.append(measure_point(c, dd, gg, sets, n, 3, torch, beam, hp))
+            points.append(measure_point(c, dd, gg, get_packed_sets(), n, 3, torch, beam, hp,
+                                        packed=True))
     for p in points:
         p["roofline"] = roofline_of(p)
         p.pop("gate_up")
@@ -218,6 +234,7 @@ def main():
         "config": {"workload": f"{cfg.name}: T={cfg.T} H={cfg.H} N={cfg.N} K={cfg.K} I={cfg.I} "
                                f"keep~{cfg.keep}", "kept_pairs": main_pt["P"],
                    "experts_touched": main_pt["U"], "weight_sets_rotated": len(sets),
+                   "weights": main_pt["weights"],
                    "input_setup_s": round(t_gen, 1)},
         "layer": {k: main_pt[k] for k in ("layer_GBs", "layer_TFLOPs", "frac_hbm", "frac_mfma",
                                           "frac_of_roofline", "stage_us")},

@@ -39,10 +39,11 @@
  *   - Errors are return codes only.  Argument checks happen on the host
  *     before anything is enqueued:
  *       BEAM_ERR_INVALID_ARG  NULL required pointer, T < 0, K < 1, K > N,
- *                             H/N/I < 1, unknown dtype, misaligned pointer
+ *                             H/N/I < 1, unknown dtype or layout, misaligned pointer
  *                             (16 bytes for x, weights, out, y_pairs, workspace)
  *       BEAM_ERR_UNSUPPORTED  outside the envelope: N <= 256, K <= 64,
- *                             H % 8 == 0, I % 8 == 0, T*K < 2^24
+ *                             H % 8 == 0, I % 8 == 0, T*K < 2^24; packed weights
+ *                             need bf16, H % 512 == 0 and I % 128 == 0
  *       BEAM_ERR_WORKSPACE    workspace smaller than beam_workspace_bytes()
  *       BEAM_ERR_HIP          a launch failed (hipGetLastError() != success)
  *     T == 0 returns BEAM_OK without launching anything.
@@ -68,11 +69,30 @@ typedef enum {
 
 typedef enum { BEAM_F32 = 0, BEAM_BF16 = 1 } beam_dtype;
 
+/* Memory order of the expert weights w_gate_up and w_down.
+ *   BEAM_WEIGHTS_PLAIN   row-major [N,2I,H] and [N,H,I] as described above.
+ *   BEAM_WEIGHTS_PACKED  the same numbers in matrix-core fragment order, written
+ *                        once by beam_pack_weights (bf16 only).  Per expert, a
+ *                        matrix W[R][Kd] (R output features, Kd reduction) is cut
+ *                        into blocks of 32 rows x 16 reduction indices; block
+ *                        (rb, ks) is 1 KiB at element offset (rb*(Kd/16) + ks)*512
+ *                        and holds, for l = 0..63 and i = 0..7, at l*8 + i the
+ *                        value W[row(rb, l & 31)][ks*16 + (l >> 5)*8 + i].
+ *                        w_down: row(rb, c) = rb*32 + c.  w_gate_up: blocks
+ *                        alternate gate and up: row(2q, c) = gate feature
+ *                        q*32 + c, row(2q+1, c) = up feature q*32 + c.
+ *                        A wavefront then reads the B operand of a 32x32x16 MFMA
+ *                        with one fully coalesced 1 KiB load.  Prefill-sized
+ *                        batches run about twice as fast from this layout. */
+typedef enum { BEAM_WEIGHTS_PLAIN = 0, BEAM_WEIGHTS_PACKED = 1 } beam_weight_layout;
+
 /* T tokens, H hidden size (d_h), N experts, K experts per token, I expert
- * intermediate size; dtype of x, of every weight and of out.  Host struct. */
+ * intermediate size; dtype of x, of every weight and of out; layout of the
+ * expert weights.  Host struct. */
 typedef struct {
     int32_t T, H, N, K, I;
-    int32_t dtype; /* beam_dtype */
+    int32_t dtype;         /* beam_dtype */
+    int32_t weight_layout; /* beam_weight_layout */
 } beam_shape;
 
 /* Bytes of device workspace sufficient for any entry point at this shape
@@ -83,8 +103,19 @@ size_t beam_workspace_bytes(const beam_shape *shape);
 /* Static description of a status code (host string, never NULL). */
 const char *beam_status_string(beam_status status);
 
-/* Library ABI version (bumped when a signature changes). */
+/* Library ABI version (bumped when a signature or struct changes). */
 int32_t beam_abi_version(void);
+
+/*
+ * One-time repack of static expert weights (Eq. 3's W_gate, W_up, W_down) from
+ * BEAM_WEIGHTS_PLAIN into BEAM_WEIGHTS_PACKED order; a pure permutation, so the
+ * packed buffers have the size of the plain ones ([N,2I,H] and [N,H,I] elements)
+ * and must not overlap them.  bf16 only, H % 32 == 0 and I % 32 == 0, else
+ * BEAM_ERR_UNSUPPORTED.  Not part of the per-layer hot path.  shape->T and
+ * shape->weight_layout are ignored.
+ */
+beam_status beam_pack_weights(const beam_shape *shape, const void *w_gate_up, const void *w_down,
+                              void *w_gate_up_packed, void *w_down_packed, void *hip_stream);
 
 /*
  * Steps 1-3 of Sec. 3.2: router logits, Top-K + softmax (Eq. 4), mask

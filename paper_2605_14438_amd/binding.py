@@ -23,17 +23,20 @@ BEAM_ERR_WORKSPACE = 3
 BEAM_ERR_HIP = 4
 BEAM_F32 = 0
 BEAM_BF16 = 1
+BEAM_WEIGHTS_PLAIN = 0
+BEAM_WEIGHTS_PACKED = 1
 
 EXPORTS = ("beam_abi_version", "beam_status_string", "beam_workspace_bytes", "beam_route_mask",
            "beam_permute", "beam_expert_ffn", "beam_combine", "beam_moe_forward",
-           "beam_moe_forward_timed")
+           "beam_moe_forward_timed", "beam_pack_weights")
 BEAM_NUM_STAGES = 6
 STAGE_NAMES = ("logits", "topk_mask", "permute", "gate_up", "down", "combine")
 
 
 class beam_shape(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32),
-                ("K", ctypes.c_int32), ("I", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+                ("K", ctypes.c_int32), ("I", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("weight_layout", ctypes.c_int32)]
 
 
 class BeamError(RuntimeError):
@@ -72,6 +75,8 @@ def load() -> ctypes.CDLL:
         lib.beam_combine.argtypes = [sp] + [vp] * 6
         lib.beam_moe_forward.restype = ctypes.c_int
         lib.beam_moe_forward.argtypes = [sp] + [vp] * 13 + [sz, vp]
+        lib.beam_pack_weights.restype = ctypes.c_int
+        lib.beam_pack_weights.argtypes = [sp] + [vp] * 5
         lib.beam_moe_forward_timed.restype = ctypes.c_int
         lib.beam_moe_forward_timed.argtypes = [sp] + [vp] * 9 + [sz, vp,
                                                                  ctypes.POINTER(ctypes.c_float)]
@@ -90,12 +95,12 @@ def _p(a) -> Optional[int]:
 def _shape(s) -> beam_shape:
     if isinstance(s, beam_shape):
         return s
-    T, H, N, K, I, dtype = s
-    return beam_shape(T, H, N, K, I, dtype)
+    return beam_shape(*s)
 
 
-def make_shape(T: int, H: int, N: int, K: int, I: int, dtype: int) -> beam_shape:
-    return beam_shape(T, H, N, K, I, dtype)
+def make_shape(T: int, H: int, N: int, K: int, I: int, dtype: int,
+               weight_layout: int = BEAM_WEIGHTS_PLAIN) -> beam_shape:
+    return beam_shape(T, H, N, K, I, dtype, weight_layout)
 
 
 def _check(fn: str, status: int, check: bool) -> int:
@@ -115,6 +120,14 @@ def beam_status_string(status: int) -> str:
 def beam_workspace_bytes(shape) -> int:
     s = _shape(shape)
     return int(load().beam_workspace_bytes(ctypes.byref(s)))
+
+
+def beam_pack_weights(shape, w_gate_up, w_down, w_gate_up_packed, w_down_packed, hip_stream=None,
+                      check: bool = True) -> int:
+    s = _shape(shape)
+    st = load().beam_pack_weights(ctypes.byref(s), _p(w_gate_up), _p(w_down),
+                                  _p(w_gate_up_packed), _p(w_down_packed), _p(hip_stream))
+    return _check("beam_pack_weights", st, check)
 
 
 def beam_route_mask(shape, x, w_router, router_bias, w_mask, mask_bias, topk_ids, topk_weights,

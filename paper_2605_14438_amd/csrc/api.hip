@@ -1,6 +1,7 @@
 // The C ABI of libbeam (include/beam.h): argument checks on the host, the
 // workspace carve-up, and the order in which the stage kernels are enqueued.
-// Nothing here allocates, copies to the host or synchronises.
+// Nothing here allocates, copies to the host or synchronises (the stage-timed
+// measurement entry point excepted).
 #include "common.hpp"
 
 namespace beam {
@@ -25,6 +26,8 @@ hipError_t launch_gate_up_tiled(const beam_shape &s, const void *x, const void *
 hipError_t launch_down_tiled(const beam_shape &s, const void *hidden, const void *w_down,
                              const int32_t *offsets, const WorkList &wl, float *y_pairs,
                              hipStream_t st);
+hipError_t launch_pack_weights(const beam_shape &s, const void *w_gate_up, const void *w_down,
+                               void *w_gate_up_packed, void *w_down_packed, hipStream_t st);
 
 static inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
@@ -77,6 +80,7 @@ WorkList work_list(void *base, const beam_shape &s, int max_tiles) {
 // Row count per expert above which the tiled GEMM beats re-streaming the
 // weights once per 16 rows (worst case, every Top-K pair kept).
 static bool use_tiled(const beam_shape &s) {
+    if (s.weight_layout == BEAM_WEIGHTS_PACKED) return true;  // the only consumer of that layout
     return tiled_ffn_supported(s) && (long)s.T * s.K > 32L * s.N;
 }
 
@@ -101,10 +105,14 @@ hipError_t launch_down(const beam_shape &s, const void *hidden, const void *w_do
 static beam_status check_shape(const beam_shape *s) {
     if (!s) return BEAM_ERR_INVALID_ARG;
     if (s->dtype != BEAM_F32 && s->dtype != BEAM_BF16) return BEAM_ERR_INVALID_ARG;
+    if (s->weight_layout != BEAM_WEIGHTS_PLAIN && s->weight_layout != BEAM_WEIGHTS_PACKED)
+        return BEAM_ERR_INVALID_ARG;
     if (s->T < 0 || s->H < 1 || s->N < 1 || s->I < 1 || s->K < 1 || s->K > s->N)
         return BEAM_ERR_INVALID_ARG;
     if (s->N > 256 || s->K > 64 || s->H % 8 != 0 || s->I % 8 != 0) return BEAM_ERR_UNSUPPORTED;
     if ((long)s->T * s->K >= (1L << 24)) return BEAM_ERR_UNSUPPORTED;
+    if (s->weight_layout == BEAM_WEIGHTS_PACKED && !tiled_ffn_supported(*s))
+        return BEAM_ERR_UNSUPPORTED;
     return BEAM_OK;
 }
 
@@ -128,7 +136,7 @@ using namespace beam;
 
 extern "C" {
 
-int32_t beam_abi_version(void) { return 1; }
+int32_t beam_abi_version(void) { return 2; }
 
 const char *beam_status_string(beam_status status) {
     switch (status) {
@@ -144,6 +152,24 @@ const char *beam_status_string(beam_status status) {
 size_t beam_workspace_bytes(const beam_shape *shape) {
     if (check_shape(shape) != BEAM_OK) return 0;
     return ws_layout(*shape).total;
+}
+
+beam_status beam_pack_weights(const beam_shape *shape, const void *w_gate_up, const void *w_down,
+                              void *w_gate_up_packed, void *w_down_packed, void *hip_stream) {
+    if (!shape) return BEAM_ERR_INVALID_ARG;
+    beam_shape s = *shape;
+    s.T = 0;
+    s.weight_layout = BEAM_WEIGHTS_PLAIN;
+    beam_status st = check_shape(&s);
+    if (st != BEAM_OK) return st;
+    if (!w_gate_up || !w_down || !w_gate_up_packed || !w_down_packed) return BEAM_ERR_INVALID_ARG;
+    if (misaligned(w_gate_up) || misaligned(w_down) || misaligned(w_gate_up_packed) ||
+        misaligned(w_down_packed) || w_gate_up == w_gate_up_packed || w_down == w_down_packed)
+        return BEAM_ERR_INVALID_ARG;
+    if (s.dtype != BEAM_BF16 || s.H % 32 != 0 || s.I % 32 != 0) return BEAM_ERR_UNSUPPORTED;
+    BEAM_TRY_HIP(launch_pack_weights(s, w_gate_up, w_down, w_gate_up_packed, w_down_packed,
+                                     (hipStream_t)hip_stream));
+    return BEAM_OK;
 }
 
 beam_status beam_route_mask(const beam_shape *shape, const void *x, const void *w_router,

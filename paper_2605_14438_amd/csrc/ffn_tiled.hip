@@ -4,250 +4,352 @@
 // The kept pairs of expert e are the grouped rows [offsets[e], offsets[e+1]).
 // Each segment is cut into row tiles of BM rows (the work list; this is the
 // "block alignment" of App. A.4 without padding the index array: rows past the
-// end of a segment are clamped on load and masked on store).  One workgroup
-// computes a BM x BN output tile, K-loop in steps of 64:
+// end of a segment are clamped on load and masked on store).  One workgroup of
+// 4 wavefronts (WM x 4/WM) computes a BM x 256 output tile, each wavefront a
+// (BM/WM) x (64*WM) sub-tile of 32x32 MFMA tiles, K-loop in steps of 64:
 //
 //   GATE_UP:  A = x rows gathered through perm (token = perm[row] / K),
-//             B = BN/2 gate rows and the BN/2 matching up rows of W_gate_up[e],
+//             B = 128 gate rows and the 128 matching up rows of W_gate_up[e],
 //             interleaved in blocks of 32 so that MFMA column tile 2q holds
 //             gate features and tile 2q+1 the same features of up; the
 //             epilogue forms SiLU(gate)*up in registers and writes bf16.
-//   DOWN:     A = hidden rows (contiguous), B = BN rows of W_down[e]; the
+//   DOWN:     A = hidden rows (contiguous), B = 256 rows of W_down[e]; the
 //             epilogue writes fp32 y_pairs.
 //
-// Both operands are "reduction dimension contiguous", which is the order the
-// MFMA wants, so tiles travel global -> registers -> LDS in 16-byte pieces,
-// double buffered: the global loads of k-step i+1 are in flight while k-step i
-// is multiplied out of the other LDS stage.  LDS rows hold 8 pieces (64 bf16);
-// piece c of row r is stored at c ^ (r & 7) so that the 16-byte operand reads
-// of 8 consecutive rows fall in 8 different bank groups.
+// Operand paths.  On gfx950 the MFMA rate is twice MI300's while the LDS still
+// delivers 128 B/clk/CU on reads and about half that on writes, so a kernel
+// that stages both operands through LDS is LDS bound.  Here only the
+// activations (A) go global -> registers -> LDS (double buffered, 16-byte
+// pieces, piece c of row r stored at c ^ (r & 7) so the operand reads of 8
+// consecutive rows fall in 8 different bank groups).  The weights (B) never
+// touch LDS; they go from global memory straight into the MFMA B registers,
+// refilled on a rolling basis about three quarters of a K-step ahead.
+//   PACKED weights (beam_pack_weights) are stored in MFMA fragment order: the B
+//   operand of one 32x32x16 MFMA is one contiguous 1 KiB block, lane l reading
+//   bytes 16*l, so every weight load is fully coalesced and a wavefront's
+//   stream through an expert is sequential.
+//   PLAIN row-major weights are also "reduction dimension contiguous", which is
+//   the order the MFMA wants, so they can be fed directly too: every lane loads
+//   the 64 contiguous bytes of its weight row that it needs for the four MFMA
+//   k-steps of a K-step.  To make them contiguous, step j of lane-half h uses
+//   k = 32*h + 8*j..+7 on BOTH operands (a permutation of the reduction index,
+//   which leaves the dot product unchanged): A piece 4*h + j from LDS.  But
+//   adjacent lanes then sit in different weight rows, and the vector memory
+//   path serves such 16-byte pieces at about one per clock: this variant runs
+//   at roughly half the speed of the packed one.
 //
 // Work order.  Workgroups are handed to the 8 XCDs round-robin by linear id,
-// and each XCD has its own L2.  Linear id b is therefore remapped to work item
-// (b % 8) * ceil(W/8) + b / 8: every XCD walks one contiguous eighth of the
-// (expert, row tile, column tile) list, column tile fastest, so the workgroups
-// that run together on an XCD share their A tile and their expert's weights
-// through that XCD's L2 instead of each pulling them from HBM.
+// and each XCD has its own L2.  The grid is persistent (one workgroup per CU);
+// workgroup b serves XCD b % 8 and walks items (b % 8) * ceil(W/8) + b/8,
+// + 32, ...: every XCD owns one contiguous eighth of the (expert, row tile,
+// column tile) list, column tile fastest, so the workgroups that run together
+// on an XCD share their A tile and their expert's weights through that XCD's
+// L2 instead of each pulling them from HBM.
 //
-// v_mfma_f32_32x32x16_bf16 layouts (wave64): A/B lane l -> row/col l & 31,
-// k = 8*(l >> 5)..+7;  D register r of lane l -> row 8*(r >> 2) + 4*(l >> 5) +
-// (r & 3), col l & 31.
+// v_mfma_f32_32x32x16_bf16 layouts (wave64): A/B lane l -> row/col l & 31;
+// D register r of lane l -> row 8*(r >> 2) + 4*(l >> 5) + (r & 3), col l & 31.
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace beam {
 
-template <int BM, int BN, int WM, int WN, bool GATE_UP>
-__global__ __launch_bounds__(64 * WM * WN) void ffn_tile_kernel(
+constexpr int kTileN = 256;
+
+// KS = MFMA k-steps (16 reduction indices each) per K-step of the main loop: one
+// K-step is the prefetch distance, and at full MFMA rate a 256 x 256 x 64 step
+// lasts about 1 us, half an HBM round trip under load, so KS = 8 (K-step 128).
+template <int BM, int WM, int KS, bool GATE_UP, bool PACKED>
+__global__ __launch_bounds__(256) void ffn_tile_kernel(
     const bf16_t *__restrict__ a_src,   // GATE_UP: x [T,H];  DOWN: hidden [P,I]
     const bf16_t *__restrict__ w,       // GATE_UP: w_gate_up [N,2I,H];  DOWN: w_down [N,H,I]
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm,
     const int32_t *__restrict__ wl_hdr, const int32_t *__restrict__ tile_expert,
     const int32_t *__restrict__ tile_row0, bf16_t *__restrict__ hidden_out,
     float *__restrict__ y_out, int H, int K, int I, int n_col_tiles) {
-    constexpr int NT = 64 * WM * WN;
-    constexpr int RPP = NT / 8;          // tile rows copied per pass
-    constexpr int AP = BM / RPP;
-    constexpr int BP = BN / RPP;
-    constexpr int WTM = BM / WM / 32;    // MFMA tiles per wavefront
-    constexpr int WTN = BN / WN / 32;
-    static_assert(BM % RPP == 0 && BN % RPP == 0, "tile/loader mismatch");
-    static_assert(!GATE_UP || WTN % 2 == 0, "gate/up tiles must pair inside a wavefront");
-
-    // XCD-aware work order
-    const int n_work = wl_hdr[1] * n_col_tiles;
-    const int per_xcd = (n_work + 7) >> 3;
-    const int slot = blockIdx.x >> 3;
-    const int work = (blockIdx.x & 7) * per_xcd + slot;
-    if (slot >= per_xcd || work >= n_work) return;
-    const int tile = work / n_col_tiles;
-    const int col_tile = work - tile * n_col_tiles;
-
-    const int e = tile_expert[tile];
-    const int row0 = tile_row0[tile];
-    const int row_end = offsets[e + 1];
-    const int n0 = col_tile * (GATE_UP ? BN / 2 : BN);
-    const int kdim = GATE_UP ? H : I;
-
-    __shared__ uint4 As[2][BM * 8];
-    __shared__ uint4 Bs[2][BN * 8];
+    constexpr int PR = 2 * KS;           // 16-byte pieces per LDS row (K-step of 16*KS indices)
+    constexpr int RPP = 256 / PR;        // tile rows copied per pass of the 256 threads
+    constexpr int AP = BM / RPP;         // A rows per thread
+    constexpr int WN = 4 / WM;
+    constexpr int WTM = BM / WM / 32;    // MFMA row tiles per wavefront
+    constexpr int WTN = 8 / WN;          // MFMA column tiles per wavefront (256 columns in all)
+    static_assert(WM == 1 || WM == 2, "wavefront grid is 1x4 or 2x2");
+    __shared__ uint4 As[2][BM * PR];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int wm = wave / WN;
     const int wn = wave % WN;
-    const int piece = tid & 7;
-    const int lr = tid >> 3;
+    const int piece = tid % PR;
+    const int lr = tid / PR;
+    const int l32 = lane & 31;
+    const int kh = lane >> 5;
+    const int kdim = GATE_UP ? H : I;
+    const int nk = kdim / (16 * KS);
 
-    const bf16_t *ap[AP];
-    const bf16_t *bp[BP];
-#pragma unroll
-    for (int p = 0; p < AP; ++p) {
-        int grow = row0 + lr + p * RPP;
-        grow = grow < row_end ? grow : row_end - 1;
-        if constexpr (GATE_UP) {
-            const int tok = perm[grow] / K;
-            ap[p] = a_src + (size_t)tok * H + piece * 8;
-        } else {
-            ap[p] = a_src + (size_t)grow * I + piece * 8;
-        }
-    }
-#pragma unroll
-    for (int p = 0; p < BP; ++p) {
-        const int r = lr + p * RPP;
-        if constexpr (GATE_UP) {
-            const int blk = r >> 5;
-            const int feat = n0 + (blk >> 1) * 32 + (r & 31);
-            const int wrow = (blk & 1) ? I + feat : feat;
-            bp[p] = w + ((size_t)e * 2 * I + wrow) * H + piece * 8;
-        } else {
-            bp[p] = w + ((size_t)e * H + n0 + r) * I + piece * 8;
-        }
-    }
+    const int n_work = wl_hdr[1] * n_col_tiles;
+    const int per_xcd = (n_work + 7) >> 3;
+    const int xcd = blockIdx.x & 7;
+    const int n_local = gridDim.x >> 3;
 
-    f32x16 acc[WTM][WTN];
+    for (int slot = blockIdx.x >> 3; slot < per_xcd; slot += n_local) {
+        const int work = xcd * per_xcd + slot;
+        if (work >= n_work) break;
+        const int tile = work / n_col_tiles;
+        const int col_tile = work - tile * n_col_tiles;
+        const int e = tile_expert[tile];
+        const int row0 = tile_row0[tile];
+        const int row_end = offsets[e + 1];
+        const int n0 = col_tile * (GATE_UP ? kTileN / 2 : kTileN);
+
+        // element offsets of this thread's A rows (32 bits: T*H and T*K*I < 2^32,
+        // checked on the host); pointers would cost twice the registers
+        uint32_t ao[AP];
+        const bf16_t *bp[WTN];
 #pragma unroll
-    for (int m = 0; m < WTM; ++m)
+        for (int p = 0; p < AP; ++p) {
+            int grow = row0 + lr + p * RPP;
+            grow = grow < row_end ? grow : row_end - 1;
+            if constexpr (GATE_UP) {
+                const int tok = perm[grow] / K;
+                ao[p] = (uint32_t)tok * (uint32_t)H + piece * 8;
+            } else {
+                ao[p] = (uint32_t)grow * (uint32_t)I + piece * 8;
+            }
+        }
+#pragma unroll
+        for (int n = 0; n < WTN; ++n) {
+            const int nb = wn * WTN + n;
+            if constexpr (PACKED) {
+                // 32-row block rb of this expert: (kdim/16) fragments of 512 elements
+                const int rows32 = (GATE_UP ? 2 * I : H) >> 5;
+                const int rb = col_tile * 8 + nb;
+                bp[n] = w + ((size_t)e * rows32 + rb) * (size_t)(kdim >> 4) * 512 + lane * 8;
+            } else if constexpr (GATE_UP) {
+                const int feat = n0 + (nb >> 1) * 32 + l32;
+                const int wrow = (nb & 1) ? I + feat : feat;
+                bp[n] = w + ((size_t)e * 2 * I + wrow) * H + kh * (8 * KS);
+            } else {
+                bp[n] = w + ((size_t)e * H + n0 + nb * 32 + l32) * I + kh * (8 * KS);
+            }
+        }
+        // element stride between the weight pieces of consecutive MFMA k-steps,
+        // and between consecutive K-steps
+        constexpr int kBStep = PACKED ? 512 : 8;
+        constexpr int kBKStep = PACKED ? 512 * KS : 16 * KS;
+
+        f32x16 acc[WTM][WTN];
+#pragma unroll
+        for (int m = 0; m < WTM; ++m)
+#pragma unroll
+            for (int n = 0; n < WTN; ++n)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.0f;
+
+        uint4 ra[AP];
+        uint4 bq[WTN][KS];
+// activation tile: global -> registers, registers -> swizzled LDS stage
+#define BEAM_GLOAD_A(ko)                                                         \
+    _Pragma("unroll") for (int p = 0; p < AP; ++p) ra[p] = *(const uint4 *)(a_src + ao[p] + (ko));
+#define BEAM_LSTORE_A(st)                                                        \
+    _Pragma("unroll") for (int p = 0; p < AP; ++p) {                             \
+        const int r_ = lr + p * RPP;                                             \
+        As[st][r_ * PR + (piece ^ (r_ & 7))] = ra[p];                            \
+    }
+        // One K-step out of LDS stage st.  The weight registers are a single
+        // buffer refilled on a rolling basis: as soon as the MFMAs of k-step j
+        // have been issued, bq[.][j] is reloaded for the next K-step, so every
+        // weight load has about three quarters of a K-step to arrive.  The A
+        // fragments of k-step j+1 are read from LDS before the MFMAs of k-step j
+        // are issued.
+        // A fragments are double buffered at half-step granularity: a k-step j is
+        // done in two halves of GH row tiles; the fragments of the next half are
+        // read from LDS before the MFMAs of the current half are issued.
+        constexpr int GH = WTM / 2;
+        auto read_a = [&](int st, int hstep, uint4 *af) {
+            const int j = hstep >> 1;
+            const int g = hstep & 1;
+            const int pc = PACKED ? j * 2 + kh : kh * KS + j;
+#pragma unroll
+            for (int m = 0; m < GH; ++m) {
+                const int r = wm * (BM / WM) + (g * GH + m) * 32 + l32;
+                af[m] = As[st][r * PR + (pc ^ (r & 7))];
+            }
+        };
+        auto compute = [&](int st, auto prefetch, int kt_next) {
+            constexpr bool PF = decltype(prefetch)::value;
+            uint4 af[2][GH];
+            read_a(st, 0, af[0]);
+#pragma unroll
+            for (int hs = 0; hs < 2 * KS; ++hs) {
+                const int j = hs >> 1;
+                const int g = hs & 1;
+                if (hs + 1 < 2 * KS) read_a(st, hs + 1, af[(hs + 1) & 1]);
+#pragma unroll
+                for (int m = 0; m < GH; ++m)
+#pragma unroll
+                    for (int n = 0; n < WTN; ++n)
+                        acc[g * GH + m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, af[hs & 1][m]),
+                            __builtin_bit_cast(bf16x8, bq[n][j]), acc[g * GH + m][n], 0, 0, 0);
+                if constexpr (PF) {
+                    if (g == 1) {
+#pragma unroll
+                        for (int n = 0; n < WTN; ++n)
+                            bq[n][j] = *(const uint4 *)(bp[n] + kt_next * kBKStep + j * kBStep);
+                    }
+                }
+            }
+        };
+
+        BEAM_GLOAD_A(0)
 #pragma unroll
         for (int n = 0; n < WTN; ++n)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.0f;
-
-    uint4 ra[AP], rb[BP];
-    auto gload = [&](int ko) {
-#pragma unroll
-        for (int p = 0; p < AP; ++p) ra[p] = *(const uint4 *)(ap[p] + ko);
-#pragma unroll
-        for (int p = 0; p < BP; ++p) rb[p] = *(const uint4 *)(bp[p] + ko);
-    };
-    auto lstore = [&](int st) {
-#pragma unroll
-        for (int p = 0; p < AP; ++p) {
-            const int r = lr + p * RPP;
-            As[st][r * 8 + (piece ^ (r & 7))] = ra[p];
-        }
-#pragma unroll
-        for (int p = 0; p < BP; ++p) {
-            const int r = lr + p * RPP;
-            Bs[st][r * 8 + (piece ^ (r & 7))] = rb[p];
-        }
-    };
-
-    const int l32 = lane & 31;
-    const int kh = lane >> 5;
-    const int nk = kdim / 64;
-
-    gload(0);
-    lstore(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int st = kt & 1;
-        const bool more = kt + 1 < nk;
-        if (more) gload((kt + 1) * 64);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const int pc = kk * 2 + kh;
-            uint4 af[WTM], bf[WTN];
-#pragma unroll
-            for (int m = 0; m < WTM; ++m) {
-                const int r = wm * (BM / WM) + m * 32 + l32;
-                af[m] = As[st][r * 8 + (pc ^ (r & 7))];
-            }
-#pragma unroll
-            for (int n = 0; n < WTN; ++n) {
-                const int r = wn * (BN / WN) + n * 32 + l32;
-                bf[n] = Bs[st][r * 8 + (pc ^ (r & 7))];
-            }
-#pragma unroll
-            for (int m = 0; m < WTM; ++m)
-#pragma unroll
-                for (int n = 0; n < WTN; ++n)
-                    acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        __builtin_bit_cast(bf16x8, af[m]), __builtin_bit_cast(bf16x8, bf[n]),
-                        acc[m][n], 0, 0, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        // the other stage was last read in iteration kt-1; the barrier that
-        // closed that iteration makes it free to overwrite now
-        if (more) lstore(st ^ 1);
+            for (int j = 0; j < KS; ++j) bq[n][j] = *(const uint4 *)(bp[n] + j * kBStep);
+        BEAM_LSTORE_A(0)
         __syncthreads();
-    }
+        // steady state without conditionals, so each wait counts only older loads
+        for (int kt = 0; kt + 1 < nk; ++kt) {
+            const int st = kt & 1;
+            BEAM_GLOAD_A((kt + 1) * (16 * KS))
+            compute(st, std::true_type{}, kt + 1);
+            BEAM_LSTORE_A(st ^ 1)
+            // The order the scheduler is to build for this K-step (left alone it
+            // sinks every load to just before its first use to save registers):
+            // activation loads first, then per k-step the LDS fragment reads, the
+            // MFMAs and the refill of the weight registers they consumed, and the
+            // LDS stores of the next activation tile last.
+            __builtin_amdgcn_sched_group_barrier(0x020, AP, 0);            // VMEM read
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * GH, 0);        // DS read
+#pragma unroll
+            for (int hs = 0; hs < 2 * KS; ++hs) {
+                __builtin_amdgcn_sched_group_barrier(0x008, GH * WTN, 0);  // MFMA
+                if (hs & 1) __builtin_amdgcn_sched_group_barrier(0x020, WTN, 0);  // refill
+                if (hs < 2 * KS - 2) __builtin_amdgcn_sched_group_barrier(0x100, GH, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x200, AP, 0);            // DS write
+            __syncthreads();
+        }
+        compute((nk - 1) & 1, std::false_type{}, 0);
 
-    // epilogue
+        // epilogue
 #pragma unroll
-    for (int m = 0; m < WTM; ++m) {
+        for (int m = 0; m < WTM; ++m) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int trow = wm * (BM / WM) + m * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
-            const int grow = row0 + trow;
-            if (grow >= row_end) continue;
-            if constexpr (GATE_UP) {
+            for (int r = 0; r < 16; ++r) {
+                const int trow = wm * (BM / WM) + m * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
+                const int grow = row0 + trow;
+                if (grow >= row_end) continue;
+                if constexpr (GATE_UP) {
 #pragma unroll
-                for (int q = 0; q < WTN / 2; ++q) {
-                    const int blk = wn * WTN + 2 * q;
-                    const int feat = n0 + (blk >> 1) * 32 + l32;
-                    const float hv = silu(acc[m][2 * q][r]) * acc[m][2 * q + 1][r];
-                    hidden_out[(size_t)grow * I + feat] = f32_to_bf16(hv);
-                }
-            } else {
+                    for (int q = 0; q < WTN / 2; ++q) {
+                        const int nb = wn * WTN + 2 * q;
+                        const int feat = n0 + (nb >> 1) * 32 + l32;
+                        const float hv = silu(acc[m][2 * q][r]) * acc[m][2 * q + 1][r];
+                        hidden_out[(size_t)grow * I + feat] = f32_to_bf16(hv);
+                    }
+                } else {
 #pragma unroll
-                for (int n = 0; n < WTN; ++n) {
-                    const int c = n0 + (wn * WTN + n) * 32 + l32;
-                    y_out[(size_t)grow * H + c] = acc[m][n][r];
+                    for (int n = 0; n < WTN; ++n) {
+                        const int c = n0 + (wn * WTN + n) * 32 + l32;
+                        y_out[(size_t)grow * H + c] = acc[m][n][r];
+                    }
                 }
             }
         }
+        __syncthreads();  // every wavefront is done with the LDS stages before the next item
     }
+#undef BEAM_GLOAD_A
+#undef BEAM_LSTORE_A
 }
 
 // Row-tile size for a shape, decided on the host from the worst-case average
 // segment length (the host never learns the real counts).
-int ffn_tile_m(const beam_shape &s) {
-    return ((long)s.T * s.K >= 512L * s.N && s.I % 128 == 0 && s.H % 256 == 0) ? 256 : 128;
-}
+int ffn_tile_m(const beam_shape &s) { return ((long)s.T * s.K >= 512L * s.N) ? 256 : 128; }
 
 bool tiled_ffn_supported(const beam_shape &s) {
-    return s.dtype == BEAM_BF16 && s.H % 128 == 0 && s.I % 64 == 0;
+    return s.dtype == BEAM_BF16 && s.H % 256 == 0 && s.I % 128 == 0 &&
+           (long)s.T * s.H < (1L << 32) && (long)s.T * s.K * s.I < (1L << 32);
 }
 
-static int max_tiles(const beam_shape &s, int tile_m) {
-    return (int)((long)s.T * s.K / tile_m + s.N);
+// one persistent workgroup per CU (256 CUs in 8 XCDs)
+constexpr int kPersistentGrid = 256;
+// wavefront grid inside a workgroup: 1 x 4 (each weight fragment is loaded by exactly one wavefront)
+constexpr int kWavesM = 1;
+constexpr int kKSteps = 8;
+
+template <bool GATE_UP>
+static void launch_tile(const beam_shape &s, const bf16_t *a, const bf16_t *w,
+                        const int32_t *offsets, const int32_t *perm, const WorkList &wl,
+                        bf16_t *hidden, float *y, int nct, hipStream_t st) {
+    const bool packed = s.weight_layout == BEAM_WEIGHTS_PACKED;
+    const bool big = ffn_tile_m(s) == 256;
+#define BEAM_LAUNCH_TILE(BM, PK)                                                               \
+    ffn_tile_kernel<BM, kWavesM, kKSteps, GATE_UP, PK><<<kPersistentGrid, 256, 0, st>>>(                \
+        a, w, offsets, perm, wl.hdr, wl.tile_expert, wl.tile_row0, hidden, y, s.H, s.K, s.I, nct)
+    if (big && packed) BEAM_LAUNCH_TILE(256, true);
+    else if (big) BEAM_LAUNCH_TILE(256, false);
+    else if (packed) BEAM_LAUNCH_TILE(128, true);
+    else BEAM_LAUNCH_TILE(128, false);
+#undef BEAM_LAUNCH_TILE
 }
 
 hipError_t launch_gate_up_tiled(const beam_shape &s, const void *x, const void *w_gate_up,
                                 const int32_t *offsets, const int32_t *perm, const WorkList &wl,
                                 void *hidden, hipStream_t st) {
-    const int tm = ffn_tile_m(s);
-    if (tm == 256) {
-        const int nct = s.I / 128;
-        ffn_tile_kernel<256, 256, 2, 4, true><<<max_tiles(s, tm) * nct, 512, 0, st>>>(
-            (const bf16_t *)x, (const bf16_t *)w_gate_up, offsets, perm, wl.hdr, wl.tile_expert,
-            wl.tile_row0, (bf16_t *)hidden, nullptr, s.H, s.K, s.I, nct);
-    } else {
-        const int nct = s.I / 64;
-        ffn_tile_kernel<128, 128, 2, 2, true><<<max_tiles(s, tm) * nct, 256, 0, st>>>(
-            (const bf16_t *)x, (const bf16_t *)w_gate_up, offsets, perm, wl.hdr, wl.tile_expert,
-            wl.tile_row0, (bf16_t *)hidden, nullptr, s.H, s.K, s.I, nct);
-    }
+    launch_tile<true>(s, (const bf16_t *)x, (const bf16_t *)w_gate_up, offsets, perm, wl,
+                      (bf16_t *)hidden, nullptr, s.I / (kTileN / 2), st);
     return hipGetLastError();
 }
 
 hipError_t launch_down_tiled(const beam_shape &s, const void *hidden, const void *w_down,
                              const int32_t *offsets, const WorkList &wl, float *y_pairs,
                              hipStream_t st) {
-    const int tm = ffn_tile_m(s);
-    if (tm == 256) {
-        const int nct = s.H / 256;
-        ffn_tile_kernel<256, 256, 2, 4, false><<<max_tiles(s, tm) * nct, 512, 0, st>>>(
-            (const bf16_t *)hidden, (const bf16_t *)w_down, offsets, nullptr, wl.hdr,
-            wl.tile_expert, wl.tile_row0, nullptr, y_pairs, s.H, s.K, s.I, nct);
-    } else {
-        const int nct = s.H / 128;
-        ffn_tile_kernel<128, 128, 2, 2, false><<<max_tiles(s, tm) * nct, 256, 0, st>>>(
-            (const bf16_t *)hidden, (const bf16_t *)w_down, offsets, nullptr, wl.hdr,
-            wl.tile_expert, wl.tile_row0, nullptr, y_pairs, s.H, s.K, s.I, nct);
+    launch_tile<false>(s, (const bf16_t *)hidden, (const bf16_t *)w_down, offsets, nullptr, wl,
+                       nullptr, y_pairs, s.H / kTileN, st);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// One-time repack of plain row-major expert weights into MFMA fragment order
+// (see BEAM_WEIGHTS_PACKED in beam.h).  One thread per 16-byte piece; writes are
+// contiguous.  rows32 = blocks of 32 output rows per expert, ksteps = Kd / 16.
+// ---------------------------------------------------------------------------
+template <bool GATE_UP>
+__global__ __launch_bounds__(256) void pack_weights_kernel(const uint4 *__restrict__ src,
+                                                           uint4 *__restrict__ dst, int N,
+                                                           int rows, int kd, int I) {
+    const size_t total = (size_t)N * rows * (kd >> 3);
+    const int ksteps = kd >> 4;
+    const int rows32 = rows >> 5;
+    for (size_t o = (size_t)blockIdx.x * 256 + threadIdx.x; o < total;
+         o += (size_t)gridDim.x * 256) {
+        const int l = (int)(o & 63);
+        size_t frag = o >> 6;
+        const int ks = (int)(frag % ksteps);
+        frag /= ksteps;
+        const int rb = (int)(frag % rows32);
+        const int e = (int)(frag / rows32);
+        const int c = l & 31;
+        int row;
+        if constexpr (GATE_UP) {
+            row = (rb & 1) ? I + (rb >> 1) * 32 + c : (rb >> 1) * 32 + c;
+        } else {
+            row = rb * 32 + c;
+        }
+        dst[o] = src[((size_t)e * rows + row) * (kd >> 3) + ks * 2 + (l >> 5)];
     }
+}
+
+hipError_t launch_pack_weights(const beam_shape &s, const void *w_gate_up, const void *w_down,
+                               void *w_gate_up_packed, void *w_down_packed, hipStream_t st) {
+    pack_weights_kernel<true><<<4096, 256, 0, st>>>((const uint4 *)w_gate_up,
+                                                    (uint4 *)w_gate_up_packed, s.N, 2 * s.I, s.H,
+                                                    s.I);
+    pack_weights_kernel<false><<<4096, 256, 0, st>>>((const uint4 *)w_down, (uint4 *)w_down_packed,
+                                                     s.N, s.H, s.I, s.I);
     return hipGetLastError();
 }
 

@@ -32,9 +32,19 @@ def upload(cfg, d):
     return g
 
 
-def shape_of(cfg, T=None):
+def shape_of(cfg, T=None, packed: bool = False):
     return binding.make_shape(cfg.T if T is None else T, cfg.H, cfg.N, cfg.K, cfg.I,
-                              binding.BEAM_BF16 if cfg.dtype == "bf16" else binding.BEAM_F32)
+                              binding.BEAM_BF16 if cfg.dtype == "bf16" else binding.BEAM_F32,
+                              binding.BEAM_WEIGHTS_PACKED if packed else binding.BEAM_WEIGHTS_PLAIN)
+
+
+def pack_weights(cfg, w_gate_up, w_down):
+    """One-time repack of plain expert weights into matrix-core fragment order."""
+    s = shape_of(cfg, packed=False)
+    pg = torch.empty_like(w_gate_up)
+    pd = torch.empty_like(w_down)
+    binding.beam_pack_weights(s, w_gate_up, w_down, pg, pd, stream_ptr())
+    return pg, pd
 
 
 def workspace(shape):

@@ -10,8 +10,8 @@ import torch
 import oracle
 import paper_2605_14438_amd as beam
 from paper_2605_14438_amd import synth
-from paper_2605_14438_amd.runtime import (dev, dev_f32, out_tensor, shape_of, stream_ptr,  # noqa: F401
-                                         upload, workspace)
+from paper_2605_14438_amd.runtime import (dev, dev_f32, out_tensor, pack_weights,  # noqa: F401
+                                         shape_of, stream_ptr, upload, workspace)
 
 # Any routing / mask decision closer than this (in logit units) could flip
 # under a different fp32 summation order; such tokens are redrawn.  fp32
@@ -48,10 +48,14 @@ def make_tie_free(cfg, sweep: int = 0, with_experts: bool = True, max_rounds: in
     return d
 
 
-def forward(cfg, g, T=None):
-    """beam_moe_forward with all optional outputs; returns host arrays."""
+def forward(cfg, g, T=None, packed=False):
+    """beam_moe_forward with all optional outputs; returns host arrays.  With
+    packed=True the expert weights are first repacked by beam_pack_weights."""
     T = cfg.T if T is None else T
-    s = shape_of(cfg, T)
+    s = shape_of(cfg, T, packed=packed)
+    if packed:
+        pg, pd = pack_weights(cfg, g["w_gate_up"], g["w_down"])
+        g = {**g, "w_gate_up": pg, "w_down": pd}
     ws, nb = workspace(s)
     out = out_tensor(cfg, T)
     ids = torch.full((T, cfg.K), -7, dtype=torch.int32, device="cuda")

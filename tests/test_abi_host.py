@@ -66,6 +66,9 @@ def test_workspace_bytes(lib):
     ((4, 256, 8, 0, 512, 0), binding.BEAM_ERR_INVALID_ARG),
     ((4, 256, 8, 9, 512, 0), binding.BEAM_ERR_INVALID_ARG),
     ((4, 256, 8, 2, 512, 7), binding.BEAM_ERR_INVALID_ARG),
+    ((4, 256, 8, 2, 512, 1, 5), binding.BEAM_ERR_INVALID_ARG),       # unknown weight layout
+    ((4, 256, 8, 2, 512, 0, 1), binding.BEAM_ERR_UNSUPPORTED),       # packed needs bf16
+    ((4, 320, 8, 2, 512, 1, 1), binding.BEAM_ERR_UNSUPPORTED),       # packed needs H % 256 == 0
     ((4, 250, 8, 2, 512, 0), binding.BEAM_ERR_UNSUPPORTED),
     ((4, 256, 300, 2, 512, 0), binding.BEAM_ERR_UNSUPPORTED),
     ((4, 256, 8, 2, 511, 1), binding.BEAM_ERR_UNSUPPORTED),
@@ -107,6 +110,18 @@ def test_null_misaligned_and_small_workspace(lib):
                                 check=False) == binding.BEAM_ERR_INVALID_ARG
     with pytest.raises(beam.BeamError):
         beam.beam_combine(s, None, ok, ok, ok, ok)
+
+
+def test_pack_weights_argument_checks(lib):
+    ok = 0x1000
+    s = beam.make_shape(0, 256, 8, 2, 512, beam.BEAM_BF16)
+    assert beam.beam_pack_weights(s, ok, ok, None, ok + 0x100, check=False) == \
+        binding.BEAM_ERR_INVALID_ARG
+    assert beam.beam_pack_weights(s, ok, ok, ok, ok, check=False) == binding.BEAM_ERR_INVALID_ARG
+    s32 = beam.make_shape(0, 256, 8, 2, 512, beam.BEAM_F32)
+    assert beam.beam_pack_weights(s32, ok, ok, ok + 0x100, ok + 0x200, check=False) == \
+        binding.BEAM_ERR_UNSUPPORTED
+    assert beam.beam_abi_version() == 2
 
 
 def test_zero_tokens_is_ok_without_launch(lib):

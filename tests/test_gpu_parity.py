@@ -174,16 +174,58 @@ FFN_CASES = [
 ]
 
 
-@pytest.mark.parametrize("cfg", FFN_CASES, ids=lambda c: f"{c.name}-T{c.T}-keep{c.keep}")
-def test_expert_ffn_and_combine(cfg):
-    _log(f"expert_ffn {cfg}")
+def _packable(cfg):
+    return cfg.dtype == "bf16" and cfg.H % 256 == 0 and cfg.I % 128 == 0
+
+
+FFN_PARAMS = [(c, False) for c in FFN_CASES] + [(c, True) for c in FFN_CASES if _packable(c)]
+
+
+def test_pack_weights_is_the_documented_permutation():
+    """beam_pack_weights against the layout written down in beam.h, bit for bit."""
+    cfg = synth.LayerConfig("pack", 1, T=1, H=256, N=3, K=1, I=128, dtype="bf16", keep=1.0)
+    d = synth.make_layer(cfg)
+    g = hp.upload(cfg, d)
+    pg, pd = hp.pack_weights(cfg, g["w_gate_up"], g["w_down"])
+    torch.cuda.synchronize()
+
+    def expect(w, gate_up):
+        n, rows, kd = w.shape
+        out = np.empty(n * rows * kd, dtype=w.dtype)
+        pos = 0
+        for e in range(n):
+            for rb in range(rows // 32):
+                if gate_up:
+                    base = (rb // 2) * 32 + (cfg.I if rb % 2 else 0)
+                else:
+                    base = rb * 32
+                for ks in range(kd // 16):
+                    blk = w[e, base:base + 32, ks * 16:ks * 16 + 16]        # [32 rows, 16 k]
+                    # lane l = (row l & 31, k half l >> 5), 8 values each
+                    out[pos:pos + 512] = blk.reshape(32, 2, 8).transpose(1, 0, 2).reshape(-1)
+                    pos += 512
+        return out
+
+    got_g = pg.view(torch.int16).cpu().numpy().view(np.uint16).reshape(-1)
+    got_d = pd.view(torch.int16).cpu().numpy().view(np.uint16).reshape(-1)
+    assert np.array_equal(got_g, expect(synth.bf16_bits(d["w_gate_up"]), True))
+    assert np.array_equal(got_d, expect(synth.bf16_bits(d["w_down"]), False))
+
+
+@pytest.mark.parametrize("cfg,packed", FFN_PARAMS,
+                         ids=lambda v: f"{v.name}-T{v.T}-keep{v.keep}" if hasattr(v, "name")
+                         else ("packed" if v else "plain"))
+def test_expert_ffn_and_combine(cfg, packed):
+    _log(f"expert_ffn packed={packed} {cfg}")
     d = hp.make_tie_free(cfg)
     ids_o, g_o, msk_o = oracle.route_mask(d["router_logits"], d["mask_logits"], cfg.K)
     counts, offsets, perm, inv, P = oracle.permute(msk_o, cfg.N)
     y_slots, evals = oracle.pair_outputs(d["x"], d["w_gate_up"], d["w_down"], msk_o)
     assert evals == P
     g = hp.upload(cfg, d)
-    s = hp.shape_of(cfg)
+    s = hp.shape_of(cfg, packed=packed)
+    if packed:
+        g["w_gate_up"], g["w_down"] = hp.pack_weights(cfg, g["w_gate_up"], g["w_down"])
     ws, nb = hp.workspace(s)
     TK = cfg.T * cfg.K
     y_pairs = torch.full((TK, cfg.H), float("nan"), dtype=torch.float32, device="cuda")
@@ -260,6 +302,9 @@ def test_moe_forward_small(cfg):
                              d["w_gate_up"], d["w_down"], cfg.K)
     res = hp.forward(cfg, hp.upload(cfg, d))
     _check_forward(cfg, d, res, ref)
+    if _packable(cfg):
+        res_p = hp.forward(cfg, hp.upload(cfg, d), packed=True)
+        _check_forward(cfg, d, res_p, ref)
     if cfg.keep == 0.0:
         assert res["num_pairs"] == 0 and (res["out"] == 0).all()
 
