@@ -31,11 +31,10 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) {
     return __uint_as_float(((uint32_t)v) << 16);
 }
-// Round-to-nearest-even; inputs are finite.
+// Round-to-nearest-even (gfx950 has a hardware conversion; the compiler emits
+// it for the __bf16 cast).
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+    return __builtin_bit_cast(bf16_t, (__bf16)f);
 }
 
 __device__ __forceinline__ float load_f32(const float *p) { return *p; }
@@ -43,7 +42,12 @@ __device__ __forceinline__ float load_f32(const bf16_t *p) { return bf16_to_f32(
 __device__ __forceinline__ void store_from_f32(float *p, float v) { *p = v; }
 __device__ __forceinline__ void store_from_f32(bf16_t *p, float v) { *p = f32_to_bf16(v); }
 
-__device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g)); }
+// SiLU with the hardware exponential and reciprocal (about 1 ulp each) instead
+// of an IEEE division: the result is rounded to bf16 (8 bits) right after, and a
+// GEMM epilogue evaluates 128 of these per lane.
+__device__ __forceinline__ float silu(float g) {
+    return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g));
+}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -46,8 +46,12 @@
 // on an XCD share their A tile and their expert's weights through that XCD's
 // L2 instead of each pulling them from HBM.
 //
-// v_mfma_f32_32x32x16_bf16 layouts (wave64): A/B lane l -> row/col l & 31;
-// D register r of lane l -> row 8*(r >> 2) + 4*(l >> 5) + (r & 3), col l & 31.
+// v_mfma_f32_32x32x16_bf16 layouts (wave64): A/B lane l -> row/col l & 31,
+// k = 8*(l >> 5)..+7; D register r of lane l -> row 8*(r >> 2) + 4*(l >> 5) +
+// (r & 3), col l & 31.  In the gate/up GEMM the weights are passed as the MFMA
+// "A" operand (result rows = output features) and the activations as "B" (result
+// columns = grouped rows), so a lane ends up with runs of four consecutive
+// features of one row; the down GEMM passes them the other way round.
 #include <type_traits>
 
 #include "common.hpp"
@@ -190,9 +194,16 @@ __global__ __launch_bounds__(256) void ffn_tile_kernel(
                 for (int m = 0; m < GH; ++m)
 #pragma unroll
                     for (int n = 0; n < WTN; ++n)
-                        acc[g * GH + m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, af[hs & 1][m]),
-                            __builtin_bit_cast(bf16x8, bq[n][j]), acc[g * GH + m][n], 0, 0, 0);
+                        if constexpr (GATE_UP)
+                            acc[g * GH + m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                __builtin_bit_cast(bf16x8, bq[n][j]),
+                                __builtin_bit_cast(bf16x8, af[hs & 1][m]), acc[g * GH + m][n], 0,
+                                0, 0);
+                        else
+                            acc[g * GH + m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                __builtin_bit_cast(bf16x8, af[hs & 1][m]),
+                                __builtin_bit_cast(bf16x8, bq[n][j]), acc[g * GH + m][n], 0, 0,
+                                0);
                 if constexpr (PF) {
                     if (g == 1) {
 #pragma unroll
@@ -218,9 +229,11 @@ __global__ __launch_bounds__(256) void ffn_tile_kernel(
             BEAM_LSTORE_A(st ^ 1)
             // The order the scheduler is to build for this K-step (left alone it
             // sinks every load to just before its first use to save registers):
-            // activation loads first, then per k-step the LDS fragment reads, the
-            // MFMAs and the refill of the weight registers they consumed, and the
-            // LDS stores of the next activation tile last.
+            // activation loads first; then per half k-step the MFMAs, the refill of
+            // the weight registers they consumed and the LDS fragment reads of the
+            // next half; the LDS stores of the next activation tile are spread over
+            // the last four half-steps, so the matrix cores keep running while the
+            // (half-rate) LDS writes drain instead of idling through a store phase.
             __builtin_amdgcn_sched_group_barrier(0x020, AP, 0);            // VMEM read
             __builtin_amdgcn_sched_group_barrier(0x100, 2 * GH, 0);        // DS read
 #pragma unroll
@@ -228,34 +241,55 @@ __global__ __launch_bounds__(256) void ffn_tile_kernel(
                 __builtin_amdgcn_sched_group_barrier(0x008, GH * WTN, 0);  // MFMA
                 if (hs & 1) __builtin_amdgcn_sched_group_barrier(0x020, WTN, 0);  // refill
                 if (hs < 2 * KS - 2) __builtin_amdgcn_sched_group_barrier(0x100, GH, 0);
+                if (hs >= 2 * KS - 4) __builtin_amdgcn_sched_group_barrier(0x200, AP / 4, 0);
             }
-            __builtin_amdgcn_sched_group_barrier(0x200, AP, 0);            // DS write
             __syncthreads();
         }
         compute((nk - 1) & 1, std::false_type{}, 0);
 
-        // epilogue
+        // Epilogue.
+        if constexpr (GATE_UP) {
+            // The weights were the MFMA A operand and the activations the B operand,
+            // so in a 32x32 result tile lane l holds activation row l & 31 and, in
+            // registers 4q..4q+3, the four consecutive features 8q + 4*(l >> 5) +
+            // 0..3: one row pointer per tile, SiLU(gate)*up in registers, 8-byte
+            // stores of four bf16.
 #pragma unroll
-        for (int m = 0; m < WTM; ++m) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int trow = wm * (BM / WM) + m * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
-                const int grow = row0 + trow;
+            for (int m = 0; m < WTM; ++m) {
+                const int grow = row0 + wm * (BM / WM) + m * 32 + l32;
                 if (grow >= row_end) continue;
-                if constexpr (GATE_UP) {
+                bf16_t *orow = hidden_out + (size_t)grow * I + n0 + kh * 4;
 #pragma unroll
-                    for (int q = 0; q < WTN / 2; ++q) {
-                        const int nb = wn * WTN + 2 * q;
-                        const int feat = n0 + (nb >> 1) * 32 + l32;
-                        const float hv = silu(acc[m][2 * q][r]) * acc[m][2 * q + 1][r];
-                        hidden_out[(size_t)grow * I + feat] = f32_to_bf16(hv);
-                    }
-                } else {
+                for (int q = 0; q < WTN / 2; ++q) {
+                    const int nb = wn * WTN + 2 * q;
 #pragma unroll
-                    for (int n = 0; n < WTN; ++n) {
-                        const int c = n0 + (wn * WTN + n) * 32 + l32;
-                        y_out[(size_t)grow * H + c] = acc[m][n][r];
+                    for (int rg = 0; rg < 4; ++rg) {
+                        uint32_t pk[2];
+#pragma unroll
+                        for (int h2 = 0; h2 < 2; ++h2) {
+                            const int r = rg * 4 + h2 * 2;
+                            const float v0 = silu(acc[m][2 * q][r]) * acc[m][2 * q + 1][r];
+                            const float v1 = silu(acc[m][2 * q][r + 1]) * acc[m][2 * q + 1][r + 1];
+                            pk[h2] = (uint32_t)f32_to_bf16(v0) | ((uint32_t)f32_to_bf16(v1) << 16);
+                        }
+                        *(uint2 *)(orow + (nb >> 1) * 32 + rg * 8) = make_uint2(pk[0], pk[1]);
                     }
+                }
+            }
+        } else {
+            // Activations were the A operand: register r of lane l is row
+            // 8*(r >> 2) + 4*(l >> 5) + (r & 3), column l & 31 of the tile, so each
+            // store instruction writes two full 128-byte row segments of fp32.
+#pragma unroll
+            for (int m = 0; m < WTM; ++m) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int trow = wm * (BM / WM) + m * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
+                    const int grow = row0 + trow;
+                    if (grow >= row_end) continue;
+                    float *orow = y_out + (size_t)grow * H + n0 + l32;
+#pragma unroll
+                    for (int n = 0; n < WTN; ++n) orow[(wn * WTN + n) * 32] = acc[m][n][r];
                 }
             }
         }
