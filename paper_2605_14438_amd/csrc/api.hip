@@ -38,15 +38,17 @@ WsLayout ws_layout(const beam_shape &s) {
     const size_t esz = s.dtype == BEAM_BF16 ? 2 : 4;
     L.nchunk = (int)((TK + kChunk - 1) / kChunk);
     if (L.nchunk < 1) L.nchunk = 1;
-    L.max_tiles = (int)(TK / kTileMMin + N);
+    L.max_tiles = (int)(TK / kTileMMin + 2 * N);
     size_t off = 0;
     auto take = [&](size_t bytes) {
         const size_t at = off;
         off = align_up(off + bytes);
         return at;
     };
-    L.router_logits = take(T * N * 4);
-    L.mask_logits = take(T * N * 4);
+    // one allocation: the prefill logits kernel writes them as a single [T,2N] array
+    L.router_logits = take(2 * T * N * 4);
+    L.mask_logits = L.router_logits + T * N * 4;
+    L.packed_heads = take(2 * N * (size_t)s.H * esz);
     L.topk_ids = take(TK * 4);
     L.topk_w = take(TK * 4);
     L.masked_ids = take(TK * 4);
@@ -192,7 +194,8 @@ beam_status beam_route_mask(const beam_shape *shape, const void *x, const void *
     float *ml = mask_logits_dbg ? mask_logits_dbg : (float *)(ws + L.mask_logits);
     hipStream_t stream = (hipStream_t)hip_stream;
     BEAM_TRY_HIP(launch_logits(s, x, w_router, router_bias, w_mask, mask_bias, rl, ml, stream));
-    BEAM_TRY_HIP(launch_topk_mask(s, rl, ml, topk_ids, topk_weights, masked_ids, stream));
+    BEAM_TRY_HIP(launch_topk_mask(s, rl, ml, nullptr, nullptr, s.N, topk_ids, topk_weights,
+                                  masked_ids, stream));
     return BEAM_OK;
 }
 
@@ -296,9 +299,17 @@ static beam_status moe_forward_impl(const beam_shape *shape, const void *x, cons
         if (ev) BEAM_TRY_HIP(hipEventRecord(ev[i], stream));    \
     } while (0)
     BEAM_STAGE_MARK(0);
-    BEAM_TRY_HIP(launch_logits(s, x, w_router, router_bias, w_mask, mask_bias, rl, ml, stream));
-    BEAM_STAGE_MARK(1);
-    BEAM_TRY_HIP(launch_topk_mask(s, rl, ml, ids, gw, mids, stream));
+    if (logits_tiled_supported(s)) {
+        // prefill: both heads as one tiled GEMM into a [T,2N] array; biases join at Top-K
+        BEAM_TRY_HIP(launch_logits_tiled(s, x, w_router, w_mask, ws + L.packed_heads, rl, stream));
+        BEAM_STAGE_MARK(1);
+        BEAM_TRY_HIP(launch_topk_mask(s, rl, rl + s.N, router_bias, mask_bias, 2 * s.N, ids, gw,
+                                      mids, stream));
+    } else {
+        BEAM_TRY_HIP(launch_logits(s, x, w_router, router_bias, w_mask, mask_bias, rl, ml, stream));
+        BEAM_STAGE_MARK(1);
+        BEAM_TRY_HIP(launch_topk_mask(s, rl, ml, nullptr, nullptr, s.N, ids, gw, mids, stream));
+    }
     BEAM_STAGE_MARK(2);
     BEAM_TRY_HIP(launch_permute(s, mids, counts, offsets, perm, inv, np,
                                 (int32_t *)(ws + L.blk_counts), (int32_t *)(ws + L.blk_base),

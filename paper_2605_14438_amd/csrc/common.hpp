@@ -18,10 +18,17 @@ constexpr int kGroupsPerChunk = 8;
 constexpr int kChunk = kWave * kGroupsPerChunk;
 
 // Smallest row tile of the prefill grouped GEMM (it bounds the length of the
-// tile list).  Every expert segment is cut into tiles of WorkList::tile_m
-// grouped rows: the paper's "block alignment" (App. A.4), done with a tile list
-// instead of padding the index array.
+// tile list).  Every expert segment is cut into row tiles: the paper's "block
+// alignment" (App. A.4), done with a tile list instead of padding the index
+// array.
 constexpr int kTileMMin = 128;
+
+// Tiles an expert segment of `count` rows is cut into.
+__host__ __device__ inline void tile_split(int count, int tile_m, int *nbig, int *nsmall) {
+    const int b = tile_m == 256 ? count >> 8 : 0;
+    *nbig = b;
+    *nsmall = (count - (b << 8) + kTileMMin - 1) / kTileMMin;
+}
 
 typedef uint16_t bf16_t;
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -58,7 +65,8 @@ __device__ __forceinline__ float wave_sum(float v) {
 // Device workspace carve-up.  Every offset is a multiple of 256 bytes.
 struct WsLayout {
     size_t router_logits;  // [T,N] f32
-    size_t mask_logits;    // [T,N] f32
+    size_t mask_logits;    // [T,N] f32 (router_logits and mask_logits are contiguous)
+    size_t packed_heads;   // [2N,H] dtype : router and mask heads in MFMA fragment order
     size_t topk_ids;       // [T,K] i32
     size_t topk_w;         // [T,K] f32
     size_t masked_ids;     // [T,K] i32
@@ -80,7 +88,11 @@ WsLayout ws_layout(const beam_shape &s);
 
 // Work list written on the device after the prefix sums:
 //   hdr[0] = number of experts with at least one kept pair (U)
-//   hdr[1] = number of row tiles of tile_m grouped rows
+//   hdr[1] = number of 256-row tiles, hdr[2] = number of 128-row tiles.  With
+//            tile_m == 256 an expert segment of c rows gives c / 256 big tiles
+//            and its remainder one or two small ones (so at most 127 padded
+//            rows per expert); with tile_m == 128 only small tiles.  The big
+//            tiles come first in the list: longest jobs first.
 //   active[u]      expert id of the u-th non-empty expert (ascending)
 //   active_beg[u], active_end[u]  its grouped rows [beg, end)
 //   tile_expert[i] expert of row tile i,  tile_row0[i] its first grouped row
@@ -93,7 +105,7 @@ struct WorkList {
     int32_t *active_end;
     int32_t *tile_expert;
     int32_t *tile_row0;
-    int32_t tile_m;  // rows per tile, chosen on the host from the shape
+    int32_t tile_m;  // 256: big and small tiles, 128: small only; chosen on the host
 };
 WorkList work_list(void *base, const beam_shape &s, int max_tiles);
 int ffn_tile_m(const beam_shape &s);
@@ -103,8 +115,13 @@ hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_route
                          const float *b_router, const void *w_mask, const float *b_mask,
                          float *router_logits, float *mask_logits, hipStream_t st);
 hipError_t launch_topk_mask(const beam_shape &s, const float *router_logits,
-                            const float *mask_logits, int32_t *topk_ids, float *topk_w,
-                            int32_t *masked_ids, hipStream_t st);
+                            const float *mask_logits, const float *b_router, const float *b_mask,
+                            int row_stride, int32_t *topk_ids, float *topk_w, int32_t *masked_ids,
+                            hipStream_t st);
+bool logits_tiled_supported(const beam_shape &s);
+hipError_t launch_logits_tiled(const beam_shape &s, const void *x, const void *w_router,
+                               const void *w_mask, void *packed_heads, float *logits2,
+                               hipStream_t st);
 hipError_t launch_permute(const beam_shape &s, const int32_t *masked_ids, int32_t *counts,
                           int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *num_pairs,
                           int32_t *blk_counts, int32_t *blk_base, int nchunk, const WorkList &wl,

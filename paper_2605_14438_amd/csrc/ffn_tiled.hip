@@ -39,12 +39,15 @@
 //   at roughly half the speed of the packed one.
 //
 // Work order.  Workgroups are handed to the 8 XCDs round-robin by linear id,
-// and each XCD has its own L2.  The grid is persistent (one workgroup per CU);
-// workgroup b serves XCD b % 8 and walks items (b % 8) * ceil(W/8) + b/8,
-// + 32, ...: every XCD owns one contiguous eighth of the (expert, row tile,
-// column tile) list, column tile fastest, so the workgroups that run together
-// on an XCD share their A tile and their expert's weights through that XCD's
-// L2 instead of each pulling them from HBM.
+// and each XCD has its own L2.  The grid is persistent: 256 workgroups, one per
+// CU, workgroup b on XCD b % 8 as its member b / 8.  The work list of (expert,
+// row tile, column tile) items, column tile fastest, is cut into chunks of 32
+// consecutive items; chunk c goes to XCD c % 8, one item per CU.  So the 32
+// workgroups that run together on an XCD hold about five row tiles of one expert
+// times all its column tiles and share their A tiles and that expert's weights
+// through the XCD's L2 instead of each pulling them from HBM, while the chunks
+// deal the work evenly over the XCDs.  256-row tiles come first in the list,
+// the 128-row remainder tiles last (longest jobs first).
 //
 // v_mfma_f32_32x32x16_bf16 layouts (wave64): A/B lane l -> row/col l & 31,
 // k = 8*(l >> 5)..+7; D register r of lane l -> row 8*(r >> 2) + 4*(l >> 5) +
@@ -59,18 +62,21 @@
 namespace beam {
 
 constexpr int kTileN = 256;
+// wavefront grid inside a workgroup: 1 x 4 (each weight fragment is loaded by exactly one wavefront)
+constexpr int kWavesM = 1;
+// MFMA k-steps per K-step of the main loop
+constexpr int kKSteps = 8;
 
 // KS = MFMA k-steps (16 reduction indices each) per K-step of the main loop: one
 // K-step is the prefetch distance, and at full MFMA rate a 256 x 256 x 64 step
 // lasts about 1 us, half an HBM round trip under load, so KS = 8 (K-step 128).
+// One BM x 256 output tile: rows [row0, min(row0 + BM, row_end)) of expert e,
+// column tile col_tile.  As: 2 * BM * 2 * KS uint4 of LDS.
 template <int BM, int WM, int KS, bool GATE_UP, bool PACKED>
-__global__ __launch_bounds__(256) void ffn_tile_kernel(
-    const bf16_t *__restrict__ a_src,   // GATE_UP: x [T,H];  DOWN: hidden [P,I]
-    const bf16_t *__restrict__ w,       // GATE_UP: w_gate_up [N,2I,H];  DOWN: w_down [N,H,I]
-    const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm,
-    const int32_t *__restrict__ wl_hdr, const int32_t *__restrict__ tile_expert,
-    const int32_t *__restrict__ tile_row0, bf16_t *__restrict__ hidden_out,
-    float *__restrict__ y_out, int H, int K, int I, int n_col_tiles) {
+__device__ __forceinline__ void ffn_tile_body(
+    uint4 *As, const bf16_t *__restrict__ a_src, const bf16_t *__restrict__ w,
+    const int32_t *__restrict__ perm, bf16_t *__restrict__ hidden_out, float *__restrict__ y_out,
+    int H, int K, int I, int e, int row0, int row_end, int col_tile) {
     constexpr int PR = 2 * KS;           // 16-byte pieces per LDS row (K-step of 16*KS indices)
     constexpr int RPP = 256 / PR;        // tile rows copied per pass of the 256 threads
     constexpr int AP = BM / RPP;         // A rows per thread
@@ -78,7 +84,7 @@ __global__ __launch_bounds__(256) void ffn_tile_kernel(
     constexpr int WTM = BM / WM / 32;    // MFMA row tiles per wavefront
     constexpr int WTN = 8 / WN;          // MFMA column tiles per wavefront (256 columns in all)
     static_assert(WM == 1 || WM == 2, "wavefront grid is 1x4 or 2x2");
-    __shared__ uint4 As[2][BM * PR];
+    constexpr int kStage = BM * PR;      // uint4 per LDS stage
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -92,19 +98,7 @@ __global__ __launch_bounds__(256) void ffn_tile_kernel(
     const int kdim = GATE_UP ? H : I;
     const int nk = kdim / (16 * KS);
 
-    const int n_work = wl_hdr[1] * n_col_tiles;
-    const int per_xcd = (n_work + 7) >> 3;
-    const int xcd = blockIdx.x & 7;
-    const int n_local = gridDim.x >> 3;
-
-    for (int slot = blockIdx.x >> 3; slot < per_xcd; slot += n_local) {
-        const int work = xcd * per_xcd + slot;
-        if (work >= n_work) break;
-        const int tile = work / n_col_tiles;
-        const int col_tile = work - tile * n_col_tiles;
-        const int e = tile_expert[tile];
-        const int row0 = tile_row0[tile];
-        const int row_end = offsets[e + 1];
+    {
         const int n0 = col_tile * (GATE_UP ? kTileN / 2 : kTileN);
 
         // element offsets of this thread's A rows (32 bits: T*H and T*K*I < 2^32,
@@ -159,7 +153,7 @@ __global__ __launch_bounds__(256) void ffn_tile_kernel(
 #define BEAM_LSTORE_A(st)                                                        \
     _Pragma("unroll") for (int p = 0; p < AP; ++p) {                             \
         const int r_ = lr + p * RPP;                                             \
-        As[st][r_ * PR + (piece ^ (r_ & 7))] = ra[p];                            \
+        As[(st) * kStage + r_ * PR + (piece ^ (r_ & 7))] = ra[p];                            \
     }
         // One K-step out of LDS stage st.  The weight registers are a single
         // buffer refilled on a rolling basis: as soon as the MFMAs of k-step j
@@ -178,7 +172,7 @@ __global__ __launch_bounds__(256) void ffn_tile_kernel(
 #pragma unroll
             for (int m = 0; m < GH; ++m) {
                 const int r = wm * (BM / WM) + (g * GH + m) * 32 + l32;
-                af[m] = As[st][r * PR + (pc ^ (r & 7))];
+                af[m] = As[st * kStage + r * PR + (pc ^ (r & 7))];
             }
         };
         auto compute = [&](int st, auto prefetch, int kt_next) {
@@ -299,6 +293,39 @@ __global__ __launch_bounds__(256) void ffn_tile_kernel(
 #undef BEAM_LSTORE_A
 }
 
+
+// Persistent kernel over the work list.  BIG: the list holds 256-row tiles
+// (first) and 128-row tiles; otherwise only 128-row tiles.
+template <bool BIG, int WM, int KS, bool GATE_UP, bool PACKED>
+__global__ __launch_bounds__(256) void ffn_tile_kernel(
+    const bf16_t *__restrict__ a_src,   // GATE_UP: x [T,H];  DOWN: hidden [P,I]
+    const bf16_t *__restrict__ w,       // GATE_UP: w_gate_up [N,2I,H];  DOWN: w_down [N,H,I]
+    const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm,
+    const int32_t *__restrict__ wl_hdr, const int32_t *__restrict__ tile_expert,
+    const int32_t *__restrict__ tile_row0, bf16_t *__restrict__ hidden_out,
+    float *__restrict__ y_out, int H, int K, int I, int n_col_tiles) {
+    __shared__ uint4 As[2 * (BIG ? 256 : 128) * 2 * KS];
+    const int n_big = BIG ? wl_hdr[1] : 0;
+    const int n_work = (n_big + wl_hdr[2]) * n_col_tiles;
+    const int xcd = blockIdx.x & 7;
+    const int member = blockIdx.x >> 3;  // 0..31: the grid is 256 workgroups
+    for (int round = 0;; ++round) {
+        const int item = (round * 8 + xcd) * 32 + member;
+        if (item >= n_work) break;       // uniform over the workgroup
+        const int tile = item / n_col_tiles;
+        const int col_tile = item - tile * n_col_tiles;
+        const int e = tile_expert[tile];
+        const int row0 = tile_row0[tile];
+        const int row_end = offsets[e + 1];
+        if (BIG && tile < n_big)
+            ffn_tile_body<256, WM, KS, GATE_UP, PACKED>(As, a_src, w, perm, hidden_out, y_out, H, K,
+                                                        I, e, row0, row_end, col_tile);
+        else
+            ffn_tile_body<128, WM, KS, GATE_UP, PACKED>(As, a_src, w, perm, hidden_out, y_out, H, K,
+                                                        I, e, row0, row_end, col_tile);
+    }
+}
+
 // Row-tile size for a shape, decided on the host from the worst-case average
 // segment length (the host never learns the real counts).
 int ffn_tile_m(const beam_shape &s) { return ((long)s.T * s.K >= 512L * s.N) ? 256 : 128; }
@@ -310,9 +337,6 @@ bool tiled_ffn_supported(const beam_shape &s) {
 
 // one persistent workgroup per CU (256 CUs in 8 XCDs)
 constexpr int kPersistentGrid = 256;
-// wavefront grid inside a workgroup: 1 x 4 (each weight fragment is loaded by exactly one wavefront)
-constexpr int kWavesM = 1;
-constexpr int kKSteps = 8;
 
 template <bool GATE_UP>
 static void launch_tile(const beam_shape &s, const bf16_t *a, const bf16_t *w,
@@ -320,13 +344,13 @@ static void launch_tile(const beam_shape &s, const bf16_t *a, const bf16_t *w,
                         bf16_t *hidden, float *y, int nct, hipStream_t st) {
     const bool packed = s.weight_layout == BEAM_WEIGHTS_PACKED;
     const bool big = ffn_tile_m(s) == 256;
-#define BEAM_LAUNCH_TILE(BM, PK)                                                               \
-    ffn_tile_kernel<BM, kWavesM, kKSteps, GATE_UP, PK><<<kPersistentGrid, 256, 0, st>>>(                \
+#define BEAM_LAUNCH_TILE(BIG, PK)                                                              \
+    ffn_tile_kernel<BIG, kWavesM, kKSteps, GATE_UP, PK><<<kPersistentGrid, 256, 0, st>>>(      \
         a, w, offsets, perm, wl.hdr, wl.tile_expert, wl.tile_row0, hidden, y, s.H, s.K, s.I, nct)
-    if (big && packed) BEAM_LAUNCH_TILE(256, true);
-    else if (big) BEAM_LAUNCH_TILE(256, false);
-    else if (packed) BEAM_LAUNCH_TILE(128, true);
-    else BEAM_LAUNCH_TILE(128, false);
+    if (big && packed) BEAM_LAUNCH_TILE(true, true);
+    else if (big) BEAM_LAUNCH_TILE(true, false);
+    else if (packed) BEAM_LAUNCH_TILE(false, true);
+    else BEAM_LAUNCH_TILE(false, false);
 #undef BEAM_LAUNCH_TILE
 }
 
@@ -343,6 +367,65 @@ hipError_t launch_down_tiled(const beam_shape &s, const void *hidden, const void
                              hipStream_t st) {
     launch_tile<false>(s, (const bf16_t *)hidden, (const bf16_t *)w_down, offsets, nullptr, wl,
                        nullptr, y_pairs, s.H / kTileN, st);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Router and mask heads for prefill batches (paper Sec. 3.2 Step 1, Eq. 5): the
+// [T,H] x [H,2N] product is the same problem as a down GEMM of one "expert" with
+// 2N output features, so it runs on the tile body above: x tiles through LDS,
+// the 2N head rows, repacked into fragment order at every call (they are 1 MB;
+// the caller's layout stays plain), straight into the MFMA registers.  Output:
+// fp32 [T,2N], router columns first.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pack_heads_kernel(const uint4 *__restrict__ w_router,
+                                                         const uint4 *__restrict__ w_mask,
+                                                         uint4 *__restrict__ dst, int N, int H) {
+    const int ksteps = H >> 4;
+    const int total = 2 * N * (H >> 3);
+    for (int o = blockIdx.x * 256 + threadIdx.x; o < total; o += gridDim.x * 256) {
+        const int l = o & 63;
+        const int frag = o >> 6;
+        const int ks = frag % ksteps;
+        const int rb = frag / ksteps;
+        const int row = rb * 32 + (l & 31);
+        const uint4 *src = row < N ? w_router + (size_t)row * (H >> 3)
+                                   : w_mask + (size_t)(row - N) * (H >> 3);
+        dst[o] = src[ks * 2 + (l >> 5)];
+    }
+}
+
+__global__ __launch_bounds__(256) void logits_tile_kernel(const bf16_t *__restrict__ x,
+                                                          const bf16_t *__restrict__ packed_heads,
+                                                          float *__restrict__ logits2, int Tn,
+                                                          int H, int N2) {
+    __shared__ uint4 As[2 * 128 * 2 * kKSteps];
+    const int nct = N2 / kTileN;
+    const int n_work = ((Tn + 127) / 128) * nct;
+    for (int item = blockIdx.x; item < n_work; item += gridDim.x) {
+        const int tile = item / nct;
+        const int col_tile = item - tile * nct;
+        // down-GEMM roles: output width N2, reduction length H, a single expert
+        ffn_tile_body<128, kWavesM, kKSteps, false, true>(As, x, packed_heads, nullptr, nullptr,
+                                                          logits2, N2, 1, H, 0, tile * 128, Tn,
+                                                          col_tile);
+    }
+}
+
+bool logits_tiled_supported(const beam_shape &s) {
+    return s.dtype == BEAM_BF16 && s.T >= 1024 && s.H % 256 == 0 && (2 * s.N) % kTileN == 0 &&
+           (long)s.T * s.H < (1L << 32);
+}
+
+hipError_t launch_logits_tiled(const beam_shape &s, const void *x, const void *w_router,
+                               const void *w_mask, void *packed_heads, float *logits2,
+                               hipStream_t st) {
+    pack_heads_kernel<<<256, 256, 0, st>>>((const uint4 *)w_router, (const uint4 *)w_mask,
+                                           (uint4 *)packed_heads, s.N, s.H);
+    const int n_work = ((s.T + 127) / 128) * (2 * s.N / kTileN);
+    const int grid = n_work < 1024 ? n_work : 1024;
+    logits_tile_kernel<<<grid, 256, 0, st>>>((const bf16_t *)x, (const bf16_t *)packed_heads,
+                                             logits2, s.T, s.H, 2 * s.N);
     return hipGetLastError();
 }
 

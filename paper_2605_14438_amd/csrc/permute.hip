@@ -2,8 +2,9 @@
 // equal to -1 are skipped when tokens are grouped by expert).  A stable
 // counting sort of the flat pair index f = t*K+k by expert id:
 //   1. count    per chunk of kChunk pairs, an LDS histogram over experts
-//   2. scan     per expert, exclusive prefix over chunks; then exclusive prefix
-//               over experts; plus the work list the FFN kernels walk
+//   2. scan     per expert, exclusive prefix over chunks (one workgroup per
+//               expert); then exclusive prefix over experts plus the work list
+//               the FFN kernels walk (one workgroup)
 //   3. scatter  every chunk re-reads its ids and places each kept pair at
 //               offset[e] + base[chunk][e] + (rank among equal ids so far)
 // Placement uses only prefix sums and wavefront ballots, never atomics on the
@@ -26,19 +27,22 @@ __device__ __forceinline__ uint64_t match_id(int id, bool valid) {
     return peers;
 }
 
-// Exclusive prefix sum over the first n (<= 256) entries held one per thread of
-// a 256-thread workgroup; returns the exclusive value, *total gets the sum.
+// Exclusive prefix sum over 256 entries held one per thread by the first 256
+// threads of a workgroup (every thread of the workgroup must call it; threads
+// >= 256 only take part in the barriers); returns the exclusive value, *total
+// gets the sum.
 __device__ __forceinline__ int block_exclusive_scan_256(int v, int *scratch /*[256]*/, int *total) {
     const int tid = threadIdx.x;
-    scratch[tid] = v;
+    const bool in = tid < 256;
+    if (in) scratch[tid] = v;
     __syncthreads();
     for (int off = 1; off < 256; off <<= 1) {
-        const int add = tid >= off ? scratch[tid - off] : 0;
+        const int add = (in && tid >= off) ? scratch[tid - off] : 0;
         __syncthreads();
-        scratch[tid] += add;
+        if (in) scratch[tid] += add;
         __syncthreads();
     }
-    const int incl = scratch[tid];
+    const int incl = in ? scratch[tid] : 0;
     *total = scratch[255];
     __syncthreads();
     return incl - v;
@@ -63,7 +67,8 @@ __global__ __launch_bounds__(64) void count_kernel(const int32_t *__restrict__ m
         if (valid && (peers & ((1ull << lane) - 1ull)) == 0) hist[id] += __popcll(peers);
         __syncthreads();
     }
-    for (int e = lane; e < N; e += 64) blk_counts[(size_t)blockIdx.x * N + e] = hist[e];
+    // expert-major [N][nchunk], so the scan reads each expert's chunk counts contiguously
+    for (int e = lane; e < N; e += 64) blk_counts[(size_t)e * gridDim.x + blockIdx.x] = hist[e];
 }
 
 // Work list from the per-expert counts (thread e owns expert e; 256 threads).
@@ -78,34 +83,73 @@ __device__ __forceinline__ void emit_work_list(int e, int N, int count, int offs
         wl.active_end[slot] = offset + count;
     }
     if (threadIdx.x == 0) wl.hdr[0] = total;
-    const int ntile = (e < N) ? (count + wl.tile_m - 1) / wl.tile_m : 0;
-    const int tbase = block_exclusive_scan_256(ntile, scratch, &total);
-    for (int i = 0; i < ntile; ++i) {
-        wl.tile_expert[tbase + i] = e;
-        wl.tile_row0[tbase + i] = offset + i * wl.tile_m;
+    int nbig = 0, nsmall = 0;
+    if (e < N) tile_split(count, wl.tile_m, &nbig, &nsmall);
+    int total_big;
+    const int bbase = block_exclusive_scan_256(nbig, scratch, &total_big);
+    const int sbase = block_exclusive_scan_256(nsmall, scratch, &total);
+    for (int i = 0; i < nbig; ++i) {
+        wl.tile_expert[bbase + i] = e;
+        wl.tile_row0[bbase + i] = offset + i * 256;
     }
-    if (threadIdx.x == 0) wl.hdr[1] = total;
+    for (int i = 0; i < nsmall; ++i) {
+        wl.tile_expert[total_big + sbase + i] = e;
+        wl.tile_row0[total_big + sbase + i] = offset + nbig * 256 + i * kTileMMin;
+    }
+    if (threadIdx.x == 0) {
+        wl.hdr[1] = total_big;
+        wl.hdr[2] = total;
+    }
 }
 
-__global__ __launch_bounds__(256) void scan_kernel(const int32_t *__restrict__ blk_counts,
-                                                   int32_t *__restrict__ blk_base,
-                                                   int32_t *__restrict__ counts,
-                                                   int32_t *__restrict__ offsets,
-                                                   int32_t *__restrict__ num_pairs, int nchunk,
-                                                   int N, WorkList wl) {
-    __shared__ int scratch[256];
-    const int e = threadIdx.x;
-    int run = 0;
-    if (e < N) {
-        for (int b = 0; b < nchunk; ++b) {
-            const int c = blk_counts[(size_t)b * N + e];
-            blk_base[(size_t)b * N + e] = run;
+// Exclusive prefix over the chunks of one expert (expert-major histograms): one
+// workgroup per expert, each thread a run of consecutive chunks, wavefront
+// shuffles plus four wave totals.  Writes the expert's total to counts[e].
+__global__ __launch_bounds__(256) void chunk_prefix_kernel(const int32_t *__restrict__ blk_counts,
+                                                           int32_t *__restrict__ blk_base,
+                                                           int32_t *__restrict__ counts,
+                                                           int nchunk) {
+    __shared__ int wtot[4];
+    const int e = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int per = (nchunk + 255) >> 8;  // chunks per thread
+    const int32_t *src = blk_counts + (size_t)e * nchunk;
+    int32_t *dst = blk_base + (size_t)e * nchunk;
+    const int b0 = tid * per;
+    int mine = 0;
+    for (int i = 0; i < per; ++i) mine += (b0 + i < nchunk) ? src[b0 + i] : 0;
+    int incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(incl, off);
+        if (lane >= off) incl += t;
+    }
+    if (lane == 63) wtot[wave] = incl;
+    __syncthreads();
+    int run = incl - mine;
+    for (int w = 0; w < wave; ++w) run += wtot[w];
+    for (int i = 0; i < per; ++i) {
+        if (b0 + i < nchunk) {
+            const int c = src[b0 + i];
+            dst[b0 + i] = run;
             run += c;
         }
-        counts[e] = run;
     }
+    if (tid == 255) counts[e] = run;
+}
+
+// Prefix over the experts and the work list, from the per-expert totals.
+__global__ __launch_bounds__(256) void scan_kernel(int32_t *__restrict__ counts,
+                                                   int32_t *__restrict__ offsets,
+                                                   int32_t *__restrict__ num_pairs, int N,
+                                                   WorkList wl) {
+    __shared__ int scratch[256];
+    const int e = threadIdx.x;
+    const int run = e < N ? counts[e] : 0;
     int total;
-    const int excl = block_exclusive_scan_256(e < N ? run : 0, scratch, &total);
+    const int excl = block_exclusive_scan_256(run, scratch, &total);
     if (e < N) offsets[e] = excl;
     if (e == 0) {
         offsets[N] = total;
@@ -135,7 +179,8 @@ __global__ __launch_bounds__(64) void scatter_kernel(const int32_t *__restrict__
                                                      int32_t *__restrict__ inv_perm, int TK, int N) {
     __shared__ int run[256];
     const int lane = threadIdx.x;
-    for (int e = lane; e < N; e += 64) run[e] = offsets[e] + blk_base[(size_t)blockIdx.x * N + e];
+    for (int e = lane; e < N; e += 64)
+        run[e] = offsets[e] + blk_base[(size_t)e * gridDim.x + blockIdx.x];
     __syncthreads();
     const int P = offsets[N];
     const int f0 = blockIdx.x * kChunk;
@@ -170,7 +215,7 @@ __global__ __launch_bounds__(64) void scatter_kernel(const int32_t *__restrict__
 struct ChunkShared {
     int grp[kGroupsPerChunk][256];  // kept pairs per (group, expert), then their prefix
     int offs[256];
-    int wtot[4][3];
+    int wtot[4][4];
 };
 
 __device__ __forceinline__ void permute_chunk_body(const int32_t *ids, ChunkShared &sh,
@@ -205,7 +250,7 @@ __device__ __forceinline__ void permute_chunk_body(const int32_t *ids, ChunkShar
         }
     }
     __syncthreads();
-    int cnt = 0, s_cnt = 0, s_has = 0, s_tile = 0;
+    int cnt = 0, s_cnt = 0, s_has = 0, s_big = 0, s_small = 0, nbig = 0, nsmall = 0;
     if (worker) {  // thread tid owns expert tid
 #pragma unroll
         for (int g = 0; g < kGroupsPerChunk; ++g) {
@@ -215,41 +260,47 @@ __device__ __forceinline__ void permute_chunk_body(const int32_t *ids, ChunkShar
         }
         s_cnt = cnt;
         s_has = cnt > 0 ? 1 : 0;
-        s_tile = (cnt + wl.tile_m - 1) / wl.tile_m;
+        tile_split(cnt, wl.tile_m, &nbig, &nsmall);
+        s_big = nbig;
+        s_small = nsmall;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const int ta = __shfl_up(s_cnt, off);
             const int tb = __shfl_up(s_has, off);
-            const int tc = __shfl_up(s_tile, off);
+            const int tc = __shfl_up(s_big, off);
+            const int td = __shfl_up(s_small, off);
             if (lane >= off) {
                 s_cnt += ta;
                 s_has += tb;
-                s_tile += tc;
+                s_big += tc;
+                s_small += td;
             }
         }
         if (lane == 63) {
             sh.wtot[wave][0] = s_cnt;
             sh.wtot[wave][1] = s_has;
-            sh.wtot[wave][2] = s_tile;
+            sh.wtot[wave][2] = s_big;
+            sh.wtot[wave][3] = s_small;
         }
     }
     __syncthreads();
     int total = 0;
     if (worker) {
-        int t_has = 0, t_tile = 0;
+        int t_has = 0, t_big = 0, t_small = 0;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             if (w < wave) {
                 s_cnt += sh.wtot[w][0];
                 s_has += sh.wtot[w][1];
-                s_tile += sh.wtot[w][2];
+                s_big += sh.wtot[w][2];
+                s_small += sh.wtot[w][3];
             }
             total += sh.wtot[w][0];
             t_has += sh.wtot[w][1];
-            t_tile += sh.wtot[w][2];
+            t_big += sh.wtot[w][2];
+            t_small += sh.wtot[w][3];
         }
         const int has = cnt > 0 ? 1 : 0;
-        const int ntile = (cnt + wl.tile_m - 1) / wl.tile_m;
         const int excl = s_cnt - cnt;
         sh.offs[tid] = excl;
         if (tid < N) {
@@ -260,16 +311,21 @@ __device__ __forceinline__ void permute_chunk_body(const int32_t *ids, ChunkShar
             offsets[N] = total;
             *num_pairs = total;
             wl.hdr[0] = t_has;
-            wl.hdr[1] = t_tile;
+            wl.hdr[1] = t_big;
+            wl.hdr[2] = t_small;
         }
         if (has) {
             wl.active[s_has - 1] = tid;
             wl.active_beg[s_has - 1] = excl;
             wl.active_end[s_has - 1] = excl + cnt;
         }
-        for (int i = 0; i < ntile; ++i) {
-            wl.tile_expert[s_tile - ntile + i] = tid;
-            wl.tile_row0[s_tile - ntile + i] = excl + i * wl.tile_m;
+        for (int i = 0; i < nbig; ++i) {
+            wl.tile_expert[s_big - nbig + i] = tid;
+            wl.tile_row0[s_big - nbig + i] = excl + i * 256;
+        }
+        for (int i = 0; i < nsmall; ++i) {
+            wl.tile_expert[t_big + s_small - nsmall + i] = tid;
+            wl.tile_row0[t_big + s_small - nsmall + i] = excl + nbig * 256 + i * kTileMMin;
         }
     }
     __syncthreads();
@@ -310,8 +366,8 @@ hipError_t launch_permute(const beam_shape &s, const int32_t *masked_ids, int32_
         return hipGetLastError();
     }
     count_kernel<<<nchunk, 64, 0, st>>>(masked_ids, blk_counts, TK, s.N);
-    scan_kernel<<<1, 256, 0, st>>>(blk_counts, blk_base, counts, offsets, num_pairs, nchunk, s.N,
-                                   wl);
+    chunk_prefix_kernel<<<s.N, 256, 0, st>>>(blk_counts, blk_base, counts, nchunk);
+    scan_kernel<<<1, 256, 0, st>>>(counts, offsets, num_pairs, s.N, wl);
     scatter_kernel<<<nchunk, 64, 0, st>>>(masked_ids, offsets, blk_base, perm, inv_perm, TK, s.N);
     return hipGetLastError();
 }

@@ -196,21 +196,26 @@ hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_route
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void topk_mask_kernel(
     const float *__restrict__ router_logits, const float *__restrict__ mask_logits,
+    const float *__restrict__ b_router, const float *__restrict__ b_mask, int row_stride,
     int32_t *__restrict__ topk_ids, float *__restrict__ topk_w, int32_t *__restrict__ masked_ids,
     int Tn, int N, int K) {
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= Tn) return;  // wave-uniform
     const size_t f = (size_t)t * K;
-    wave_route_token(router_logits + (size_t)t * N, mask_logits + (size_t)t * N, N, K,
-                     topk_ids + f, topk_w + f, masked_ids + f);
+    wave_route_token(router_logits + (size_t)t * row_stride, mask_logits + (size_t)t * row_stride,
+                     b_router, b_mask, N, K, topk_ids + f, topk_w + f, masked_ids + f);
 }
 
+// Logits live as two [T,N] arrays that already include the biases, or (row_stride
+// = 2N, biases still to add) as one [T,2N] array: router columns, then mask columns.
 hipError_t launch_topk_mask(const beam_shape &s, const float *router_logits,
-                            const float *mask_logits, int32_t *topk_ids, float *topk_w,
-                            int32_t *masked_ids, hipStream_t st) {
+                            const float *mask_logits, const float *b_router, const float *b_mask,
+                            int row_stride, int32_t *topk_ids, float *topk_w, int32_t *masked_ids,
+                            hipStream_t st) {
     dim3 grid((s.T + 3) / 4);
-    topk_mask_kernel<<<grid, 256, 0, st>>>(router_logits, mask_logits, topk_ids, topk_w,
-                                           masked_ids, s.T, s.N, s.K);
+    topk_mask_kernel<<<grid, 256, 0, st>>>(router_logits, mask_logits, b_router, b_mask,
+                                           row_stride, topk_ids, topk_w, masked_ids, s.T, s.N,
+                                           s.K);
     return hipGetLastError();
 }
 

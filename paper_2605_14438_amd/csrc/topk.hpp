@@ -64,8 +64,12 @@ __device__ __forceinline__ float key_logit(uint64_t key) {
 // (N <= 256) of both heads.  K rounds of wave arg-max; after round k lane k
 // keeps the winner, so slot k = rank k+1.  Lanes k < K then write ids, softmax
 // weights over the K survivors and the masked id (a >= 0 keeps, otherwise -1).
+// br / bm: optional biases still to be added to r / a (NULL if the logits already
+// include them).
 __device__ __forceinline__ void wave_route_token(const float *__restrict__ r,
-                                                 const float *__restrict__ a, int N, int K,
+                                                 const float *__restrict__ a,
+                                                 const float *__restrict__ br,
+                                                 const float *__restrict__ bm, int N, int K,
                                                  int32_t *__restrict__ ids_out,
                                                  float *__restrict__ w_out,
                                                  int32_t *__restrict__ masked_out) {
@@ -74,7 +78,12 @@ __device__ __forceinline__ void wave_route_token(const float *__restrict__ r,
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int e = lane + 64 * i;
-        key[i] = e < N ? topk_key(r[e], e, a[e] >= 0.0f) : 0ull;
+        key[i] = 0ull;
+        if (e < N) {
+            const float rv = br ? r[e] + br[e] : r[e];
+            const float av = bm ? a[e] + bm[e] : a[e];
+            key[i] = topk_key(rv, e, av >= 0.0f);
+        }
     }
     uint64_t mine = 0;
     for (int k = 0; k < K; ++k) {

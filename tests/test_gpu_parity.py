@@ -338,3 +338,49 @@ def test_moe_forward_qwen3_decode_full_size(T):
         # run it again into the same buffers: identical bits
         res2 = hp.forward(cfg, hp.upload(cfg, d))
         assert torch.equal(res["out_raw"], res2["out_raw"])
+
+
+# ---------------------------------------------------------------------------
+# full-size prefill layers: indices on ALL tokens, outputs on a stratified sample
+# ---------------------------------------------------------------------------
+def _sampled_forward_check(cfg, packed, n_sample=48):
+    d = hp.make_tie_free(cfg)
+    ids_o, g_o, msk_o = oracle.route_mask(d["router_logits"], d["mask_logits"], cfg.K)
+    res = hp.forward(cfg, hp.upload(cfg, d), packed=packed)
+    assert np.array_equal(res["topk_ids"], ids_o)
+    assert np.array_equal(res["masked_ids"], msk_o)
+    np.testing.assert_allclose(res["topk_weights"], g_o, atol=2e-6, rtol=0)
+    assert res["num_pairs"] == int((msk_o >= 0).sum())
+    kept = (msk_o >= 0).sum(axis=1)
+    rng = np.random.default_rng(cfg.T + int(cfg.keep * 100))
+    pick = set(np.argsort(-kept, kind="stable")[:8].tolist())            # most experts kept
+    zero = np.flatnonzero(kept == 0)
+    pick.update(zero[:8].tolist())                                       # none kept
+    pick.update([0, cfg.T - 1])
+    pick.update(rng.choice(cfg.T, size=n_sample, replace=False).tolist())
+    sub = np.array(sorted(pick))
+    ref = oracle.moe_forward(d["x"][sub], d["w_router"], d["b_router"], d["w_mask"], d["b_mask"],
+                             d["w_gate_up"], d["w_down"], cfg.K)
+    assert np.array_equal(ref["masked_ids"], msk_o[sub])
+    got = res["out"][sub]
+    # the RMS of the tolerance is that of the whole output, estimated on the sample
+    literal, ratio = hp.output_error(got, ref["out"], cfg.dtype)
+    _log(f"  {cfg.name} T={cfg.T} keep={cfg.keep} packed={packed}: P={res['num_pairs']} "
+         f"sample {sub.size} tokens max|err|/RMS={literal:.4f} worst/bound={ratio:.3f}")
+    assert ratio <= 1.0
+    z = sub[kept[sub] == 0]
+    if z.size:
+        raw = res["out_raw"][torch.from_numpy(z).cuda()]
+        assert (raw.view(torch.int16) == 0).all()
+    # every zero-kept token of the whole batch is an exact zero row
+    if zero.size:
+        raw = res["out_raw"][torch.from_numpy(zero).cuda()]
+        assert (raw.view(torch.int16) == 0).all()
+
+
+@pytest.mark.parametrize("T,keep,packed", [(4096, 0.15, True), (4096, 1.0, False),
+                                           (16384, 0.15, True), (16384, 0.5, True)])
+def test_moe_forward_qwen3_prefill_full_size_sampled(T, keep, packed):
+    cfg = CFG["qwen3_prefill"].with_(T=T, keep=keep)
+    _log(f"moe_forward full size sampled {cfg} packed={packed}")
+    _sampled_forward_check(cfg, packed)
