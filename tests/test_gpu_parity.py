@@ -384,3 +384,69 @@ def test_moe_forward_qwen3_prefill_full_size_sampled(T, keep, packed):
     cfg = CFG["qwen3_prefill"].with_(T=T, keep=keep)
     _log(f"moe_forward full size sampled {cfg} packed={packed}")
     _sampled_forward_check(cfg, packed)
+
+
+# ---------------------------------------------------------------------------
+# the other full-size workloads: Mixtral-shaped and the large fine-grained layer.
+# One draw per workload at its largest T; smaller batches take the first rows.
+# ---------------------------------------------------------------------------
+_BIG = {}
+
+
+def _big_layer(name, T):
+    if name not in _BIG:
+        _BIG.clear()                      # one multi-GB layer in host memory at a time
+        cfg = CFG[name].with_(T=T)
+        d = hp.make_tie_free(cfg)
+        _BIG[name] = (cfg, d, hp.upload(cfg, d))
+    return _BIG[name]
+
+
+def _prefix_check(name, Tmax, T, packed):
+    cfg_max, d, g = _big_layer(name, Tmax)
+    cfg = cfg_max.with_(T=T)
+    _log(f"moe_forward full size {cfg} packed={packed}")
+    dd = {**d, "x": d["x"][:T], "router_logits": d["router_logits"][:T],
+          "mask_logits": d["mask_logits"][:T]}
+    gg = {**g, "x": g["x"][:T].contiguous()}
+    ids_o, g_o, msk_o = oracle.route_mask(dd["router_logits"], dd["mask_logits"], cfg.K)
+    res = hp.forward(cfg, gg, packed=packed)
+    assert np.array_equal(res["topk_ids"], ids_o)
+    assert np.array_equal(res["masked_ids"], msk_o)
+    np.testing.assert_allclose(res["topk_weights"], g_o, atol=2e-6, rtol=0)
+    kept = (msk_o >= 0).sum(axis=1)
+    if T <= 64:
+        sub = np.arange(T)
+    else:
+        rng = np.random.default_rng(T)
+        pick = set(np.argsort(-kept, kind="stable")[:6].tolist())
+        pick.update(np.flatnonzero(kept == 0)[:6].tolist())
+        pick.update(rng.choice(T, size=24, replace=False).tolist())
+        sub = np.array(sorted(pick))
+    ref = oracle.moe_forward(dd["x"][sub], d["w_router"], d["b_router"], d["w_mask"], d["b_mask"],
+                             d["w_gate_up"], d["w_down"], cfg.K)
+    literal, ratio = hp.output_error(res["out"][sub], ref["out"], cfg.dtype)
+    _log(f"  {name} T={T}: P={res['num_pairs']} kept/token min {kept.min()} max {kept.max()} "
+         f"mean {kept.mean():.2f}; {sub.size} tokens max|err|/RMS={literal:.4f} "
+         f"worst/bound={ratio:.3f}")
+    assert ratio <= 1.0
+    zero = np.flatnonzero(kept == 0)
+    if zero.size:
+        raw = res["out_raw"][torch.from_numpy(zero).cuda()]
+        assert (raw.view(torch.int16) == 0).all()
+    return kept
+
+
+@pytest.mark.parametrize("T,packed", [(1, False), (16, False), (2048, True), (2048, False)])
+def test_moe_forward_mixtral_full_size(T, packed):
+    kept = _prefix_check("mixtral", 2048, T, packed)
+    if T == 2048:
+        assert 0.5 < kept.mean() / 2 < 0.7          # ~60% of the Top-2 pairs kept
+
+
+@pytest.mark.parametrize("T,packed", [(64, False), (8192, True)])
+def test_moe_forward_large_full_size(T, packed):
+    kept = _prefix_check("large", 8192, T, packed)
+    if T == 8192:
+        assert 0.15 < kept.mean() / 8 < 0.25        # Beta(2,8): mean ~20%
+        assert kept.max() >= 7 and kept.min() == 0  # heavy tail
