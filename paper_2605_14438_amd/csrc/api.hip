@@ -38,7 +38,7 @@ WsLayout ws_layout(const beam_shape &s) {
     const size_t esz = s.dtype == BEAM_BF16 ? 2 : 4;
     L.nchunk = (int)((TK + kChunk - 1) / kChunk);
     if (L.nchunk < 1) L.nchunk = 1;
-    L.max_tiles = (int)(TK / kTileMMin + 2 * N);
+    L.max_tiles = (int)(TK / kTileM + N);  // sum over experts of ceil(c_e / kTileM)
     size_t off = 0;
     auto take = [&](size_t bytes) {
         const size_t at = off;
@@ -75,7 +75,6 @@ WorkList work_list(void *base, const beam_shape &s, int max_tiles) {
     wl.active_end = wl.active_beg + s.N;
     wl.tile_expert = wl.active_end + s.N;
     wl.tile_row0 = wl.tile_expert + max_tiles;
-    wl.tile_m = ffn_tile_m(s);
     return wl;
 }
 

@@ -17,18 +17,13 @@ constexpr int kWave = 64;
 constexpr int kGroupsPerChunk = 8;
 constexpr int kChunk = kWave * kGroupsPerChunk;
 
-// Smallest row tile of the prefill grouped GEMM (it bounds the length of the
-// tile list).  Every expert segment is cut into row tiles: the paper's "block
+// Row tile of the prefill grouped GEMM.  Every expert segment is cut into row
+// tiles of this many grouped rows (the last one ragged): the paper's "block
 // alignment" (App. A.4), done with a tile list instead of padding the index
-// array.
-constexpr int kTileMMin = 128;
+// array, so at most kTileM - 1 padded rows per expert are ever multiplied.
+constexpr int kTileM = 128;
 
-// Tiles an expert segment of `count` rows is cut into.
-__host__ __device__ inline void tile_split(int count, int tile_m, int *nbig, int *nsmall) {
-    const int b = tile_m == 256 ? count >> 8 : 0;
-    *nbig = b;
-    *nsmall = (count - (b << 8) + kTileMMin - 1) / kTileMMin;
-}
+__host__ __device__ inline int tiles_of(int count) { return (count + kTileM - 1) / kTileM; }
 
 typedef uint16_t bf16_t;
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -88,11 +83,7 @@ WsLayout ws_layout(const beam_shape &s);
 
 // Work list written on the device after the prefix sums:
 //   hdr[0] = number of experts with at least one kept pair (U)
-//   hdr[1] = number of 256-row tiles, hdr[2] = number of 128-row tiles.  With
-//            tile_m == 256 an expert segment of c rows gives c / 256 big tiles
-//            and its remainder one or two small ones (so at most 127 padded
-//            rows per expert); with tile_m == 128 only small tiles.  The big
-//            tiles come first in the list: longest jobs first.
+//   hdr[1] = number of row tiles
 //   active[u]      expert id of the u-th non-empty expert (ascending)
 //   active_beg[u], active_end[u]  its grouped rows [beg, end)
 //   tile_expert[i] expert of row tile i,  tile_row0[i] its first grouped row
@@ -105,10 +96,8 @@ struct WorkList {
     int32_t *active_end;
     int32_t *tile_expert;
     int32_t *tile_row0;
-    int32_t tile_m;  // 256: big and small tiles, 128: small only; chosen on the host
 };
 WorkList work_list(void *base, const beam_shape &s, int max_tiles);
-int ffn_tile_m(const beam_shape &s);
 
 // ---- launchers (each returns hipGetLastError() after enqueueing) ----------
 hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_router,

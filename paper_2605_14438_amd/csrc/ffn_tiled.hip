@@ -2,11 +2,11 @@
 // grouped GEMM over the expert-sorted rows on the matrix cores.
 //
 // The kept pairs of expert e are the grouped rows [offsets[e], offsets[e+1]).
-// Each segment is cut into row tiles of BM rows (the work list; this is the
-// "block alignment" of App. A.4 without padding the index array: rows past the
-// end of a segment are clamped on load and masked on store).  One workgroup of
-// 4 wavefronts (WM x 4/WM) computes a BM x 256 output tile, each wavefront a
-// (BM/WM) x (64*WM) sub-tile of 32x32 MFMA tiles, K-loop in steps of 64:
+// Each segment is cut into row tiles of BM = 128 rows (the work list; this is
+// the "block alignment" of App. A.4 without padding the index array: rows past
+// the end of a segment are clamped on load and masked on store).  One workgroup
+// of 4 wavefronts (WM x 4/WM) computes a BM x 256 output tile, each wavefront a
+// (BM/WM) x (64*WM) sub-tile of 32x32 MFMA tiles, K-loop in steps of 16*KS:
 //
 //   GATE_UP:  A = x rows gathered through perm (token = perm[row] / K),
 //             B = 128 gate rows and the 128 matching up rows of W_gate_up[e],
@@ -39,15 +39,16 @@
 //   at roughly half the speed of the packed one.
 //
 // Work order.  Workgroups are handed to the 8 XCDs round-robin by linear id,
-// and each XCD has its own L2.  The grid is persistent: 256 workgroups, one per
-// CU, workgroup b on XCD b % 8 as its member b / 8.  The work list of (expert,
-// row tile, column tile) items, column tile fastest, is cut into chunks of 32
-// consecutive items; chunk c goes to XCD c % 8, one item per CU.  So the 32
-// workgroups that run together on an XCD hold about five row tiles of one expert
-// times all its column tiles and share their A tiles and that expert's weights
-// through the XCD's L2 instead of each pulling them from HBM, while the chunks
-// deal the work evenly over the XCDs.  256-row tiles come first in the list,
-// the 128-row remainder tiles last (longest jobs first).
+// and each XCD has its own L2.  The grid is persistent: 512 workgroups, two per
+// CU, workgroup b on XCD b % 8 as its member b / 8.  The (row tile, column
+// tile) items are ordered by groups of four consecutive row tiles (mostly one
+// expert), inside a group by column tile, then by row tile, and this sequence
+// is cut into chunks of 64 consecutive items; chunk c goes to XCD c % 8, one
+// item per resident workgroup.  So the 64 workgroups that run together on an
+// XCD hold four row tiles times 16 column tiles (or, when an expert has fewer
+// column tiles, all of them for about ten row tiles): they share their A tiles
+// and that expert's weights through the XCD's L2 instead of each pulling them
+// from HBM, while the chunks deal the work evenly over the XCDs.
 //
 // v_mfma_f32_32x32x16_bf16 layouts (wave64): A/B lane l -> row/col l & 31,
 // k = 8*(l >> 5)..+7; D register r of lane l -> row 8*(r >> 2) + 4*(l >> 5) +
@@ -62,14 +63,18 @@
 namespace beam {
 
 constexpr int kTileN = 256;
+constexpr int kWorkgroupsPerCU = 2;
+// row tiles that share a column tile's weights back to back in the work order
+constexpr int kRowGroup = 4;
 // wavefront grid inside a workgroup: 1 x 4 (each weight fragment is loaded by exactly one wavefront)
 constexpr int kWavesM = 1;
 // MFMA k-steps per K-step of the main loop
-constexpr int kKSteps = 8;
+constexpr int kKSteps = 4;
 
 // KS = MFMA k-steps (16 reduction indices each) per K-step of the main loop: one
-// K-step is the prefetch distance, and at full MFMA rate a 256 x 256 x 64 step
-// lasts about 1 us, half an HBM round trip under load, so KS = 8 (K-step 128).
+// K-step is the prefetch distance.  With two workgroups per CU the register
+// budget is 256 per lane (128 of them accumulators), which fits KS = 4; the
+// other workgroup's MFMAs cover what a 64-wide prefetch distance does not.
 // One BM x 256 output tile: rows [row0, min(row0 + BM, row_end)) of expert e,
 // column tile col_tile.  As: 2 * BM * 2 * KS uint4 of LDS.
 template <int BM, int WM, int KS, bool GATE_UP, bool PACKED>
@@ -235,7 +240,8 @@ __device__ __forceinline__ void ffn_tile_body(
                 __builtin_amdgcn_sched_group_barrier(0x008, GH * WTN, 0);  // MFMA
                 if (hs & 1) __builtin_amdgcn_sched_group_barrier(0x020, WTN, 0);  // refill
                 if (hs < 2 * KS - 2) __builtin_amdgcn_sched_group_barrier(0x100, GH, 0);
-                if (hs >= 2 * KS - 4) __builtin_amdgcn_sched_group_barrier(0x200, AP / 4, 0);
+                if (hs >= 2 * KS - (AP < 4 ? AP : 4))
+                    __builtin_amdgcn_sched_group_barrier(0x200, AP < 4 ? 1 : AP / 4, 0);
             }
             __syncthreads();
         }
@@ -294,63 +300,63 @@ __device__ __forceinline__ void ffn_tile_body(
 }
 
 
-// Persistent kernel over the work list.  BIG: the list holds 256-row tiles
-// (first) and 128-row tiles; otherwise only 128-row tiles.
-template <bool BIG, int WM, int KS, bool GATE_UP, bool PACKED>
-__global__ __launch_bounds__(256) void ffn_tile_kernel(
+// Persistent kernel over the work list: kWorkgroupsPerCU resident workgroups
+// per CU, each walking (row tile, column tile) items.  Two 128-row workgroups
+// per CU measured faster than one 256-row workgroup (the second workgroup's
+// MFMAs cover the first one's prologue, epilogue and barriers) and than three
+// 64-row ones (more weight traffic per flop).
+template <int WM, int KS, bool GATE_UP, bool PACKED>
+__global__ __launch_bounds__(256, kWorkgroupsPerCU) void ffn_tile_kernel(
     const bf16_t *__restrict__ a_src,   // GATE_UP: x [T,H];  DOWN: hidden [P,I]
     const bf16_t *__restrict__ w,       // GATE_UP: w_gate_up [N,2I,H];  DOWN: w_down [N,H,I]
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm,
     const int32_t *__restrict__ wl_hdr, const int32_t *__restrict__ tile_expert,
     const int32_t *__restrict__ tile_row0, bf16_t *__restrict__ hidden_out,
     float *__restrict__ y_out, int H, int K, int I, int n_col_tiles) {
-    __shared__ uint4 As[2 * (BIG ? 256 : 128) * 2 * KS];
-    const int n_big = BIG ? wl_hdr[1] : 0;
-    const int n_work = (n_big + wl_hdr[2]) * n_col_tiles;
+    __shared__ uint4 As[2 * kTileM * 2 * KS];
+    // Item order: row tiles in groups of kRowGroup; inside a group the column
+    // tile is the slow index and the row tile the fast one, so neighbouring
+    // items multiply different rows by the SAME weight fragments.
+    const int n_tiles = wl_hdr[1];
+    const int group_items = kRowGroup * n_col_tiles;
+    const int n_work = ((n_tiles + kRowGroup - 1) / kRowGroup) * group_items;
     const int xcd = blockIdx.x & 7;
-    const int member = blockIdx.x >> 3;  // 0..31: the grid is 256 workgroups
+    const int member = blockIdx.x >> 3;  // gridDim.x / 8 workgroups per XCD
+    const int per_xcd = gridDim.x >> 3;
     for (int round = 0;; ++round) {
-        const int item = (round * 8 + xcd) * 32 + member;
+        const int item = (round * 8 + xcd) * per_xcd + member;
         if (item >= n_work) break;       // uniform over the workgroup
-        const int tile = item / n_col_tiles;
-        const int col_tile = item - tile * n_col_tiles;
+        const int group = item / group_items;
+        const int rem = item - group * group_items;
+        const int col_tile = rem / kRowGroup;
+        const int tile = group * kRowGroup + (rem - col_tile * kRowGroup);
+        if (tile >= n_tiles) continue;   // ragged last group (uniform)
         const int e = tile_expert[tile];
         const int row0 = tile_row0[tile];
         const int row_end = offsets[e + 1];
-        if (BIG && tile < n_big)
-            ffn_tile_body<256, WM, KS, GATE_UP, PACKED>(As, a_src, w, perm, hidden_out, y_out, H, K,
-                                                        I, e, row0, row_end, col_tile);
-        else
-            ffn_tile_body<128, WM, KS, GATE_UP, PACKED>(As, a_src, w, perm, hidden_out, y_out, H, K,
-                                                        I, e, row0, row_end, col_tile);
+        ffn_tile_body<kTileM, WM, KS, GATE_UP, PACKED>(As, a_src, w, perm, hidden_out, y_out, H,
+                                                       K, I, e, row0, row_end, col_tile);
     }
 }
-
-// Row-tile size for a shape, decided on the host from the worst-case average
-// segment length (the host never learns the real counts).
-int ffn_tile_m(const beam_shape &s) { return ((long)s.T * s.K >= 512L * s.N) ? 256 : 128; }
 
 bool tiled_ffn_supported(const beam_shape &s) {
     return s.dtype == BEAM_BF16 && s.H % 256 == 0 && s.I % 128 == 0 &&
            (long)s.T * s.H < (1L << 32) && (long)s.T * s.K * s.I < (1L << 32);
 }
 
-// one persistent workgroup per CU (256 CUs in 8 XCDs)
-constexpr int kPersistentGrid = 256;
+// 256 CUs in 8 XCDs
+constexpr int kPersistentGrid = 256 * kWorkgroupsPerCU;
 
 template <bool GATE_UP>
 static void launch_tile(const beam_shape &s, const bf16_t *a, const bf16_t *w,
                         const int32_t *offsets, const int32_t *perm, const WorkList &wl,
                         bf16_t *hidden, float *y, int nct, hipStream_t st) {
     const bool packed = s.weight_layout == BEAM_WEIGHTS_PACKED;
-    const bool big = ffn_tile_m(s) == 256;
-#define BEAM_LAUNCH_TILE(BIG, PK)                                                              \
-    ffn_tile_kernel<BIG, kWavesM, kKSteps, GATE_UP, PK><<<kPersistentGrid, 256, 0, st>>>(      \
+#define BEAM_LAUNCH_TILE(PK)                                                                   \
+    ffn_tile_kernel<kWavesM, kKSteps, GATE_UP, PK><<<kPersistentGrid, 256, 0, st>>>(           \
         a, w, offsets, perm, wl.hdr, wl.tile_expert, wl.tile_row0, hidden, y, s.H, s.K, s.I, nct)
-    if (big && packed) BEAM_LAUNCH_TILE(true, true);
-    else if (big) BEAM_LAUNCH_TILE(true, false);
-    else if (packed) BEAM_LAUNCH_TILE(false, true);
-    else BEAM_LAUNCH_TILE(false, false);
+    if (packed) BEAM_LAUNCH_TILE(true);
+    else BEAM_LAUNCH_TILE(false);
 #undef BEAM_LAUNCH_TILE
 }
 
@@ -395,20 +401,23 @@ __global__ __launch_bounds__(256) void pack_heads_kernel(const uint4 *__restrict
     }
 }
 
-__global__ __launch_bounds__(256) void logits_tile_kernel(const bf16_t *__restrict__ x,
-                                                          const bf16_t *__restrict__ packed_heads,
-                                                          float *__restrict__ logits2, int Tn,
-                                                          int H, int N2) {
-    __shared__ uint4 As[2 * 128 * 2 * kKSteps];
+// 64-row tiles: the output is only 2N wide, so the row tiles alone have to fill
+// the chip (T = 16384 gives 256 of them).
+constexpr int kLogitsM = 64;
+
+__global__ __launch_bounds__(256, 2) void logits_tile_kernel(
+    const bf16_t *__restrict__ x, const bf16_t *__restrict__ packed_heads,
+    float *__restrict__ logits2, int Tn, int H, int N2) {
+    __shared__ uint4 As[2 * kLogitsM * 2 * kKSteps];
     const int nct = N2 / kTileN;
-    const int n_work = ((Tn + 127) / 128) * nct;
+    const int n_work = ((Tn + kLogitsM - 1) / kLogitsM) * nct;
     for (int item = blockIdx.x; item < n_work; item += gridDim.x) {
         const int tile = item / nct;
         const int col_tile = item - tile * nct;
         // down-GEMM roles: output width N2, reduction length H, a single expert
-        ffn_tile_body<128, kWavesM, kKSteps, false, true>(As, x, packed_heads, nullptr, nullptr,
-                                                          logits2, N2, 1, H, 0, tile * 128, Tn,
-                                                          col_tile);
+        ffn_tile_body<kLogitsM, kWavesM, kKSteps, false, true>(
+            As, x, packed_heads, nullptr, nullptr, logits2, N2, 1, H, 0, tile * kLogitsM, Tn,
+            col_tile);
     }
 }
 
@@ -422,8 +431,8 @@ hipError_t launch_logits_tiled(const beam_shape &s, const void *x, const void *w
                                hipStream_t st) {
     pack_heads_kernel<<<256, 256, 0, st>>>((const uint4 *)w_router, (const uint4 *)w_mask,
                                            (uint4 *)packed_heads, s.N, s.H);
-    const int n_work = ((s.T + 127) / 128) * (2 * s.N / kTileN);
-    const int grid = n_work < 1024 ? n_work : 1024;
+    const int n_work = ((s.T + kLogitsM - 1) / kLogitsM) * (2 * s.N / kTileN);
+    const int grid = n_work < 512 ? n_work : 512;
     logits_tile_kernel<<<grid, 256, 0, st>>>((const bf16_t *)x, (const bf16_t *)packed_heads,
                                              logits2, s.T, s.H, 2 * s.N);
     return hipGetLastError();

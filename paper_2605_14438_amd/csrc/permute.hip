@@ -83,23 +83,13 @@ __device__ __forceinline__ void emit_work_list(int e, int N, int count, int offs
         wl.active_end[slot] = offset + count;
     }
     if (threadIdx.x == 0) wl.hdr[0] = total;
-    int nbig = 0, nsmall = 0;
-    if (e < N) tile_split(count, wl.tile_m, &nbig, &nsmall);
-    int total_big;
-    const int bbase = block_exclusive_scan_256(nbig, scratch, &total_big);
-    const int sbase = block_exclusive_scan_256(nsmall, scratch, &total);
-    for (int i = 0; i < nbig; ++i) {
-        wl.tile_expert[bbase + i] = e;
-        wl.tile_row0[bbase + i] = offset + i * 256;
+    const int nt = e < N ? tiles_of(count) : 0;
+    const int tbase = block_exclusive_scan_256(nt, scratch, &total);
+    for (int i = 0; i < nt; ++i) {
+        wl.tile_expert[tbase + i] = e;
+        wl.tile_row0[tbase + i] = offset + i * kTileM;
     }
-    for (int i = 0; i < nsmall; ++i) {
-        wl.tile_expert[total_big + sbase + i] = e;
-        wl.tile_row0[total_big + sbase + i] = offset + nbig * 256 + i * kTileMMin;
-    }
-    if (threadIdx.x == 0) {
-        wl.hdr[1] = total_big;
-        wl.hdr[2] = total;
-    }
+    if (threadIdx.x == 0) wl.hdr[1] = total;
 }
 
 // Exclusive prefix over the chunks of one expert (expert-major histograms): one
@@ -215,7 +205,7 @@ __global__ __launch_bounds__(64) void scatter_kernel(const int32_t *__restrict__
 struct ChunkShared {
     int grp[kGroupsPerChunk][256];  // kept pairs per (group, expert), then their prefix
     int offs[256];
-    int wtot[4][4];
+    int wtot[4][3];
 };
 
 __device__ __forceinline__ void permute_chunk_body(const int32_t *ids, ChunkShared &sh,
@@ -250,7 +240,7 @@ __device__ __forceinline__ void permute_chunk_body(const int32_t *ids, ChunkShar
         }
     }
     __syncthreads();
-    int cnt = 0, s_cnt = 0, s_has = 0, s_big = 0, s_small = 0, nbig = 0, nsmall = 0;
+    int cnt = 0, s_cnt = 0, s_has = 0, s_tiles = 0, nt = 0;
     if (worker) {  // thread tid owns expert tid
 #pragma unroll
         for (int g = 0; g < kGroupsPerChunk; ++g) {
@@ -260,45 +250,39 @@ __device__ __forceinline__ void permute_chunk_body(const int32_t *ids, ChunkShar
         }
         s_cnt = cnt;
         s_has = cnt > 0 ? 1 : 0;
-        tile_split(cnt, wl.tile_m, &nbig, &nsmall);
-        s_big = nbig;
-        s_small = nsmall;
+        nt = tiles_of(cnt);
+        s_tiles = nt;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const int ta = __shfl_up(s_cnt, off);
             const int tb = __shfl_up(s_has, off);
-            const int tc = __shfl_up(s_big, off);
-            const int td = __shfl_up(s_small, off);
+            const int tc = __shfl_up(s_tiles, off);
             if (lane >= off) {
                 s_cnt += ta;
                 s_has += tb;
-                s_big += tc;
-                s_small += td;
+                s_tiles += tc;
             }
         }
         if (lane == 63) {
             sh.wtot[wave][0] = s_cnt;
             sh.wtot[wave][1] = s_has;
-            sh.wtot[wave][2] = s_big;
-            sh.wtot[wave][3] = s_small;
+            sh.wtot[wave][2] = s_tiles;
         }
     }
     __syncthreads();
     int total = 0;
     if (worker) {
-        int t_has = 0, t_big = 0, t_small = 0;
+        int t_has = 0, t_tiles = 0;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             if (w < wave) {
                 s_cnt += sh.wtot[w][0];
                 s_has += sh.wtot[w][1];
-                s_big += sh.wtot[w][2];
-                s_small += sh.wtot[w][3];
+                s_tiles += sh.wtot[w][2];
             }
             total += sh.wtot[w][0];
             t_has += sh.wtot[w][1];
-            t_big += sh.wtot[w][2];
-            t_small += sh.wtot[w][3];
+            t_tiles += sh.wtot[w][2];
         }
         const int has = cnt > 0 ? 1 : 0;
         const int excl = s_cnt - cnt;
@@ -311,21 +295,16 @@ __device__ __forceinline__ void permute_chunk_body(const int32_t *ids, ChunkShar
             offsets[N] = total;
             *num_pairs = total;
             wl.hdr[0] = t_has;
-            wl.hdr[1] = t_big;
-            wl.hdr[2] = t_small;
+            wl.hdr[1] = t_tiles;
         }
         if (has) {
             wl.active[s_has - 1] = tid;
             wl.active_beg[s_has - 1] = excl;
             wl.active_end[s_has - 1] = excl + cnt;
         }
-        for (int i = 0; i < nbig; ++i) {
-            wl.tile_expert[s_big - nbig + i] = tid;
-            wl.tile_row0[s_big - nbig + i] = excl + i * 256;
-        }
-        for (int i = 0; i < nsmall; ++i) {
-            wl.tile_expert[t_big + s_small - nsmall + i] = tid;
-            wl.tile_row0[t_big + s_small - nsmall + i] = excl + nbig * 256 + i * kTileMMin;
+        for (int i = 0; i < nt; ++i) {
+            wl.tile_expert[s_tiles - nt + i] = tid;
+            wl.tile_row0[s_tiles - nt + i] = excl + i * kTileM;
         }
     }
     __syncthreads();
