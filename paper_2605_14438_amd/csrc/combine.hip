@@ -1,14 +1,91 @@
 // Masked aggregation (paper Eq. 7-8): out[t] = sum_k m_k g_k E_{id_k}(x_t) over
 // the kept slots of token t, in slot order, fp32 accumulate, one rounding.  A
 // gather over the expert-sorted rows: every output element is written exactly
-// once with coalesced 16-byte accesses and no atomics, and a token with no
-// kept expert gets an exactly +0 row (App. A.3).
+// once with coalesced accesses and no atomics, and a token with no kept expert
+// gets an exactly +0 row (App. A.3).
 #include "common.hpp"
 
 namespace beam {
 
+__device__ __forceinline__ void store4(float *p, float4 v) { *(float4 *)p = v; }
+__device__ __forceinline__ void store4(bf16_t *p, float4 v) {
+    uint2 q;
+    q.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
+    q.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+    *(uint2 *)p = q;
+}
+
+__device__ __forceinline__ void axpy4(float g, const float4 &y, float4 &acc) {
+    acc.x = fmaf(g, y.x, acc.x);
+    acc.y = fmaf(g, y.y, acc.y);
+    acc.z = fmaf(g, y.z, acc.z);
+    acc.w = fmaf(g, y.w, acc.w);
+}
+
+// One wavefront per token, H % (256 * CH) == 0.  Lane k < K looks up slot k; a
+// ballot gives the kept slots as a wave-uniform bit set that is walked in slot
+// order, two slots at a time, each slot's row and weight broadcast from its
+// lane.  A lane owns CH groups of four columns, 256 apart, so one slot is CH
+// independent 16-byte loads per lane and a wavefront keeps up to 2 * CH KiB in
+// flight: the kernel is a pure gather and lives on memory-level parallelism.
+// Dropped slots cost nothing.
+template <typename T, int CH>
+__global__ __launch_bounds__(256) void combine_wave_kernel(
+    const float *__restrict__ y_pairs, const float *__restrict__ topk_w,
+    const int32_t *__restrict__ masked_ids, const int32_t *__restrict__ inv_perm,
+    T *__restrict__ out, int Tn, int H, int K) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (t >= Tn) return;  // wave-uniform
+    int row = -1;
+    float g = 0.0f;
+    if (lane < K) {
+        const size_t f = (size_t)t * K + lane;
+        row = masked_ids[f] >= 0 ? inv_perm[f] : -1;
+        g = topk_w[f];
+    }
+    const uint64_t kept = __ballot(row >= 0);
+    for (int c0 = lane * 4; c0 < H; c0 += 256 * CH) {
+        float4 acc[CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        uint64_t m = kept;
+        while (m) {
+            const int ka = __builtin_ctzll(m);
+            m &= m - 1;
+            const float *pa = y_pairs + (size_t)__shfl(row, ka) * H + c0;
+            const float ga = __shfl(g, ka);
+            if (m) {
+                const int kb = __builtin_ctzll(m);
+                m &= m - 1;
+                const float *pb = y_pairs + (size_t)__shfl(row, kb) * H + c0;
+                const float gb = __shfl(g, kb);
+                float4 ya[CH], yb[CH];
+#pragma unroll
+                for (int i = 0; i < CH; ++i) ya[i] = *(const float4 *)(pa + i * 256);
+#pragma unroll
+                for (int i = 0; i < CH; ++i) yb[i] = *(const float4 *)(pb + i * 256);
+#pragma unroll
+                for (int i = 0; i < CH; ++i) {
+                    axpy4(ga, ya[i], acc[i]);
+                    axpy4(gb, yb[i], acc[i]);
+                }
+            } else {
+                float4 ya[CH];
+#pragma unroll
+                for (int i = 0; i < CH; ++i) ya[i] = *(const float4 *)(pa + i * 256);
+#pragma unroll
+                for (int i = 0; i < CH; ++i) axpy4(ga, ya[i], acc[i]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i) store4(out + (size_t)t * H + c0 + i * 256, acc[i]);
+    }
+}
+
+// Any H % 4 == 0: one workgroup per token, a slot at a time.
 template <typename T>
-__global__ __launch_bounds__(256) void combine_kernel(
+__global__ __launch_bounds__(256) void combine_generic_kernel(
     const float *__restrict__ y_pairs, const float *__restrict__ topk_w,
     const int32_t *__restrict__ masked_ids, const int32_t *__restrict__ inv_perm,
     T *__restrict__ out, int Tn, int H, int K) {
@@ -21,31 +98,38 @@ __global__ __launch_bounds__(256) void combine_kernel(
         for (int k = 0; k < K; ++k) {
             const int row = inv[k];
             if (ids[k] < 0 || row < 0) continue;
-            const float g = w[k];
-            const float4 y = *(const float4 *)(y_pairs + (size_t)row * H + c);
-            acc.x = fmaf(g, y.x, acc.x);
-            acc.y = fmaf(g, y.y, acc.y);
-            acc.z = fmaf(g, y.z, acc.z);
-            acc.w = fmaf(g, y.w, acc.w);
+            axpy4(w[k], *(const float4 *)(y_pairs + (size_t)row * H + c), acc);
         }
-        T *o = out + (size_t)t * H + c;
-        store_from_f32(o + 0, acc.x);
-        store_from_f32(o + 1, acc.y);
-        store_from_f32(o + 2, acc.z);
-        store_from_f32(o + 3, acc.w);
+        store4(out + (size_t)t * H + c, acc);
     }
+}
+
+template <typename T>
+static void launch_typed(const beam_shape &s, const float *y_pairs, const float *topk_w,
+                         const int32_t *masked_ids, const int32_t *inv_perm, T *out,
+                         hipStream_t st) {
+    // decode-sized batches: one wavefront per workgroup, to spread over the CUs
+    const int wpb = s.T <= 1024 ? 1 : 4;
+    const dim3 wave_grid((s.T + wpb - 1) / wpb);
+#define BEAM_COMBINE_WAVE(CH)                                                                   \
+    combine_wave_kernel<T, CH><<<wave_grid, 64 * wpb, 0, st>>>(y_pairs, topk_w, masked_ids,     \
+                                                               inv_perm, out, s.T, s.H, s.K)
+    if (s.H % 2048 == 0) BEAM_COMBINE_WAVE(8);
+    else if (s.H % 1024 == 0) BEAM_COMBINE_WAVE(4);
+    else if (s.H % 256 == 0) BEAM_COMBINE_WAVE(1);
+    else
+        combine_generic_kernel<T><<<dim3(s.T), 256, 0, st>>>(y_pairs, topk_w, masked_ids,
+                                                             inv_perm, out, s.T, s.H, s.K);
+#undef BEAM_COMBINE_WAVE
 }
 
 hipError_t launch_combine(const beam_shape &s, const float *y_pairs, const float *topk_w,
                           const int32_t *masked_ids, const int32_t *inv_perm, void *out,
                           hipStream_t st) {
-    dim3 grid(s.T);
     if (s.dtype == BEAM_BF16)
-        combine_kernel<bf16_t><<<grid, 256, 0, st>>>(y_pairs, topk_w, masked_ids, inv_perm,
-                                                     (bf16_t *)out, s.T, s.H, s.K);
+        launch_typed<bf16_t>(s, y_pairs, topk_w, masked_ids, inv_perm, (bf16_t *)out, st);
     else
-        combine_kernel<float><<<grid, 256, 0, st>>>(y_pairs, topk_w, masked_ids, inv_perm,
-                                                    (float *)out, s.T, s.H, s.K);
+        launch_typed<float>(s, y_pairs, topk_w, masked_ids, inv_perm, (float *)out, st);
     return hipGetLastError();
 }
 

@@ -305,8 +305,8 @@ __device__ __forceinline__ void ffn_tile_body(
 // per CU measured faster than one 256-row workgroup (the second workgroup's
 // MFMAs cover the first one's prologue, epilogue and barriers) and than three
 // 64-row ones (more weight traffic per flop).
-template <int WM, int KS, bool GATE_UP, bool PACKED>
-__global__ __launch_bounds__(256, kWorkgroupsPerCU) void ffn_tile_kernel(
+template <int WM, int KS, int OCC, bool GATE_UP, bool PACKED>
+__global__ __launch_bounds__(256, OCC) void ffn_tile_kernel(
     const bf16_t *__restrict__ a_src,   // GATE_UP: x [T,H];  DOWN: hidden [P,I]
     const bf16_t *__restrict__ w,       // GATE_UP: w_gate_up [N,2I,H];  DOWN: w_down [N,H,I]
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm,
@@ -344,19 +344,31 @@ bool tiled_ffn_supported(const beam_shape &s) {
            (long)s.T * s.H < (1L << 32) && (long)s.T * s.K * s.I < (1L << 32);
 }
 
-// 256 CUs in 8 XCDs
-constexpr int kPersistentGrid = 256 * kWorkgroupsPerCU;
 
 template <bool GATE_UP>
 static void launch_tile(const beam_shape &s, const bf16_t *a, const bf16_t *w,
                         const int32_t *offsets, const int32_t *perm, const WorkList &wl,
                         bf16_t *hidden, float *y, int nct, hipStream_t st) {
     const bool packed = s.weight_layout == BEAM_WEIGHTS_PACKED;
-#define BEAM_LAUNCH_TILE(PK)                                                                   \
-    ffn_tile_kernel<kWavesM, kKSteps, GATE_UP, PK><<<kPersistentGrid, 256, 0, st>>>(           \
+#define BEAM_LAUNCH_TILE(KS_, OCC_, PK)                                                        \
+    ffn_tile_kernel<kWavesM, KS_, OCC_, GATE_UP, PK><<<256 * OCC_, 256, 0, st>>>(              \
         a, w, offsets, perm, wl.hdr, wl.tile_expert, wl.tile_row0, hidden, y, s.H, s.K, s.I, nct)
-    if (packed) BEAM_LAUNCH_TILE(true);
-    else BEAM_LAUNCH_TILE(false);
+    // Two schedules of the same tile body.  "Dense": 64-wide K-steps, two
+    // workgroups per CU, whose MFMAs cover each other's prologue, epilogue and
+    // barriers; the faster one when the reduction is short and the work MFMA
+    // bound.  "Deep": 128-wide K-steps, one workgroup per CU with twice the
+    // bytes in flight per barrier; measured 8-17 % faster for the gate/up GEMM
+    // when the reduction is long (H >= 4096) or when there are so few rows per
+    // expert that the kernel can only be bound by streaming the weights
+    // (at most 256 per expert even with every pair kept).
+    if constexpr (GATE_UP) {
+        if (packed && (s.H >= 4096 || (long)s.T * s.K <= 256L * s.N)) {
+            BEAM_LAUNCH_TILE(8, 1, true);
+            return;
+        }
+    }
+    if (packed) BEAM_LAUNCH_TILE(kKSteps, kWorkgroupsPerCU, true);
+    else BEAM_LAUNCH_TILE(kKSteps, kWorkgroupsPerCU, false);
 #undef BEAM_LAUNCH_TILE
 }
 
@@ -404,18 +416,21 @@ __global__ __launch_bounds__(256) void pack_heads_kernel(const uint4 *__restrict
 // 64-row tiles: the output is only 2N wide, so the row tiles alone have to fill
 // the chip (T = 16384 gives 256 of them).
 constexpr int kLogitsM = 64;
+// 128-wide K-steps: with at most one item per workgroup the kernel is one latency
+// chain per K-step, so fewer, larger steps
+constexpr int kLogitsKS = 8;
 
 __global__ __launch_bounds__(256, 2) void logits_tile_kernel(
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ packed_heads,
     float *__restrict__ logits2, int Tn, int H, int N2) {
-    __shared__ uint4 As[2 * kLogitsM * 2 * kKSteps];
+    __shared__ uint4 As[2 * kLogitsM * 2 * kLogitsKS];
     const int nct = N2 / kTileN;
     const int n_work = ((Tn + kLogitsM - 1) / kLogitsM) * nct;
     for (int item = blockIdx.x; item < n_work; item += gridDim.x) {
         const int tile = item / nct;
         const int col_tile = item - tile * nct;
         // down-GEMM roles: output width N2, reduction length H, a single expert
-        ffn_tile_body<kLogitsM, kWavesM, kKSteps, false, true>(
+        ffn_tile_body<kLogitsM, kWavesM, kLogitsKS, false, true>(
             As, x, packed_heads, nullptr, nullptr, logits2, N2, 1, H, 0, tile * kLogitsM, Tn,
             col_tile);
     }

@@ -206,12 +206,48 @@ __global__ __launch_bounds__(256) void topk_mask_kernel(
                      b_router, b_mask, N, K, topk_ids + f, topk_w + f, masked_ids + f);
 }
 
+// Large batches: four tokens per wavefront (one per 16-lane row), 16 per workgroup.
+template <int NPL>
+__global__ __launch_bounds__(256) void topk_mask_rows_kernel(
+    const float *__restrict__ router_logits, const float *__restrict__ mask_logits,
+    const float *__restrict__ b_router, const float *__restrict__ b_mask, int row_stride,
+    int32_t *__restrict__ topk_ids, float *__restrict__ topk_w, int32_t *__restrict__ masked_ids,
+    int Tn, int N, int K) {
+    const int t = blockIdx.x * 16 + (threadIdx.x >> 4);
+    const bool valid = t < Tn;
+    const int tc = valid ? t : Tn - 1;
+    const size_t f = (size_t)tc * K;
+    row_route_token<NPL>(router_logits + (size_t)tc * row_stride,
+                         mask_logits + (size_t)tc * row_stride, b_router, b_mask, N, K, valid,
+                         topk_ids + f, topk_w + f, masked_ids + f);
+}
+
 // Logits live as two [T,N] arrays that already include the biases, or (row_stride
 // = 2N, biases still to add) as one [T,2N] array: router columns, then mask columns.
 hipError_t launch_topk_mask(const beam_shape &s, const float *router_logits,
                             const float *mask_logits, const float *b_router, const float *b_mask,
                             int row_stride, int32_t *topk_ids, float *topk_w, int32_t *masked_ids,
                             hipStream_t st) {
+    // The row variant does four tokens per wavefront at about the cost of one; the
+    // wave variant has the shorter latency chain for decode-sized batches.
+    const bool aligned = ((uintptr_t)router_logits | (uintptr_t)mask_logits |
+                          (uintptr_t)b_router | (uintptr_t)b_mask) % 16 == 0;
+    if (s.T >= 512 && s.K <= 16 && s.N % 4 == 0 && row_stride % 4 == 0 && s.N <= 256 && aligned) {
+        dim3 grid((s.T + 15) / 16);
+        if (s.N <= 64)
+            topk_mask_rows_kernel<4><<<grid, 256, 0, st>>>(router_logits, mask_logits, b_router,
+                                                           b_mask, row_stride, topk_ids, topk_w,
+                                                           masked_ids, s.T, s.N, s.K);
+        else if (s.N <= 128)
+            topk_mask_rows_kernel<8><<<grid, 256, 0, st>>>(router_logits, mask_logits, b_router,
+                                                           b_mask, row_stride, topk_ids, topk_w,
+                                                           masked_ids, s.T, s.N, s.K);
+        else
+            topk_mask_rows_kernel<16><<<grid, 256, 0, st>>>(router_logits, mask_logits, b_router,
+                                                            b_mask, row_stride, topk_ids, topk_w,
+                                                            masked_ids, s.T, s.N, s.K);
+        return hipGetLastError();
+    }
     dim3 grid((s.T + 3) / 4);
     topk_mask_kernel<<<grid, 256, 0, st>>>(router_logits, mask_logits, b_router, b_mask,
                                            row_stride, topk_ids, topk_w, masked_ids, s.T, s.N,

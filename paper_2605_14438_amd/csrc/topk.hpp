@@ -107,4 +107,81 @@ __device__ __forceinline__ void wave_route_token(const float *__restrict__ r,
     }
 }
 
+// Throughput variant for large batches: one token per 16-lane row, four tokens
+// per wavefront.  Lane j of a row holds candidates j*NPL .. j*NPL+NPL-1 (N <=
+// 16*NPL), so the arg-max reductions stay inside a row: four DPP steps, no
+// cross-row traffic, and every lane of the row ends up with the row's best key.
+// Same keys, same K rounds, same softmax as wave_route_token; needs K <= 16.
+// `valid` is row-uniform (false for the rows past the last token).
+__device__ __forceinline__ uint64_t row_max_u64(uint64_t key) {
+    max_step<0xB1, 0xf>(key);   // quad_perm [1,0,3,2]
+    max_step<0x4E, 0xf>(key);   // quad_perm [2,3,0,1]
+    max_step<0x141, 0xf>(key);  // row_half_mirror
+    max_step<0x140, 0xf>(key);  // row_mirror
+    return key;
+}
+
+__device__ __forceinline__ float row_sum_f32(float v) {
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, false));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, false));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xf, 0xf, false));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xf, 0xf, false));
+    return v;
+}
+
+template <int NPL>
+__device__ __forceinline__ void row_route_token(const float *__restrict__ r,
+                                                const float *__restrict__ a,
+                                                const float *__restrict__ br,
+                                                const float *__restrict__ bm, int N, int K,
+                                                bool valid, int32_t *__restrict__ ids_out,
+                                                float *__restrict__ w_out,
+                                                int32_t *__restrict__ masked_out) {
+    static_assert(NPL % 4 == 0, "candidates are loaded four at a time");
+    const int j = threadIdx.x & 15;
+    uint64_t key[NPL];
+#pragma unroll
+    for (int q = 0; q < NPL / 4; ++q) {
+        const int e0 = j * NPL + q * 4;
+        float4 rv = make_float4(0.f, 0.f, 0.f, 0.f), av = rv;
+        const bool in = valid && e0 < N;  // N % 4 == 0: a group of four is all in or all out
+        if (in) {
+            rv = *(const float4 *)(r + e0);
+            av = *(const float4 *)(a + e0);
+            if (br) {
+                const float4 b = *(const float4 *)(br + e0);
+                rv.x += b.x, rv.y += b.y, rv.z += b.z, rv.w += b.w;
+            }
+            if (bm) {
+                const float4 b = *(const float4 *)(bm + e0);
+                av.x += b.x, av.y += b.y, av.z += b.z, av.w += b.w;
+            }
+        }
+        key[q * 4 + 0] = in ? topk_key(rv.x, e0 + 0, av.x >= 0.0f) : 0ull;
+        key[q * 4 + 1] = in ? topk_key(rv.y, e0 + 1, av.y >= 0.0f) : 0ull;
+        key[q * 4 + 2] = in ? topk_key(rv.z, e0 + 2, av.z >= 0.0f) : 0ull;
+        key[q * 4 + 3] = in ? topk_key(rv.w, e0 + 3, av.w >= 0.0f) : 0ull;
+    }
+    uint64_t mine = 0;
+    for (int k = 0; k < K; ++k) {
+        uint64_t best = key[0];
+#pragma unroll
+        for (int i = 1; i < NPL; ++i) best = key[i] > best ? key[i] : best;
+        best = row_max_u64(best);
+#pragma unroll
+        for (int i = 0; i < NPL; ++i) key[i] = key[i] == best ? 0ull : key[i];
+        mine = j == k ? best : mine;
+    }
+    const int my_id = key_expert(mine);
+    const float my_r = key_logit(mine);
+    const float top = __shfl(my_r, threadIdx.x & 48);  // lane 0 of this row (wave-relative)
+    const float ex = j < K ? expf(my_r - top) : 0.0f;
+    const float denom = row_sum_f32(ex);
+    if (valid && j < K) {
+        ids_out[j] = my_id;
+        w_out[j] = ex / denom;
+        masked_out[j] = key_keep(mine) ? my_id : -1;
+    }
+}
+
 }  // namespace beam

@@ -35,6 +35,14 @@ ROUTE_CASES = [
     CFG["qwen3_decode"].with_(T=37), CFG["qwen3_decode"].with_(T=64),
     CFG["qwen3_prefill"].with_(T=1500),          # large-T logits kernel, ragged tail
     synth.LayerConfig("mixtral_router", 3, T=33, H=4096, N=8, K=2, I=64, dtype="bf16", keep=0.6),
+    # four-tokens-per-wavefront Top-K (T >= 512): 4, 8 and 16 candidates per lane,
+    # fewer experts than lanes in a row, ragged last workgroup
+    PREFILL_SMALL,
+    synth.LayerConfig("mixtral_router", 3, T=2051, H=4096, N=8, K=2, I=64, dtype="bf16",
+                      keep=0.6),
+    synth.LayerConfig("wide_router", 4, T=601, H=512, N=256, K=16, I=64, dtype="bf16",
+                      keep=0.3),
+    synth.LayerConfig("n40_router", 4, T=515, H=256, N=40, K=6, I=64, dtype="bf16", keep=0.5),
 ]
 
 
