@@ -75,13 +75,34 @@ constexpr int kKSteps = 4;
 // K-step is the prefetch distance.  With two workgroups per CU the register
 // budget is 256 per lane (128 of them accumulators), which fits KS = 4; the
 // other workgroup's MFMAs cover what a 64-wide prefetch distance does not.
-// One BM x 256 output tile: rows [row0, min(row0 + BM, row_end)) of expert e,
-// column tile col_tile.  As: 2 * BM * 2 * KS uint4 of LDS.
-template <int BM, int WM, int KS, bool GATE_UP, bool PACKED>
-__device__ __forceinline__ void ffn_tile_body(
-    uint4 *As, const bf16_t *__restrict__ a_src, const bf16_t *__restrict__ w,
+// One item of work: output tile rows [row0, min(row0 + BM, row_end)) of expert
+// e, column tile col_tile.
+// 16 bytes as a native vector: register arrays of it are promoted reliably,
+// which arrays of the uint4 struct are not once they live across items
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct TileItem {
+    int e, row0, row_end, col_tile;
+};
+
+// The persistent tile loop of one workgroup.  next_item(seq, it) advances seq to
+// this workgroup's next item at or after position seq and fills `it`, or returns
+// false when there is none; it must be uniform over the workgroup.
+// As: 2 * BM * 2 * KS uint4 of LDS.
+//
+// CHAIN: items are chained without a pipeline bubble: the last K-step of an item
+// already issues the next item's first weight fragments and, behind its MFMAs,
+// the next item's first activation tile, which then lands during the epilogue's
+// stores; only the very first item of a workgroup pays a prologue.  That keeps
+// one K-step of operands live across the epilogue (48 more registers with 128-row
+// tiles), which the schedule with two workgroups per CU cannot afford: there
+// CHAIN is off, every item starts with its own prologue, and the other
+// workgroup's MFMAs cover it.
+template <int BM, int WM, int KS, bool GATE_UP, bool PACKED, bool CHAIN, typename NextItem>
+__device__ __forceinline__ void ffn_tile_run(
+    u32x4 *As, const bf16_t *__restrict__ a_src, const bf16_t *__restrict__ w,
     const int32_t *__restrict__ perm, bf16_t *__restrict__ hidden_out, float *__restrict__ y_out,
-    int H, int K, int I, int e, int row0, int row_end, int col_tile) {
+    int H, int K, int I, NextItem next_item) {
     constexpr int PR = 2 * KS;           // 16-byte pieces per LDS row (K-step of 16*KS indices)
     constexpr int RPP = 256 / PR;        // tile rows copied per pass of the 256 threads
     constexpr int AP = BM / RPP;         // A rows per thread
@@ -102,152 +123,180 @@ __device__ __forceinline__ void ffn_tile_body(
     const int kh = lane >> 5;
     const int kdim = GATE_UP ? H : I;
     const int nk = kdim / (16 * KS);
+    // element stride between the weight pieces of consecutive MFMA k-steps,
+    // and between consecutive K-steps
+    constexpr int kBStep = PACKED ? 512 : 8;
+    constexpr int kBKStep = PACKED ? 512 * KS : 16 * KS;
 
-    {
-        const int n0 = col_tile * (GATE_UP ? kTileN / 2 : kTileN);
+    int seq = 0;
+    TileItem cur;
+    if (!next_item(seq, cur)) return;
 
-        // element offsets of this thread's A rows (32 bits: T*H and T*K*I < 2^32,
-        // checked on the host); pointers would cost twice the registers
-        uint32_t ao[AP];
-        const bf16_t *bp[WTN];
-#pragma unroll
-        for (int p = 0; p < AP; ++p) {
-            int grow = row0 + lr + p * RPP;
-            grow = grow < row_end ? grow : row_end - 1;
-            if constexpr (GATE_UP) {
-                const int tok = perm[grow] / K;
-                ao[p] = (uint32_t)tok * (uint32_t)H + piece * 8;
-            } else {
-                ao[p] = (uint32_t)grow * (uint32_t)I + piece * 8;
-            }
-        }
-#pragma unroll
-        for (int n = 0; n < WTN; ++n) {
-            const int nb = wn * WTN + n;
-            if constexpr (PACKED) {
-                // 32-row block rb of this expert: (kdim/16) fragments of 512 elements
-                const int rows32 = (GATE_UP ? 2 * I : H) >> 5;
-                const int rb = col_tile * 8 + nb;
-                bp[n] = w + ((size_t)e * rows32 + rb) * (size_t)(kdim >> 4) * 512 + lane * 8;
-            } else if constexpr (GATE_UP) {
-                const int feat = n0 + (nb >> 1) * 32 + l32;
-                const int wrow = (nb & 1) ? I + feat : feat;
-                bp[n] = w + ((size_t)e * 2 * I + wrow) * H + kh * (8 * KS);
-            } else {
-                bp[n] = w + ((size_t)e * H + n0 + nb * 32 + l32) * I + kh * (8 * KS);
-            }
-        }
-        // element stride between the weight pieces of consecutive MFMA k-steps,
-        // and between consecutive K-steps
-        constexpr int kBStep = PACKED ? 512 : 8;
-        constexpr int kBKStep = PACKED ? 512 * KS : 16 * KS;
+    // element offsets of this thread's A rows (32 bits: T*H and T*K*I < 2^32,
+    // checked on the host); pointers would cost twice the registers
+    uint32_t ao[AP];
+    const bf16_t *bp[WTN];
+// operand addresses of item `it`
+#define BEAM_SETUP(it)                                                                          \
+    _Pragma("unroll") for (int p = 0; p < AP; ++p) {                                            \
+        int grow = (it).row0 + lr + p * RPP;                                                    \
+        grow = grow < (it).row_end ? grow : (it).row_end - 1;                                   \
+        if constexpr (GATE_UP) {                                                                \
+            const int tok = perm[grow] / K;                                                     \
+            ao[p] = (uint32_t)tok * (uint32_t)H + piece * 8;                                    \
+        } else {                                                                                \
+            ao[p] = (uint32_t)grow * (uint32_t)I + piece * 8;                                   \
+        }                                                                                       \
+    }                                                                                           \
+    _Pragma("unroll") for (int n = 0; n < WTN; ++n) {                                           \
+        const int nb = wn * WTN + n;                                                            \
+        if constexpr (PACKED) {                                                                 \
+            /* 32-row block rb of this expert: (kdim/16) fragments of 512 elements */           \
+            const int rows32 = (GATE_UP ? 2 * I : H) >> 5;                                      \
+            const int rb = (it).col_tile * 8 + nb;                                              \
+            bp[n] = w + ((size_t)(it).e * rows32 + rb) * (size_t)(kdim >> 4) * 512 + lane * 8;  \
+        } else if constexpr (GATE_UP) {                                                         \
+            const int feat = (it).col_tile * (kTileN / 2) + (nb >> 1) * 32 + l32;               \
+            const int wrow = (nb & 1) ? I + feat : feat;                                        \
+            bp[n] = w + ((size_t)(it).e * 2 * I + wrow) * H + kh * (8 * KS);                    \
+        } else {                                                                                \
+            bp[n] = w + ((size_t)(it).e * H + (it).col_tile * kTileN + nb * 32 + l32) * I +     \
+                    kh * (8 * KS);                                                              \
+        }                                                                                       \
+    }
 
-        f32x16 acc[WTM][WTN];
-#pragma unroll
-        for (int m = 0; m < WTM; ++m)
-#pragma unroll
-            for (int n = 0; n < WTN; ++n)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.0f;
+    f32x16 acc[WTM][WTN];
+#define BEAM_ZERO_ACC                                                                           \
+    _Pragma("unroll") for (int m = 0; m < WTM; ++m)                                             \
+        _Pragma("unroll") for (int n = 0; n < WTN; ++n)                                         \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.0f;
 
-        uint4 ra[AP];
-        uint4 bq[WTN][KS];
+    u32x4 ra[AP];
+    u32x4 bq[WTN][KS];
 // activation tile: global -> registers, registers -> swizzled LDS stage
 #define BEAM_GLOAD_A(ko)                                                         \
-    _Pragma("unroll") for (int p = 0; p < AP; ++p) ra[p] = *(const uint4 *)(a_src + ao[p] + (ko));
+    _Pragma("unroll") for (int p = 0; p < AP; ++p) ra[p] = *(const u32x4 *)(a_src + ao[p] + (ko));
 #define BEAM_LSTORE_A(st)                                                        \
     _Pragma("unroll") for (int p = 0; p < AP; ++p) {                             \
         const int r_ = lr + p * RPP;                                             \
-        As[(st) * kStage + r_ * PR + (piece ^ (r_ & 7))] = ra[p];                            \
+        As[(st) * kStage + r_ * PR + (piece ^ (r_ & 7))] = ra[p];                \
     }
-        // One K-step out of LDS stage st.  The weight registers are a single
-        // buffer refilled on a rolling basis: as soon as the MFMAs of k-step j
-        // have been issued, bq[.][j] is reloaded for the next K-step, so every
-        // weight load has about three quarters of a K-step to arrive.  The A
-        // fragments of k-step j+1 are read from LDS before the MFMAs of k-step j
-        // are issued.
-        // A fragments are double buffered at half-step granularity: a k-step j is
-        // done in two halves of GH row tiles; the fragments of the next half are
-        // read from LDS before the MFMAs of the current half are issued.
-        constexpr int GH = WTM / 2;
-        auto read_a = [&](int st, int hstep, uint4 *af) {
-            const int j = hstep >> 1;
-            const int g = hstep & 1;
-            const int pc = PACKED ? j * 2 + kh : kh * KS + j;
+    // One K-step out of LDS stage st.  The weight registers are a single
+    // buffer refilled on a rolling basis: as soon as the MFMAs of k-step j
+    // have been issued, bq[.][j] is reloaded for the next K-step, so every
+    // weight load has about three quarters of a K-step to arrive.
+    // A fragments are double buffered at half-step granularity: a k-step j is
+    // done in two halves of GH row tiles; the fragments of the next half are
+    // read from LDS before the MFMAs of the current half are issued.
+    constexpr int GH = WTM / 2;
+    auto read_a = [&](int st, int hstep, u32x4 *af) {
+        const int j = hstep >> 1;
+        const int g = hstep & 1;
+        const int pc = PACKED ? j * 2 + kh : kh * KS + j;
 #pragma unroll
-            for (int m = 0; m < GH; ++m) {
-                const int r = wm * (BM / WM) + (g * GH + m) * 32 + l32;
-                af[m] = As[st * kStage + r * PR + (pc ^ (r & 7))];
-            }
-        };
-        auto compute = [&](int st, auto prefetch, int kt_next) {
-            constexpr bool PF = decltype(prefetch)::value;
-            uint4 af[2][GH];
-            read_a(st, 0, af[0]);
+        for (int m = 0; m < GH; ++m) {
+            const int r = wm * (BM / WM) + (g * GH + m) * 32 + l32;
+            af[m] = As[st * kStage + r * PR + (pc ^ (r & 7))];
+        }
+    };
+    auto compute = [&](int st, auto prefetch, int kt_next) {
+        constexpr bool PF = decltype(prefetch)::value;
+        u32x4 af[2][GH];
+        read_a(st, 0, af[0]);
 #pragma unroll
-            for (int hs = 0; hs < 2 * KS; ++hs) {
-                const int j = hs >> 1;
-                const int g = hs & 1;
-                if (hs + 1 < 2 * KS) read_a(st, hs + 1, af[(hs + 1) & 1]);
+        for (int hs = 0; hs < 2 * KS; ++hs) {
+            const int j = hs >> 1;
+            const int g = hs & 1;
+            if (hs + 1 < 2 * KS) read_a(st, hs + 1, af[(hs + 1) & 1]);
 #pragma unroll
-                for (int m = 0; m < GH; ++m)
+            for (int m = 0; m < GH; ++m)
+#pragma unroll
+                for (int n = 0; n < WTN; ++n)
+                    if constexpr (GATE_UP)
+                        acc[g * GH + m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, bq[n][j]),
+                            __builtin_bit_cast(bf16x8, af[hs & 1][m]), acc[g * GH + m][n], 0, 0, 0);
+                    else
+                        acc[g * GH + m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, af[hs & 1][m]),
+                            __builtin_bit_cast(bf16x8, bq[n][j]), acc[g * GH + m][n], 0, 0, 0);
+            if constexpr (PF) {
+                if (g == 1) {
 #pragma unroll
                     for (int n = 0; n < WTN; ++n)
-                        if constexpr (GATE_UP)
-                            acc[g * GH + m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                                __builtin_bit_cast(bf16x8, bq[n][j]),
-                                __builtin_bit_cast(bf16x8, af[hs & 1][m]), acc[g * GH + m][n], 0,
-                                0, 0);
-                        else
-                            acc[g * GH + m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                                __builtin_bit_cast(bf16x8, af[hs & 1][m]),
-                                __builtin_bit_cast(bf16x8, bq[n][j]), acc[g * GH + m][n], 0, 0,
-                                0);
-                if constexpr (PF) {
-                    if (g == 1) {
-#pragma unroll
-                        for (int n = 0; n < WTN; ++n)
-                            bq[n][j] = *(const uint4 *)(bp[n] + kt_next * kBKStep + j * kBStep);
-                    }
+                        bq[n][j] = *(const u32x4 *)(bp[n] + kt_next * kBKStep + j * kBStep);
                 }
             }
-        };
+        }
+    };
+// The order the scheduler is to build for one K-step (left alone it sinks every
+// load to just before its first use to save registers): per half k-step the
+// MFMAs, the refill of the weight registers they consumed and the LDS fragment
+// reads of the next half.
+#define BEAM_SCHED_HALF_STEP(hs)                                                                \
+    __builtin_amdgcn_sched_group_barrier(0x008, GH * WTN, 0);             /* MFMA */            \
+    if ((hs) & 1) __builtin_amdgcn_sched_group_barrier(0x020, WTN, 0);    /* refill */          \
+    if ((hs) < 2 * KS - 2) __builtin_amdgcn_sched_group_barrier(0x100, GH, 0);
 
-        BEAM_GLOAD_A(0)
+    int par = 0;  // LDS stage that holds K-step 0 of the current item
+    bool prologue = true;
+    for (;;) {
+        if (prologue) {  // the workgroup's first item; without CHAIN, every item
+            BEAM_ZERO_ACC
+            BEAM_SETUP(cur)
+            BEAM_GLOAD_A(0)
 #pragma unroll
-        for (int n = 0; n < WTN; ++n)
+            for (int n = 0; n < WTN; ++n)
 #pragma unroll
-            for (int j = 0; j < KS; ++j) bq[n][j] = *(const uint4 *)(bp[n] + j * kBStep);
-        BEAM_LSTORE_A(0)
-        __syncthreads();
+                for (int j = 0; j < KS; ++j) bq[n][j] = *(const u32x4 *)(bp[n] + j * kBStep);
+            BEAM_LSTORE_A(0)
+            __syncthreads();
+            prologue = !CHAIN;
+        }
+        TileItem nxt;
+        int seq_next = seq + 1;
+        const bool has_next = next_item(seq_next, nxt);
+
         // steady state without conditionals, so each wait counts only older loads
         for (int kt = 0; kt + 1 < nk; ++kt) {
-            const int st = kt & 1;
+            const int st = (par + kt) & 1;
             BEAM_GLOAD_A((kt + 1) * (16 * KS))
             compute(st, std::true_type{}, kt + 1);
             BEAM_LSTORE_A(st ^ 1)
-            // The order the scheduler is to build for this K-step (left alone it
-            // sinks every load to just before its first use to save registers):
-            // activation loads first; then per half k-step the MFMAs, the refill of
-            // the weight registers they consumed and the LDS fragment reads of the
-            // next half; the LDS stores of the next activation tile are spread over
-            // the last four half-steps, so the matrix cores keep running while the
-            // (half-rate) LDS writes drain instead of idling through a store phase.
+            // activation loads first; the LDS stores of the next activation tile are
+            // spread over the last four half-steps, so the matrix cores keep running
+            // while the (half-rate) LDS writes drain instead of idling through a
+            // store phase.
             __builtin_amdgcn_sched_group_barrier(0x020, AP, 0);            // VMEM read
             __builtin_amdgcn_sched_group_barrier(0x100, 2 * GH, 0);        // DS read
 #pragma unroll
             for (int hs = 0; hs < 2 * KS; ++hs) {
-                __builtin_amdgcn_sched_group_barrier(0x008, GH * WTN, 0);  // MFMA
-                if (hs & 1) __builtin_amdgcn_sched_group_barrier(0x020, WTN, 0);  // refill
-                if (hs < 2 * KS - 2) __builtin_amdgcn_sched_group_barrier(0x100, GH, 0);
+                BEAM_SCHED_HALF_STEP(hs)
                 if (hs >= 2 * KS - (AP < 4 ? AP : 4))
                     __builtin_amdgcn_sched_group_barrier(0x200, AP < 4 ? 1 : AP / 4, 0);
             }
             __syncthreads();
         }
-        compute((nk - 1) & 1, std::false_type{}, 0);
+        const int lst = (par + nk - 1) & 1;
+        const TileItem done = cur;
+        if (CHAIN && has_next) {
+            // Last K-step: operand addresses of the next item (for the gate/up GEMM a
+            // lookup through perm, whose latency the MFMAs cover), its first weight
+            // fragments as the refills, its first activation tile last.
+            BEAM_SETUP(nxt)
+            compute(lst, std::true_type{}, 0);
+            BEAM_GLOAD_A(0)
+            if constexpr (GATE_UP) __builtin_amdgcn_sched_group_barrier(0x020, AP, 0);  // perm
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * GH, 0);
+#pragma unroll
+            for (int hs = 0; hs < 2 * KS; ++hs) { BEAM_SCHED_HALF_STEP(hs) }
+            __builtin_amdgcn_sched_group_barrier(0x020, AP, 0);
+        } else {
+            compute(lst, std::false_type{}, 0);
+        }
 
-        // Epilogue.
+        // Epilogue of item `done`.
+        const int n0 = done.col_tile * (GATE_UP ? kTileN / 2 : kTileN);
         if constexpr (GATE_UP) {
             // The weights were the MFMA A operand and the activations the B operand,
             // so in a 32x32 result tile lane l holds activation row l & 31 and, in
@@ -256,8 +305,8 @@ __device__ __forceinline__ void ffn_tile_body(
             // stores of four bf16.
 #pragma unroll
             for (int m = 0; m < WTM; ++m) {
-                const int grow = row0 + wm * (BM / WM) + m * 32 + l32;
-                if (grow >= row_end) continue;
+                const int grow = done.row0 + wm * (BM / WM) + m * 32 + l32;
+                if (grow >= done.row_end) continue;
                 bf16_t *orow = hidden_out + (size_t)grow * I + n0 + kh * 4;
 #pragma unroll
                 for (int q = 0; q < WTN / 2; ++q) {
@@ -285,20 +334,32 @@ __device__ __forceinline__ void ffn_tile_body(
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int trow = wm * (BM / WM) + m * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
-                    const int grow = row0 + trow;
-                    if (grow >= row_end) continue;
+                    const int grow = done.row0 + trow;
+                    if (grow >= done.row_end) continue;
                     float *orow = y_out + (size_t)grow * H + n0 + l32;
 #pragma unroll
                     for (int n = 0; n < WTN; ++n) orow[(wn * WTN + n) * 32] = acc[m][n][r];
                 }
             }
         }
-        __syncthreads();  // every wavefront is done with the LDS stages before the next item
+        if (!has_next) break;
+        cur = nxt;
+        seq = seq_next;
+        if constexpr (CHAIN) {
+            // The next item's first activation tile goes into the stage that the
+            // K-step before last used (every wavefront left it at that K-step's barrier).
+            BEAM_LSTORE_A(lst ^ 1)
+            BEAM_ZERO_ACC
+            par = lst ^ 1;
+        }
+        __syncthreads();  // CHAIN: the tile is visible; else: both stages are free again
     }
+#undef BEAM_SETUP
+#undef BEAM_ZERO_ACC
 #undef BEAM_GLOAD_A
 #undef BEAM_LSTORE_A
+#undef BEAM_SCHED_HALF_STEP
 }
-
 
 // Persistent kernel over the work list: kWorkgroupsPerCU resident workgroups
 // per CU, each walking (row tile, column tile) items.  Two 128-row workgroups
@@ -313,7 +374,7 @@ __global__ __launch_bounds__(256, OCC) void ffn_tile_kernel(
     const int32_t *__restrict__ wl_hdr, const int32_t *__restrict__ tile_expert,
     const int32_t *__restrict__ tile_row0, bf16_t *__restrict__ hidden_out,
     float *__restrict__ y_out, int H, int K, int I, int n_col_tiles) {
-    __shared__ uint4 As[2 * kTileM * 2 * KS];
+    __shared__ u32x4 As[2 * kTileM * 2 * KS];
     // Item order: row tiles in groups of kRowGroup; inside a group the column
     // tile is the slow index and the row tile the fast one, so neighbouring
     // items multiply different rows by the SAME weight fragments.
@@ -323,20 +384,24 @@ __global__ __launch_bounds__(256, OCC) void ffn_tile_kernel(
     const int xcd = blockIdx.x & 7;
     const int member = blockIdx.x >> 3;  // gridDim.x / 8 workgroups per XCD
     const int per_xcd = gridDim.x >> 3;
-    for (int round = 0;; ++round) {
-        const int item = (round * 8 + xcd) * per_xcd + member;
-        if (item >= n_work) break;       // uniform over the workgroup
-        const int group = item / group_items;
-        const int rem = item - group * group_items;
-        const int col_tile = rem / kRowGroup;
-        const int tile = group * kRowGroup + (rem - col_tile * kRowGroup);
-        if (tile >= n_tiles) continue;   // ragged last group (uniform)
-        const int e = tile_expert[tile];
-        const int row0 = tile_row0[tile];
-        const int row_end = offsets[e + 1];
-        ffn_tile_body<kTileM, WM, KS, GATE_UP, PACKED>(As, a_src, w, perm, hidden_out, y_out, H,
-                                                       K, I, e, row0, row_end, col_tile);
-    }
+    auto next_item = [&](int &round, TileItem &it) -> bool {
+        for (;; ++round) {
+            const int item = (round * 8 + xcd) * per_xcd + member;
+            if (item >= n_work) return false;    // uniform over the workgroup
+            const int group = item / group_items;
+            const int rem = item - group * group_items;
+            const int col_tile = rem / kRowGroup;
+            const int tile = group * kRowGroup + (rem - col_tile * kRowGroup);
+            if (tile >= n_tiles) continue;       // ragged last group (uniform)
+            it.e = tile_expert[tile];
+            it.row0 = tile_row0[tile];
+            it.row_end = offsets[it.e + 1];
+            it.col_tile = col_tile;
+            return true;
+        }
+    };
+    ffn_tile_run<kTileM, WM, KS, GATE_UP, PACKED, OCC == 1>(As, a_src, w, perm, hidden_out, y_out,
+                                                            H, K, I, next_item);
 }
 
 bool tiled_ffn_supported(const beam_shape &s) {
@@ -357,7 +422,8 @@ static void launch_tile(const beam_shape &s, const bf16_t *a, const bf16_t *w,
     // workgroups per CU, whose MFMAs cover each other's prologue, epilogue and
     // barriers; the faster one when the reduction is short and the work MFMA
     // bound.  "Deep": 128-wide K-steps, one workgroup per CU with twice the
-    // bytes in flight per barrier; measured 8-17 % faster for the gate/up GEMM
+    // bytes in flight per barrier and items chained without a prologue;
+    // measured 8-17 % faster for the gate/up GEMM
     // when the reduction is long (H >= 4096) or when there are so few rows per
     // expert that the kernel can only be bound by streaming the weights
     // (at most 256 per expert even with every pair kept).
@@ -423,17 +489,22 @@ constexpr int kLogitsKS = 8;
 __global__ __launch_bounds__(256, 2) void logits_tile_kernel(
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ packed_heads,
     float *__restrict__ logits2, int Tn, int H, int N2) {
-    __shared__ uint4 As[2 * kLogitsM * 2 * kLogitsKS];
+    __shared__ u32x4 As[2 * kLogitsM * 2 * kLogitsKS];
     const int nct = N2 / kTileN;
     const int n_work = ((Tn + kLogitsM - 1) / kLogitsM) * nct;
-    for (int item = blockIdx.x; item < n_work; item += gridDim.x) {
+    auto next_item = [&](int &round, TileItem &it) -> bool {
+        const int item = blockIdx.x + round * gridDim.x;
+        if (item >= n_work) return false;
         const int tile = item / nct;
-        const int col_tile = item - tile * nct;
-        // down-GEMM roles: output width N2, reduction length H, a single expert
-        ffn_tile_body<kLogitsM, kWavesM, kLogitsKS, false, true>(
-            As, x, packed_heads, nullptr, nullptr, logits2, N2, 1, H, 0, tile * kLogitsM, Tn,
-            col_tile);
-    }
+        it.e = 0;
+        it.row0 = tile * kLogitsM;
+        it.row_end = Tn;
+        it.col_tile = item - tile * nct;
+        return true;
+    };
+    // down-GEMM roles: output width N2, reduction length H, a single expert
+    ffn_tile_run<kLogitsM, kWavesM, kLogitsKS, false, true, true>(
+        As, x, packed_heads, nullptr, nullptr, logits2, N2, 1, H, next_item);
 }
 
 bool logits_tiled_supported(const beam_shape &s) {
