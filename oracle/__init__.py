@@ -46,6 +46,7 @@ def _load() -> ctypes.CDLL:
         lib.beam_oracle_expert_ffn.restype = None
         lib.beam_oracle_pair_outputs.restype = ctypes.c_int64
         lib.beam_oracle_moe_forward.restype = ctypes.c_int64
+        lib.beam_oracle_block_forward.restype = ctypes.c_int64
         _lib = lib
     return _lib
 
@@ -161,6 +162,50 @@ def moe_forward(x, w_router, b_router, w_mask, b_mask, w_gate_up, w_down, K: int
         _ptr(g, _f64p), _ptr(msk, _i32p), int(nthreads))
     return {"out": out, "topk_ids": ids, "topk_weights": g, "masked_ids": msk,
             "pair_evals": int(n)}
+
+
+def block_forward(x, w_router, b_router, w_mask, b_mask, w_gate_up, w_down, K: int,
+                  w_sh_gate_up=None, w_sh_down=None, w_sh_gate=None, residual=None,
+                  nthreads: int = 0):
+    """Whole block with shared expert and residual (App. A.3) -> dict like moe_forward
+    plus g_shared [T] f64.  w_sh_gate_up [2*I_sh,H], w_sh_down [H,I_sh] (both or neither)."""
+    x = _f32(x)
+    wr = _f32(w_router)
+    wm = _f32(w_mask)
+    br = None if b_router is None else _f32(b_router)
+    bm = None if b_mask is None else _f32(b_mask)
+    wgu = _f32(w_gate_up)
+    wd = _f32(w_down)
+    T, H = x.shape
+    N, H2, I = wd.shape
+    assert H2 == H and wr.shape == (N, H) and wm.shape == (N, H) and wgu.shape == (N, 2 * I, H)
+    assert 1 <= K <= N
+    assert (w_sh_gate_up is None) == (w_sh_down is None)
+    I_sh = 0
+    sgu = sd = sg = res = None
+    if w_sh_down is not None:
+        sgu = _f32(w_sh_gate_up)
+        sd = _f32(w_sh_down)
+        I_sh = sd.shape[1]
+        assert sd.shape == (H, I_sh) and sgu.shape == (2 * I_sh, H)
+    if w_sh_gate is not None:
+        sg = _f32(w_sh_gate)
+        assert sg.shape == (H,)
+    if residual is not None:
+        res = _f32(residual)
+        assert res.shape == (T, H)
+    out = np.empty((T, H), dtype=np.float64)
+    ids = np.empty((T, K), dtype=np.int32)
+    g = np.empty((T, K), dtype=np.float64)
+    msk = np.empty((T, K), dtype=np.int32)
+    gsh = np.empty((T,), dtype=np.float64)
+    n = _load().beam_oracle_block_forward(
+        T, H, N, K, I, _ptr(x, _f32p), _ptr(wr, _f32p), _ptr(br, _f32p), _ptr(wm, _f32p),
+        _ptr(bm, _f32p), _ptr(wgu, _f32p), _ptr(wd, _f32p), I_sh, _ptr(sgu, _f32p),
+        _ptr(sd, _f32p), _ptr(sg, _f32p), _ptr(res, _f32p), _ptr(out, _f64p), _ptr(ids, _i32p),
+        _ptr(g, _f64p), _ptr(msk, _i32p), _ptr(gsh, _f64p), int(nthreads))
+    return {"out": out, "topk_ids": ids, "topk_weights": g, "masked_ids": msk,
+            "g_shared": gsh, "pair_evals": int(n)}
 
 
 def decision_margin(router_logits, mask_logits, K: int) -> np.ndarray:

@@ -31,10 +31,16 @@
  *   - delta in the GLU expert (Eq. 3) is SiLU.
  *   - Pairs are grouped by expert with a stable order (ascending flat pair
  *     index t*K+k inside an expert); dropped pairs carry id -1 (App. A.4).
+ *   - Whole block (App. A.3): the layer input x is the already normalised
+ *     hidden state, the residual h is a separate input; the shared expert is
+ *     one GLU expert of its own width; its weight g_sh, for which the paper
+ *     gives no formula, is 1, or sigma(x . w) when a gate vector w is given.
  *
  * Parity pins: every function here is pinned by the CPU tests (closed-form
  * micro case, all-ones / all-zero mask, dense library evaluation, brute force
- * over mask patterns, special cases K=1 / K=N / N=K=1, permutation invariants).
+ * over mask patterns, special cases K=1 / K=N / N=K=1, permutation invariants;
+ * for the whole block: the zero-activation forms of App. A.3, a dense library
+ * evaluation and the micro case extended by a shared expert and a residual).
  */
 #include <math.h>
 #include <stdint.h>
@@ -270,6 +276,60 @@ int64_t beam_oracle_moe_forward(int T, int H, int N, int K, int I, const float *
                 masked_ids[(size_t)t * K + k] = msk[k];
         }
         free(r); free(a); free(ids); free(msk); free(g); free(y);
+    }
+    return evals;
+}
+
+/* The whole MoE block with residual and shared expert (App. A.3):
+ *   out[t,:] = h[t,:] + sum over kept slots of g[k] * E_ids[k](x_t)
+ *                     + g_sh[t] * E_sh(x_t)
+ * x is the normalised hidden state N(h); h (residual) may be NULL (no residual
+ * term).  The shared expert is a GLU expert of width I_sh with weights
+ * w_sh_gate_up [2*I_sh,H] and w_sh_down [H,I_sh]; I_sh = 0 means delta_sh = 0.
+ * g_sh[t] = 1 / (1 + exp(-(x_t . w_sh_gate))) if w_sh_gate is given, else 1.
+ * With every routed expert masked the sum over slots is empty and the block
+ * reduces to the second form in App. A.3.  Returns the number of routed expert
+ * evaluations (the shared expert is not counted: it is never skipped).      */
+int64_t beam_oracle_block_forward(int T, int H, int N, int K, int I, const float *x,
+                                  const float *w_router, const float *b_router,
+                                  const float *w_mask, const float *b_mask,
+                                  const float *w_gate_up, const float *w_down, int I_sh,
+                                  const float *w_sh_gate_up, const float *w_sh_down,
+                                  const float *w_sh_gate, const float *residual, double *out,
+                                  int32_t *topk_ids, double *topk_weights, int32_t *masked_ids,
+                                  double *g_shared, int nthreads)
+{
+    int64_t evals = beam_oracle_moe_forward(T, H, N, K, I, x, w_router, b_router, w_mask, b_mask,
+                                            w_gate_up, w_down, out, topk_ids, topk_weights,
+                                            masked_ids, nthreads);
+    (void)nthreads;
+#ifdef _OPENMP
+    if (nthreads < 1)
+        nthreads = omp_get_max_threads();
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+#endif
+    for (int t = 0; t < T; ++t) {
+        const float *xt = x + (size_t)t * H;
+        double *o = out + (size_t)t * H;
+        double gsh = 1.0;
+        if (w_sh_gate) {
+            double z = 0.0;
+            for (int h = 0; h < H; ++h)
+                z += (double)xt[h] * (double)w_sh_gate[h];
+            gsh = 1.0 / (1.0 + exp(-z));
+        }
+        if (I_sh > 0) {
+            double *y = (double *)malloc(sizeof(double) * (size_t)H);
+            beam_oracle_expert_ffn(H, I_sh, xt, w_sh_gate_up, w_sh_down, y);
+            for (int c = 0; c < H; ++c)
+                o[c] += gsh * y[c];
+            free(y);
+        }
+        if (residual)
+            for (int c = 0; c < H; ++c)
+                o[c] += (double)residual[(size_t)t * H + c];
+        if (g_shared)
+            g_shared[t] = gsh;
     }
     return evals;
 }

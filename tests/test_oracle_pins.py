@@ -93,6 +93,72 @@ def test_micro_case_closed_form():
     assert P == exp["num_pairs"]
 
 
+def test_micro_case_shared_expert_and_residual():
+    """Whole block of App. A.3 on the hand-derived micro case."""
+    with open(os.path.join(GOLDEN, "micro_case.json")) as fh:
+        c = json.load(fh)
+    with open(os.path.join(GOLDEN, "micro_case_shared.json")) as fh:
+        sh = json.load(fh)
+    K = c["shape"]["K"]
+    args = (np.array(c["x"]), np.array(c["w_router"]), None, np.array(c["w_mask"]), None,
+            np.array(c["w_gate_up"]), np.array(c["w_down"]), K)
+    kw = dict(w_sh_gate_up=np.array(sh["w_sh_gate_up"]), w_sh_down=np.array(sh["w_sh_down"]),
+              residual=np.array(sh["residual"]))
+    exp, tol = sh["expected"], sh["tolerance"]
+    res = oracle.block_forward(*args, w_sh_gate=np.array(sh["w_sh_gate"]), **kw)
+    np.testing.assert_allclose(res["g_shared"], exp["g_shared"], atol=tol, rtol=0)
+    np.testing.assert_allclose(res["out"], exp["out_gated"], atol=tol, rtol=0)
+    assert res["masked_ids"].tolist() == c["expected"]["masked_ids"]
+    assert res["pair_evals"] == c["expected"]["pair_evals"]    # the shared expert is not counted
+    res1 = oracle.block_forward(*args, **kw)
+    np.testing.assert_allclose(res1["g_shared"], [1.0, 1.0], atol=0, rtol=0)
+    np.testing.assert_allclose(res1["out"], exp["out_ungated"], atol=tol, rtol=0)
+    # zero activation: every routed expert masked -> residual + shared expert only
+    off = np.full((c["shape"]["N"],), -1e4, np.float32)
+    a0 = list(args)
+    a0[4] = off
+    res0 = oracle.block_forward(*a0, w_sh_gate=np.array(sh["w_sh_gate"]), **kw)
+    assert (res0["masked_ids"] == -1).all() and res0["pair_evals"] == 0
+    np.testing.assert_allclose(res0["out"], exp["out_zero_activation_gated"], atol=tol, rtol=0)
+    # ... and without a shared expert the token bypasses the block: out == h exactly
+    res00 = oracle.block_forward(*a0, residual=np.array(sh["residual"]))
+    assert np.array_equal(res00["out"], np.array(sh["residual"], dtype=np.float32).astype(np.float64))
+
+
+@pytest.mark.parametrize("T,H,N,K,I,I_sh,gated", [(7, 24, 5, 3, 10, 20, True),
+                                                  (5, 16, 8, 2, 12, 36, False)])
+def test_block_forward_against_dense_library_evaluation(T, H, N, K, I, I_sh, gated):
+    """App. A.3's update written with library matmuls: h + routed + g_sh E_sh(x)."""
+    d = _rand_layer(5, T, H, N, K, I)
+    rng = np.random.default_rng(77)
+    sgu = (rng.standard_normal((2 * I_sh, H)) * 0.3).astype(np.float32)
+    sd = (rng.standard_normal((H, I_sh)) * 0.3).astype(np.float32)
+    sg = (rng.standard_normal((H,)) * 0.5).astype(np.float32) if gated else None
+    h = rng.standard_normal((T, H)).astype(np.float32)
+    res = oracle.block_forward(d["x"], d["w_router"], d["b_router"], d["w_mask"], d["b_mask"],
+                               d["w_gate_up"], d["w_down"], K, w_sh_gate_up=sgu, w_sh_down=sd,
+                               w_sh_gate=sg, residual=h)
+    routed = _fwd(d, K)
+    assert np.array_equal(res["masked_ids"], routed["masked_ids"])
+    x = d["x"].astype(np.float64)
+    gate = x @ sgu[:I_sh].astype(np.float64).T
+    up = x @ sgu[I_sh:].astype(np.float64).T
+    e_sh = (gate / (1.0 + np.exp(-gate)) * up) @ sd.astype(np.float64).T
+    g_sh = 1.0 / (1.0 + np.exp(-(x @ sg.astype(np.float64)))) if gated else np.ones(T)
+    ref = h.astype(np.float64) + routed["out"] + g_sh[:, None] * e_sh
+    np.testing.assert_allclose(res["g_shared"], g_sh, atol=1e-12, rtol=0)
+    assert np.abs(res["out"] - ref).max() <= 1e-9 * np.sqrt((ref ** 2).mean())
+    # a shared expert of width S*I is the sum of S experts of width I on its column blocks:
+    # the identity the GPU layout (shared experts appended as experts N..N+S-1) rests on
+    if I_sh % I == 0:
+        S = I_sh // I
+        parts = sum(oracle.expert_ffn(d["x"][0],
+                                      np.concatenate([sgu[j * I:(j + 1) * I],
+                                                      sgu[I_sh + j * I:I_sh + (j + 1) * I]]),
+                                      sd[:, j * I:(j + 1) * I]) for j in range(S))
+        np.testing.assert_allclose(parts, e_sh[0], atol=1e-9 * np.abs(e_sh[0]).max(), rtol=0)
+
+
 # --------------------------------------------------------------------------
 # all-ones mask == standard Top-K MoE (zero-initialised mask router, Sec. 3.3.1)
 # --------------------------------------------------------------------------
