@@ -190,6 +190,42 @@ beam_status beam_moe_forward(const beam_shape *shape, const void *x, const void 
                              size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The whole MoE block of App. A.3 in one call: residual, routed experts under the
+ * binary mask, and the shared expert,
+ *   out[t,:] = h[t,:] + sum_i g^_i E_i(x_t) + g_sh[t] E_sh(x_t),
+ * where x is the already normalised hidden state and h the residual.
+ *   shape          N routed experts, K of them per token (as everywhere else)
+ *   num_shared     S >= 0.  The shared expert is a GLU expert of width S*I, stored
+ *                  as S further experts of width I after the routed ones:
+ *                  w_gate_up [N+S, 2I, H], w_down [N+S, H, I]; block j holds
+ *                  the shared expert's gate/up rows and down columns j*I .. j*I+I-1
+ *                  (a GLU expert is the sum of its column blocks).  For packed
+ *                  weights call beam_pack_weights with N+S experts.  S = 0: no
+ *                  shared expert (delta_sh = 0).
+ *   w_shared_gate  [H] dtype or NULL.  The paper gives no formula for g_sh: NULL
+ *                  means g_sh = 1, otherwise g_sh[t] = sigma(x_t . w_shared_gate).
+ *                  Must be NULL when S = 0.
+ *   residual       [T,H] dtype or NULL (no residual term); must not overlap out.
+ *                  The sum starts from h in fp32 and is rounded once.
+ *   *_opt          as in beam_moe_forward but with K+S slots per token:
+ *                  [T,K+S]; slots K .. K+S-1 are the shared blocks (ids N .. N+S-1,
+ *                  weight g_sh, never masked).  num_pairs_opt counts them too.
+ * A token whose routed experts are all masked gets h + g_sh E_sh(x) (h itself
+ * without a shared expert): the zero-activation case of App. A.3.
+ * The workspace must hold beam_block_workspace_bytes(shape, num_shared) bytes
+ * (0 = invalid or unsupported; N+S <= 256 and K+S <= 64).
+ */
+size_t beam_block_workspace_bytes(const beam_shape *shape, int32_t num_shared);
+beam_status beam_moe_block_forward(const beam_shape *shape, int32_t num_shared, const void *x,
+                                   const void *w_router, const float *router_bias,
+                                   const void *w_mask, const float *mask_bias,
+                                   const void *w_gate_up, const void *w_down,
+                                   const void *w_shared_gate, const void *residual, void *out,
+                                   int32_t *topk_ids_opt, float *topk_weights_opt,
+                                   int32_t *masked_ids_opt, int32_t *num_pairs_opt,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Measurement aid, not part of the layer: beam_moe_forward with a HIP event
  * recorded on `hip_stream` before and after every stage.  Unlike every other
  * entry point this one creates and destroys events and WAITS for the stream;

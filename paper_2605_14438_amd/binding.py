@@ -28,7 +28,8 @@ BEAM_WEIGHTS_PACKED = 1
 
 EXPORTS = ("beam_abi_version", "beam_status_string", "beam_workspace_bytes", "beam_route_mask",
            "beam_permute", "beam_expert_ffn", "beam_combine", "beam_moe_forward",
-           "beam_moe_forward_timed", "beam_pack_weights")
+           "beam_moe_forward_timed", "beam_pack_weights", "beam_block_workspace_bytes",
+           "beam_moe_block_forward")
 BEAM_NUM_STAGES = 6
 STAGE_NAMES = ("logits", "topk_mask", "permute", "gate_up", "down", "combine")
 
@@ -75,6 +76,10 @@ def load() -> ctypes.CDLL:
         lib.beam_combine.argtypes = [sp] + [vp] * 6
         lib.beam_moe_forward.restype = ctypes.c_int
         lib.beam_moe_forward.argtypes = [sp] + [vp] * 13 + [sz, vp]
+        lib.beam_block_workspace_bytes.restype = sz
+        lib.beam_block_workspace_bytes.argtypes = [sp, ctypes.c_int32]
+        lib.beam_moe_block_forward.restype = ctypes.c_int
+        lib.beam_moe_block_forward.argtypes = [sp, ctypes.c_int32] + [vp] * 15 + [sz, vp]
         lib.beam_pack_weights.restype = ctypes.c_int
         lib.beam_pack_weights.argtypes = [sp] + [vp] * 5
         lib.beam_moe_forward_timed.restype = ctypes.c_int
@@ -177,6 +182,26 @@ def beam_moe_forward(shape, x, w_router, router_bias, w_mask, mask_bias, w_gate_
                                  _p(num_pairs_opt), _p(workspace), int(workspace_bytes),
                                  _p(hip_stream))
     return _check("beam_moe_forward", st, check)
+
+
+def beam_block_workspace_bytes(shape, num_shared: int) -> int:
+    s = _shape(shape)
+    return int(load().beam_block_workspace_bytes(ctypes.byref(s), int(num_shared)))
+
+
+def beam_moe_block_forward(shape, num_shared, x, w_router, router_bias, w_mask, mask_bias,
+                           w_gate_up, w_down, w_shared_gate, residual, out, topk_ids_opt,
+                           topk_weights_opt, masked_ids_opt, num_pairs_opt, workspace,
+                           workspace_bytes, hip_stream=None, check: bool = True) -> int:
+    s = _shape(shape)
+    st = load().beam_moe_block_forward(ctypes.byref(s), int(num_shared), _p(x), _p(w_router),
+                                       _p(router_bias), _p(w_mask), _p(mask_bias),
+                                       _p(w_gate_up), _p(w_down), _p(w_shared_gate),
+                                       _p(residual), _p(out), _p(topk_ids_opt),
+                                       _p(topk_weights_opt), _p(masked_ids_opt),
+                                       _p(num_pairs_opt), _p(workspace), int(workspace_bytes),
+                                       _p(hip_stream))
+    return _check("beam_moe_block_forward", st, check)
 
 
 def beam_moe_forward_timed(shape, x, w_router, router_bias, w_mask, mask_bias, w_gate_up, w_down,

@@ -48,10 +48,11 @@ WsLayout ws_layout(const beam_shape &s) {
     // one allocation: the prefill logits kernel writes them as a single [T,2N] array
     L.router_logits = take(2 * T * N * 4);
     L.mask_logits = L.router_logits + T * N * 4;
-    L.packed_heads = take(2 * N * (size_t)s.H * esz);
+    L.packed_heads = take((2 * N + 255) / 256 * 256 * (size_t)s.H * esz);  // padded to a column tile
     L.topk_ids = take(TK * 4);
     L.topk_w = take(TK * 4);
     L.masked_ids = take(TK * 4);
+    L.g_shared = take(T * 4);
     L.blk_counts = take((size_t)L.nchunk * N * 4);
     L.blk_base = take((size_t)L.nchunk * N * 4);
     L.counts = take(N * 4);
@@ -137,7 +138,7 @@ using namespace beam;
 
 extern "C" {
 
-int32_t beam_abi_version(void) { return 2; }
+int32_t beam_abi_version(void) { return 3; }
 
 const char *beam_status_string(beam_status status) {
     switch (status) {
@@ -193,8 +194,8 @@ beam_status beam_route_mask(const beam_shape *shape, const void *x, const void *
     float *ml = mask_logits_dbg ? mask_logits_dbg : (float *)(ws + L.mask_logits);
     hipStream_t stream = (hipStream_t)hip_stream;
     BEAM_TRY_HIP(launch_logits(s, x, w_router, router_bias, w_mask, mask_bias, rl, ml, stream));
-    BEAM_TRY_HIP(launch_topk_mask(s, rl, ml, nullptr, nullptr, s.N, topk_ids, topk_weights,
-                                  masked_ids, stream));
+    BEAM_TRY_HIP(launch_topk_mask(s, rl, ml, nullptr, nullptr, s.N, 0, nullptr, topk_ids,
+                                  topk_weights, masked_ids, stream));
     return BEAM_OK;
 }
 
@@ -255,33 +256,52 @@ beam_status beam_combine(const beam_shape *shape, const float *y_pairs, const fl
     if (!y_pairs || !topk_weights || !masked_ids || !inv_perm || !out) return BEAM_ERR_INVALID_ARG;
     if (misaligned(y_pairs) || misaligned(out)) return BEAM_ERR_INVALID_ARG;
     if (s.T == 0) return BEAM_OK;
-    BEAM_TRY_HIP(launch_combine(s, y_pairs, topk_weights, masked_ids, inv_perm, out,
+    BEAM_TRY_HIP(launch_combine(s, y_pairs, topk_weights, masked_ids, inv_perm, nullptr, out,
                                 (hipStream_t)hip_stream));
     return BEAM_OK;
 }
 
-static beam_status moe_forward_impl(const beam_shape *shape, const void *x, const void *w_router,
-                                    const float *router_bias, const void *w_mask,
-                                    const float *mask_bias, const void *w_gate_up,
-                                    const void *w_down, void *out, int32_t *topk_ids_opt,
-                                    float *topk_weights_opt, int32_t *masked_ids_opt,
-                                    int32_t *num_pairs_opt, void *workspace,
-                                    size_t workspace_bytes, void *hip_stream, hipEvent_t *ev) {
+// The fused layer.  `shape` counts the routed experts (N, K per token); S shared
+// experts (App. A.3) follow them in the weight arrays and ride the same grouped
+// kernels as experts N .. N+S-1 with S always-kept slots per token, so from
+// grouping on everything runs at N+S experts and K+S slots.
+static beam_status moe_forward_impl(const beam_shape *shape, int S, const void *x,
+                                    const void *w_router, const float *router_bias,
+                                    const void *w_mask, const float *mask_bias,
+                                    const void *w_gate_up, const void *w_down,
+                                    const void *w_shared_gate, const void *residual, void *out,
+                                    int32_t *topk_ids_opt, float *topk_weights_opt,
+                                    int32_t *masked_ids_opt, int32_t *num_pairs_opt,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream,
+                                    hipEvent_t *ev) {
     beam_status st = check_shape(shape);
     if (st != BEAM_OK) return st;
     const beam_shape &s = *shape;
+    if (S < 0) return BEAM_ERR_INVALID_ARG;
+    beam_shape se = s;  // experts and slots including the shared ones
+    se.N = s.N + S;
+    se.K = s.K + S;
+    if (S > 0) {
+        // K <= N holds for the routed part; the slot count may exceed N + S never
+        if (se.N > 256 || se.K > 64) return BEAM_ERR_UNSUPPORTED;
+        if ((long)se.T * se.K >= (1L << 24)) return BEAM_ERR_UNSUPPORTED;
+        if (se.weight_layout == BEAM_WEIGHTS_PACKED && !tiled_ffn_supported(se))
+            return BEAM_ERR_UNSUPPORTED;
+    }
     if (!x || !w_router || !w_mask || !w_gate_up || !w_down || !out) return BEAM_ERR_INVALID_ARG;
     if (misaligned(x) || misaligned(w_router) || misaligned(w_mask) || misaligned(w_gate_up) ||
-        misaligned(w_down) || misaligned(out))
+        misaligned(w_down) || misaligned(out) || misaligned(residual) ||
+        misaligned(w_shared_gate))
         return BEAM_ERR_INVALID_ARG;
-    const WsLayout L = ws_layout(s);
-    st = check_ws(s, workspace, workspace_bytes, L);
+    if (w_shared_gate && S == 0) return BEAM_ERR_INVALID_ARG;
+    const WsLayout L = ws_layout(se);
+    st = check_ws(se, workspace, workspace_bytes, L);
     if (st != BEAM_OK) return st;
     if (s.T == 0) return BEAM_OK;
     char *ws = (char *)workspace;
     hipStream_t stream = (hipStream_t)hip_stream;
     float *rl = (float *)(ws + L.router_logits);
-    float *ml = (float *)(ws + L.mask_logits);
+    float *ml = rl + (size_t)s.T * s.N;
     int32_t *ids = topk_ids_opt ? topk_ids_opt : (int32_t *)(ws + L.topk_ids);
     float *gw = topk_weights_opt ? topk_weights_opt : (float *)(ws + L.topk_w);
     int32_t *mids = masked_ids_opt ? masked_ids_opt : (int32_t *)(ws + L.masked_ids);
@@ -291,34 +311,37 @@ static beam_status moe_forward_impl(const beam_shape *shape, const void *x, cons
     int32_t *perm = (int32_t *)(ws + L.perm);
     int32_t *inv = (int32_t *)(ws + L.inv_perm);
     float *y_pairs = (float *)(ws + L.y_pairs);
-    const WorkList wl = work_list(ws + L.work, s, L.max_tiles);
+    float *g_shared = w_shared_gate ? (float *)(ws + L.g_shared) : nullptr;
+    const WorkList wl = work_list(ws + L.work, se, L.max_tiles);
 
 #define BEAM_STAGE_MARK(i)                                      \
     do {                                                        \
         if (ev) BEAM_TRY_HIP(hipEventRecord(ev[i], stream));    \
     } while (0)
     BEAM_STAGE_MARK(0);
+    if (g_shared) BEAM_TRY_HIP(launch_shared_gate(s, x, w_shared_gate, g_shared, stream));
     if (logits_tiled_supported(s)) {
         // prefill: both heads as one tiled GEMM into a [T,2N] array; biases join at Top-K
         BEAM_TRY_HIP(launch_logits_tiled(s, x, w_router, w_mask, ws + L.packed_heads, rl, stream));
         BEAM_STAGE_MARK(1);
-        BEAM_TRY_HIP(launch_topk_mask(s, rl, rl + s.N, router_bias, mask_bias, 2 * s.N, ids, gw,
-                                      mids, stream));
+        BEAM_TRY_HIP(launch_topk_mask(s, rl, rl + s.N, router_bias, mask_bias, 2 * s.N, S,
+                                      g_shared, ids, gw, mids, stream));
     } else {
         BEAM_TRY_HIP(launch_logits(s, x, w_router, router_bias, w_mask, mask_bias, rl, ml, stream));
         BEAM_STAGE_MARK(1);
-        BEAM_TRY_HIP(launch_topk_mask(s, rl, ml, nullptr, nullptr, s.N, ids, gw, mids, stream));
+        BEAM_TRY_HIP(launch_topk_mask(s, rl, ml, nullptr, nullptr, s.N, S, g_shared, ids, gw,
+                                      mids, stream));
     }
     BEAM_STAGE_MARK(2);
-    BEAM_TRY_HIP(launch_permute(s, mids, counts, offsets, perm, inv, np,
+    BEAM_TRY_HIP(launch_permute(se, mids, counts, offsets, perm, inv, np,
                                 (int32_t *)(ws + L.blk_counts), (int32_t *)(ws + L.blk_base),
                                 L.nchunk, wl, stream));
     BEAM_STAGE_MARK(3);
-    BEAM_TRY_HIP(launch_gate_up(s, x, w_gate_up, offsets, perm, np, wl, ws + L.hidden, stream));
+    BEAM_TRY_HIP(launch_gate_up(se, x, w_gate_up, offsets, perm, np, wl, ws + L.hidden, stream));
     BEAM_STAGE_MARK(4);
-    BEAM_TRY_HIP(launch_down(s, ws + L.hidden, w_down, offsets, np, wl, y_pairs, stream));
+    BEAM_TRY_HIP(launch_down(se, ws + L.hidden, w_down, offsets, np, wl, y_pairs, stream));
     BEAM_STAGE_MARK(5);
-    BEAM_TRY_HIP(launch_combine(s, y_pairs, gw, mids, inv, out, stream));
+    BEAM_TRY_HIP(launch_combine(se, y_pairs, gw, mids, inv, residual, out, stream));
     BEAM_STAGE_MARK(6);
 #undef BEAM_STAGE_MARK
     return BEAM_OK;
@@ -330,9 +353,34 @@ beam_status beam_moe_forward(const beam_shape *shape, const void *x, const void 
                              int32_t *topk_ids_opt, float *topk_weights_opt,
                              int32_t *masked_ids_opt, int32_t *num_pairs_opt, void *workspace,
                              size_t workspace_bytes, void *hip_stream) {
-    return moe_forward_impl(shape, x, w_router, router_bias, w_mask, mask_bias, w_gate_up, w_down,
-                            out, topk_ids_opt, topk_weights_opt, masked_ids_opt, num_pairs_opt,
-                            workspace, workspace_bytes, hip_stream, nullptr);
+    return moe_forward_impl(shape, 0, x, w_router, router_bias, w_mask, mask_bias, w_gate_up,
+                            w_down, nullptr, nullptr, out, topk_ids_opt, topk_weights_opt,
+                            masked_ids_opt, num_pairs_opt, workspace, workspace_bytes, hip_stream,
+                            nullptr);
+}
+
+size_t beam_block_workspace_bytes(const beam_shape *shape, int32_t num_shared) {
+    if (check_shape(shape) != BEAM_OK || num_shared < 0) return 0;
+    beam_shape se = *shape;
+    se.N += num_shared;
+    se.K += num_shared;
+    if (se.N > 256 || se.K > 64 || (long)se.T * se.K >= (1L << 24)) return 0;
+    if (se.weight_layout == BEAM_WEIGHTS_PACKED && !tiled_ffn_supported(se)) return 0;
+    return ws_layout(se).total;
+}
+
+beam_status beam_moe_block_forward(const beam_shape *shape, int32_t num_shared, const void *x,
+                                   const void *w_router, const float *router_bias,
+                                   const void *w_mask, const float *mask_bias,
+                                   const void *w_gate_up, const void *w_down,
+                                   const void *w_shared_gate, const void *residual, void *out,
+                                   int32_t *topk_ids_opt, float *topk_weights_opt,
+                                   int32_t *masked_ids_opt, int32_t *num_pairs_opt,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream) {
+    return moe_forward_impl(shape, num_shared, x, w_router, router_bias, w_mask, mask_bias,
+                            w_gate_up, w_down, w_shared_gate, residual, out, topk_ids_opt,
+                            topk_weights_opt, masked_ids_opt, num_pairs_opt, workspace,
+                            workspace_bytes, hip_stream, nullptr);
 }
 
 beam_status beam_moe_forward_timed(const beam_shape *shape, const void *x, const void *w_router,
@@ -344,9 +392,10 @@ beam_status beam_moe_forward_timed(const beam_shape *shape, const void *x, const
     if (!stage_ms_host) return BEAM_ERR_INVALID_ARG;
     hipEvent_t ev[BEAM_NUM_STAGES + 1];
     for (int i = 0; i <= BEAM_NUM_STAGES; ++i) BEAM_TRY_HIP(hipEventCreate(&ev[i]));
-    beam_status st = moe_forward_impl(shape, x, w_router, router_bias, w_mask, mask_bias,
-                                      w_gate_up, w_down, out, nullptr, nullptr, nullptr, nullptr,
-                                      workspace, workspace_bytes, hip_stream, ev);
+    beam_status st = moe_forward_impl(shape, 0, x, w_router, router_bias, w_mask, mask_bias,
+                                      w_gate_up, w_down, nullptr, nullptr, out, nullptr, nullptr,
+                                      nullptr, nullptr, workspace, workspace_bytes, hip_stream,
+                                      ev);
     if (st == BEAM_OK && shape->T > 0) {
         if (hipEventSynchronize(ev[BEAM_NUM_STAGES]) != hipSuccess) st = BEAM_ERR_HIP;
         for (int i = 0; st == BEAM_OK && i < BEAM_NUM_STAGES; ++i)

@@ -1,5 +1,6 @@
 // Masked aggregation (paper Eq. 7-8): out[t] = sum_k m_k g_k E_{id_k}(x_t) over
-// the kept slots of token t, in slot order, fp32 accumulate, one rounding.  A
+// the kept slots of token t, in slot order, fp32 accumulate, one rounding.  With
+// a residual h (App. A.3) the sum starts from h[t] instead of zero.  A
 // gather over the expert-sorted rows: every output element is written exactly
 // once with coalesced accesses and no atomics, and a token with no kept expert
 // gets an exactly +0 row (App. A.3).
@@ -13,6 +14,13 @@ __device__ __forceinline__ void store4(bf16_t *p, float4 v) {
     q.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
     q.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
     *(uint2 *)p = q;
+}
+
+__device__ __forceinline__ float4 load4(const float *p) { return *(const float4 *)p; }
+__device__ __forceinline__ float4 load4(const bf16_t *p) {
+    const uint2 q = *(const uint2 *)p;
+    return make_float4(__uint_as_float(q.x << 16), __uint_as_float(q.x & 0xffff0000u),
+                       __uint_as_float(q.y << 16), __uint_as_float(q.y & 0xffff0000u));
 }
 
 __device__ __forceinline__ void axpy4(float g, const float4 &y, float4 &acc) {
@@ -33,7 +41,7 @@ template <typename T, int CH>
 __global__ __launch_bounds__(256) void combine_wave_kernel(
     const float *__restrict__ y_pairs, const float *__restrict__ topk_w,
     const int32_t *__restrict__ masked_ids, const int32_t *__restrict__ inv_perm,
-    T *__restrict__ out, int Tn, int H, int K) {
+    const T *__restrict__ residual, T *__restrict__ out, int Tn, int H, int K) {
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (t >= Tn) return;  // wave-uniform
@@ -48,7 +56,9 @@ __global__ __launch_bounds__(256) void combine_wave_kernel(
     for (int c0 = lane * 4; c0 < H; c0 += 256 * CH) {
         float4 acc[CH];
 #pragma unroll
-        for (int i = 0; i < CH; ++i) acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int i = 0; i < CH; ++i)
+            acc[i] = residual ? load4(residual + (size_t)t * H + c0 + i * 256)
+                              : make_float4(0.f, 0.f, 0.f, 0.f);
         uint64_t m = kept;
         while (m) {
             const int ka = __builtin_ctzll(m);
@@ -88,13 +98,14 @@ template <typename T>
 __global__ __launch_bounds__(256) void combine_generic_kernel(
     const float *__restrict__ y_pairs, const float *__restrict__ topk_w,
     const int32_t *__restrict__ masked_ids, const int32_t *__restrict__ inv_perm,
-    T *__restrict__ out, int Tn, int H, int K) {
+    const T *__restrict__ residual, T *__restrict__ out, int Tn, int H, int K) {
     const int t = blockIdx.x;
     const int32_t *ids = masked_ids + (size_t)t * K;
     const int32_t *inv = inv_perm + (size_t)t * K;
     const float *w = topk_w + (size_t)t * K;
     for (int c = threadIdx.x * 4; c < H; c += 1024) {
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 acc = residual ? load4(residual + (size_t)t * H + c)
+                              : make_float4(0.f, 0.f, 0.f, 0.f);
         for (int k = 0; k < K; ++k) {
             const int row = inv[k];
             if (ids[k] < 0 || row < 0) continue;
@@ -106,30 +117,34 @@ __global__ __launch_bounds__(256) void combine_generic_kernel(
 
 template <typename T>
 static void launch_typed(const beam_shape &s, const float *y_pairs, const float *topk_w,
-                         const int32_t *masked_ids, const int32_t *inv_perm, T *out,
-                         hipStream_t st) {
+                         const int32_t *masked_ids, const int32_t *inv_perm, const T *residual,
+                         T *out, hipStream_t st) {
     // decode-sized batches: one wavefront per workgroup, to spread over the CUs
     const int wpb = s.T <= 1024 ? 1 : 4;
     const dim3 wave_grid((s.T + wpb - 1) / wpb);
 #define BEAM_COMBINE_WAVE(CH)                                                                   \
-    combine_wave_kernel<T, CH><<<wave_grid, 64 * wpb, 0, st>>>(y_pairs, topk_w, masked_ids,     \
-                                                               inv_perm, out, s.T, s.H, s.K)
+    combine_wave_kernel<T, CH><<<wave_grid, 64 * wpb, 0, st>>>(                                 \
+        y_pairs, topk_w, masked_ids, inv_perm, residual, out, s.T, s.H, s.K)
     if (s.H % 2048 == 0) BEAM_COMBINE_WAVE(8);
     else if (s.H % 1024 == 0) BEAM_COMBINE_WAVE(4);
+    else if (s.H % 512 == 0) BEAM_COMBINE_WAVE(2);
     else if (s.H % 256 == 0) BEAM_COMBINE_WAVE(1);
     else
         combine_generic_kernel<T><<<dim3(s.T), 256, 0, st>>>(y_pairs, topk_w, masked_ids,
-                                                             inv_perm, out, s.T, s.H, s.K);
+                                                             inv_perm, residual, out, s.T, s.H,
+                                                             s.K);
 #undef BEAM_COMBINE_WAVE
 }
 
 hipError_t launch_combine(const beam_shape &s, const float *y_pairs, const float *topk_w,
-                          const int32_t *masked_ids, const int32_t *inv_perm, void *out,
-                          hipStream_t st) {
+                          const int32_t *masked_ids, const int32_t *inv_perm,
+                          const void *residual, void *out, hipStream_t st) {
     if (s.dtype == BEAM_BF16)
-        launch_typed<bf16_t>(s, y_pairs, topk_w, masked_ids, inv_perm, (bf16_t *)out, st);
+        launch_typed<bf16_t>(s, y_pairs, topk_w, masked_ids, inv_perm, (const bf16_t *)residual,
+                             (bf16_t *)out, st);
     else
-        launch_typed<float>(s, y_pairs, topk_w, masked_ids, inv_perm, (float *)out, st);
+        launch_typed<float>(s, y_pairs, topk_w, masked_ids, inv_perm, (const float *)residual,
+                            (float *)out, st);
     return hipGetLastError();
 }
 

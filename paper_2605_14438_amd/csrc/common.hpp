@@ -65,6 +65,7 @@ struct WsLayout {
     size_t topk_ids;       // [T,K] i32
     size_t topk_w;         // [T,K] f32
     size_t masked_ids;     // [T,K] i32
+    size_t g_shared;       // [T] f32 : weight of the shared-expert slots (block entry point)
     size_t blk_counts;     // [nchunk,N] i32 : kept pairs per (chunk, expert)
     size_t blk_base;       // [nchunk,N] i32 : exclusive prefix over chunks
     size_t counts;         // [N] i32
@@ -103,10 +104,12 @@ WorkList work_list(void *base, const beam_shape &s, int max_tiles);
 hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_router,
                          const float *b_router, const void *w_mask, const float *b_mask,
                          float *router_logits, float *mask_logits, hipStream_t st);
+hipError_t launch_shared_gate(const beam_shape &s, const void *x, const void *w_shared_gate,
+                              float *g_shared, hipStream_t st);
 hipError_t launch_topk_mask(const beam_shape &s, const float *router_logits,
                             const float *mask_logits, const float *b_router, const float *b_mask,
-                            int row_stride, int32_t *topk_ids, float *topk_w, int32_t *masked_ids,
-                            hipStream_t st);
+                            int row_stride, int S, const float *g_shared, int32_t *topk_ids,
+                            float *topk_w, int32_t *masked_ids, hipStream_t st);
 bool logits_tiled_supported(const beam_shape &s);
 hipError_t launch_logits_tiled(const beam_shape &s, const void *x, const void *w_router,
                                const void *w_mask, void *packed_heads, float *logits2,
@@ -124,7 +127,7 @@ hipError_t launch_down(const beam_shape &s, const void *hidden, const void *w_do
                        const int32_t *offsets, const int32_t *num_pairs, const WorkList &wl,
                        float *y_pairs, hipStream_t st);
 hipError_t launch_combine(const beam_shape &s, const float *y_pairs, const float *topk_w,
-                          const int32_t *masked_ids, const int32_t *inv_perm, void *out,
-                          hipStream_t st);
+                          const int32_t *masked_ids, const int32_t *inv_perm,
+                          const void *residual, void *out, hipStream_t st);
 
 }  // namespace beam

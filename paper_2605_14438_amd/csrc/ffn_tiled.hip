@@ -98,7 +98,10 @@ struct TileItem {
 // tiles), which the schedule with two workgroups per CU cannot afford: there
 // CHAIN is off, every item starts with its own prologue, and the other
 // workgroup's MFMAs cover it.
-template <int BM, int WM, int KS, bool GATE_UP, bool PACKED, bool CHAIN, typename NextItem>
+// COL_GUARD (down roles only): the output is narrower than the last column tile;
+// columns >= H are computed from zero padding and not stored.
+template <int BM, int WM, int KS, bool GATE_UP, bool PACKED, bool CHAIN, bool COL_GUARD,
+          typename NextItem>
 __device__ __forceinline__ void ffn_tile_run(
     u32x4 *As, const bf16_t *__restrict__ a_src, const bf16_t *__restrict__ w,
     const int32_t *__restrict__ perm, bf16_t *__restrict__ hidden_out, float *__restrict__ y_out,
@@ -338,7 +341,10 @@ __device__ __forceinline__ void ffn_tile_run(
                     if (grow >= done.row_end) continue;
                     float *orow = y_out + (size_t)grow * H + n0 + l32;
 #pragma unroll
-                    for (int n = 0; n < WTN; ++n) orow[(wn * WTN + n) * 32] = acc[m][n][r];
+                    for (int n = 0; n < WTN; ++n) {
+                        if (COL_GUARD && n0 + l32 + (wn * WTN + n) * 32 >= H) continue;
+                        orow[(wn * WTN + n) * 32] = acc[m][n][r];
+                    }
                 }
             }
         }
@@ -400,8 +406,8 @@ __global__ __launch_bounds__(256, OCC) void ffn_tile_kernel(
             return true;
         }
     };
-    ffn_tile_run<kTileM, WM, KS, GATE_UP, PACKED, OCC == 1>(As, a_src, w, perm, hidden_out, y_out,
-                                                            H, K, I, next_item);
+    ffn_tile_run<kTileM, WM, KS, GATE_UP, PACKED, OCC == 1, false>(
+        As, a_src, w, perm, hidden_out, y_out, H, K, I, next_item);
 }
 
 bool tiled_ffn_supported(const beam_shape &s) {
@@ -466,16 +472,21 @@ __global__ __launch_bounds__(256) void pack_heads_kernel(const uint4 *__restrict
                                                          const uint4 *__restrict__ w_mask,
                                                          uint4 *__restrict__ dst, int N, int H) {
     const int ksteps = H >> 4;
-    const int total = 2 * N * (H >> 3);
+    const int rows = (2 * N + kTileN - 1) / kTileN * kTileN;  // zero rows pad the last column tile
+    const int total = rows * (H >> 3);
     for (int o = blockIdx.x * 256 + threadIdx.x; o < total; o += gridDim.x * 256) {
         const int l = o & 63;
         const int frag = o >> 6;
         const int ks = frag % ksteps;
         const int rb = frag / ksteps;
         const int row = rb * 32 + (l & 31);
-        const uint4 *src = row < N ? w_router + (size_t)row * (H >> 3)
-                                   : w_mask + (size_t)(row - N) * (H >> 3);
-        dst[o] = src[ks * 2 + (l >> 5)];
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (row < 2 * N) {
+            const uint4 *src = row < N ? w_router + (size_t)row * (H >> 3)
+                                       : w_mask + (size_t)(row - N) * (H >> 3);
+            v = src[ks * 2 + (l >> 5)];
+        }
+        dst[o] = v;
     }
 }
 
@@ -490,7 +501,7 @@ __global__ __launch_bounds__(256, 2) void logits_tile_kernel(
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ packed_heads,
     float *__restrict__ logits2, int Tn, int H, int N2) {
     __shared__ u32x4 As[2 * kLogitsM * 2 * kLogitsKS];
-    const int nct = N2 / kTileN;
+    const int nct = (N2 + kTileN - 1) / kTileN;
     const int n_work = ((Tn + kLogitsM - 1) / kLogitsM) * nct;
     auto next_item = [&](int &round, TileItem &it) -> bool {
         const int item = blockIdx.x + round * gridDim.x;
@@ -503,12 +514,12 @@ __global__ __launch_bounds__(256, 2) void logits_tile_kernel(
         return true;
     };
     // down-GEMM roles: output width N2, reduction length H, a single expert
-    ffn_tile_run<kLogitsM, kWavesM, kLogitsKS, false, true, true>(
+    ffn_tile_run<kLogitsM, kWavesM, kLogitsKS, false, true, true, true>(
         As, x, packed_heads, nullptr, nullptr, logits2, N2, 1, H, next_item);
 }
 
 bool logits_tiled_supported(const beam_shape &s) {
-    return s.dtype == BEAM_BF16 && s.T >= 1024 && s.H % 256 == 0 && (2 * s.N) % kTileN == 0 &&
+    return s.dtype == BEAM_BF16 && s.T >= 1024 && s.H % 256 == 0 &&
            (long)s.T * s.H < (1L << 32);
 }
 
@@ -517,7 +528,7 @@ hipError_t launch_logits_tiled(const beam_shape &s, const void *x, const void *w
                                hipStream_t st) {
     pack_heads_kernel<<<256, 256, 0, st>>>((const uint4 *)w_router, (const uint4 *)w_mask,
                                            (uint4 *)packed_heads, s.N, s.H);
-    const int n_work = ((s.T + kLogitsM - 1) / kLogitsM) * (2 * s.N / kTileN);
+    const int n_work = ((s.T + kLogitsM - 1) / kLogitsM) * ((2 * s.N + kTileN - 1) / kTileN);
     const int grid = n_work < 512 ? n_work : 512;
     logits_tile_kernel<<<grid, 256, 0, st>>>((const bf16_t *)x, (const bf16_t *)packed_heads,
                                              logits2, s.T, s.H, 2 * s.N);

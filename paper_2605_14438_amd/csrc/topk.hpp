@@ -66,10 +66,13 @@ __device__ __forceinline__ float key_logit(uint64_t key) {
 // weights over the K survivors and the masked id (a >= 0 keeps, otherwise -1).
 // br / bm: optional biases still to be added to r / a (NULL if the logits already
 // include them).
+// Shared experts (App. A.3): lanes K .. K+S-1 append S always-kept slots for the
+// experts N .. N+S-1 with weight g_shared; the three outputs are rows of K+S.
 __device__ __forceinline__ void wave_route_token(const float *__restrict__ r,
                                                  const float *__restrict__ a,
                                                  const float *__restrict__ br,
                                                  const float *__restrict__ bm, int N, int K,
+                                                 int S, float g_shared,
                                                  int32_t *__restrict__ ids_out,
                                                  float *__restrict__ w_out,
                                                  int32_t *__restrict__ masked_out) {
@@ -104,6 +107,10 @@ __device__ __forceinline__ void wave_route_token(const float *__restrict__ r,
         ids_out[lane] = my_id;
         w_out[lane] = ex / denom;
         masked_out[lane] = key_keep(mine) ? my_id : -1;
+    } else if (lane < K + S) {
+        ids_out[lane] = N + lane - K;
+        w_out[lane] = g_shared;
+        masked_out[lane] = N + lane - K;
     }
 }
 
@@ -111,7 +118,8 @@ __device__ __forceinline__ void wave_route_token(const float *__restrict__ r,
 // per wavefront.  Lane j of a row holds candidates j*NPL .. j*NPL+NPL-1 (N <=
 // 16*NPL), so the arg-max reductions stay inside a row: four DPP steps, no
 // cross-row traffic, and every lane of the row ends up with the row's best key.
-// Same keys, same K rounds, same softmax as wave_route_token; needs K <= 16.
+// Same keys, same K rounds, same softmax and shared-expert slots as
+// wave_route_token; needs K + S <= 16.
 // `valid` is row-uniform (false for the rows past the last token).
 __device__ __forceinline__ uint64_t row_max_u64(uint64_t key) {
     max_step<0xB1, 0xf>(key);   // quad_perm [1,0,3,2]
@@ -134,7 +142,8 @@ __device__ __forceinline__ void row_route_token(const float *__restrict__ r,
                                                 const float *__restrict__ a,
                                                 const float *__restrict__ br,
                                                 const float *__restrict__ bm, int N, int K,
-                                                bool valid, int32_t *__restrict__ ids_out,
+                                                int S, float g_shared, bool valid,
+                                                int32_t *__restrict__ ids_out,
                                                 float *__restrict__ w_out,
                                                 int32_t *__restrict__ masked_out) {
     static_assert(NPL % 4 == 0, "candidates are loaded four at a time");
@@ -181,6 +190,10 @@ __device__ __forceinline__ void row_route_token(const float *__restrict__ r,
         ids_out[j] = my_id;
         w_out[j] = ex / denom;
         masked_out[j] = key_keep(mine) ? my_id : -1;
+    } else if (valid && j < K + S) {
+        ids_out[j] = N + j - K;
+        w_out[j] = g_shared;
+        masked_out[j] = N + j - K;
     }
 }
 

@@ -14,6 +14,13 @@ K experts per token, I = expert intermediate size.  Weight layouts are
     w_gate_up [N, 2I, H]  rows 0..I-1 = W_gate^T, rows I..2I-1 = W_up^T   (Eq. 3)
     w_down    [N, H, I]   W_down^T                      (Eq. 3)
 
+With a shared expert (App. A.3; S > 0) there are also, drawn last so that the
+streams of the routed layer do not move:
+
+    w_sh_gate_up [2*S*I, H], w_sh_down [H, S*I]   one GLU expert of width S*I
+    w_sh_gate    [H]      gate vector of the shared expert's weight (optional)
+    residual     [T, H]   the block input h before normalisation, ~ N(0, 1)
+
 The recipe (value distributions, keep-rate calibration, popularity skew) is a
 stand-in for real model activations, which need trained weights:
 
@@ -64,6 +71,8 @@ class LayerConfig:
     keep_mode: str = "uniform"  # "uniform" | "beta"
     beta_a: float = 2.0
     beta_b: float = 8.0
+    S: int = 0                  # shared expert of width S*I (0 = none)
+    shared_gate: bool = False   # draw a gate vector for the shared expert's weight
 
     def with_(self, **kw) -> "LayerConfig":
         return replace(self, **kw)
@@ -81,6 +90,12 @@ CONFIGS: Dict[str, LayerConfig] = {
                            dtype="bf16", keep=0.6),
     "large": LayerConfig("large", 4, T=64, H=4096, N=128, K=8, I=1536,
                          dtype="bf16", keep=0.2, keep_mode="beta"),
+    # The two shared-expert models of the paper's evaluation (App. A.5): 60 routed
+    # experts, 4 per token, 4 shared (gated); 64 routed, 6 per token, 2 shared.
+    "qwen15_moe": LayerConfig("qwen15_moe", 5, T=64, H=2560, N=60, K=4, I=1408,
+                              dtype="bf16", keep=0.25, S=4, shared_gate=True),
+    "dsv2_lite": LayerConfig("dsv2_lite", 6, T=64, H=2048, N=64, K=6, I=1408,
+                             dtype="bf16", keep=0.25, S=2),
 }
 
 
@@ -175,7 +190,31 @@ def make_layer(cfg: LayerConfig, sweep: int = 0, with_experts: bool = True) -> D
             w_gate_up = bf16_round(w_gate_up)
             w_down = bf16_round(w_down)
     out.update(x=x, w_router=w_router, w_mask=w_mask, w_gate_up=w_gate_up, w_down=w_down)
+    if cfg.S > 0:
+        rnd = bf16_round if cfg.dtype == "bf16" else (lambda a: a)
+        if with_experts:
+            out["w_sh_gate_up"] = rnd(_normal(rng, (2 * cfg.S * I, H), _INIT_STD))
+            out["w_sh_down"] = rnd(_normal(rng, (H, cfg.S * I), _INIT_STD))
+        out["w_sh_gate"] = rnd(_normal(rng, (H,), _INIT_STD)) if cfg.shared_gate else None
+        out["residual"] = rnd(_normal(rng, (T, H), 1.0))
     return out
+
+
+def append_shared_blocks(cfg: LayerConfig, data: Dict[str, Optional[np.ndarray]]):
+    """Expert arrays with the shared expert cut into S column blocks of width I
+    and appended as experts N .. N+S-1 (a copy; the layout the library's block
+    entry point takes).  Returns (w_gate_up [N+S,2I,H], w_down [N+S,H,I])."""
+    S, I, H = cfg.S, cfg.I, cfg.H
+    sgu, sd = data["w_sh_gate_up"], data["w_sh_down"]
+    gu = np.empty((cfg.N + S, 2 * I, H), dtype=np.float32)
+    dn = np.empty((cfg.N + S, H, I), dtype=np.float32)
+    gu[:cfg.N] = data["w_gate_up"]
+    dn[:cfg.N] = data["w_down"]
+    for j in range(S):
+        gu[cfg.N + j, :I] = sgu[j * I:(j + 1) * I]
+        gu[cfg.N + j, I:] = sgu[S * I + j * I:S * I + (j + 1) * I]
+        dn[cfg.N + j] = sd[:, j * I:(j + 1) * I]
+    return gu, dn
 
 
 def redraw_rows(cfg: LayerConfig, data: Dict[str, Optional[np.ndarray]], rows: np.ndarray,

@@ -71,6 +71,46 @@ def forward(cfg, g, T=None, packed=False):
             "masked_ids": mids.cpu().numpy(), "num_pairs": int(npairs.item())}
 
 
+def block_forward(cfg, d, g=None, T=None, packed=False, use_gate=True, use_residual=True,
+                  S=None):
+    """beam_moe_block_forward on layer data d (host) with the shared expert cut
+    into cfg.S blocks and appended to the expert arrays; returns host arrays."""
+    T = cfg.T if T is None else T
+    S = cfg.S if S is None else S
+    if g is None:
+        g = upload(cfg, d)
+    if S > 0:
+        gu, dn = synth.append_shared_blocks(cfg, d)
+        w_gate_up, w_down = dev(gu, cfg.dtype), dev(dn, cfg.dtype)
+    else:
+        w_gate_up, w_down = g["w_gate_up"], g["w_down"]
+    s = shape_of(cfg, T, packed=packed)
+    if packed:
+        sp = beam.make_shape(0, cfg.H, cfg.N + S, cfg.K, cfg.I, s.dtype)
+        pg, pd = torch.empty_like(w_gate_up), torch.empty_like(w_down)
+        beam.beam_pack_weights(sp, w_gate_up, w_down, pg, pd, stream_ptr())
+        w_gate_up, w_down = pg, pd
+    nb = beam.beam_block_workspace_bytes(s, S)
+    assert nb > 0
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    gate = dev(d["w_sh_gate"], cfg.dtype) if (use_gate and S > 0 and
+                                              d.get("w_sh_gate") is not None) else None
+    res = dev(d["residual"][:T], cfg.dtype) if use_residual else None
+    out = out_tensor(cfg, T)
+    KS = cfg.K + S
+    ids = torch.full((T, KS), -7, dtype=torch.int32, device="cuda")
+    gw = torch.full((T, KS), float("nan"), dtype=torch.float32, device="cuda")
+    mids = torch.full((T, KS), -7, dtype=torch.int32, device="cuda")
+    npairs = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    beam.beam_moe_block_forward(s, S, g["x"], g["w_router"], g["b_router"], g["w_mask"],
+                                g["b_mask"], w_gate_up, w_down, gate, res, out, ids, gw, mids,
+                                npairs, ws, nb, stream_ptr())
+    torch.cuda.synchronize()
+    return {"out": out.float().cpu().numpy().astype(np.float64),
+            "topk_ids": ids.cpu().numpy(), "topk_weights": gw.cpu().numpy(),
+            "masked_ids": mids.cpu().numpy(), "num_pairs": int(npairs.item())}
+
+
 def output_error(got, ref, dtype: str):
     """Return (literal metric, worst ratio to the element-wise bound).
 

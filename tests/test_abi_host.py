@@ -121,7 +121,7 @@ def test_pack_weights_argument_checks(lib):
     s32 = beam.make_shape(0, 256, 8, 2, 512, beam.BEAM_F32)
     assert beam.beam_pack_weights(s32, ok, ok, ok + 0x100, ok + 0x200, check=False) == \
         binding.BEAM_ERR_UNSUPPORTED
-    assert beam.beam_abi_version() == 2
+    assert beam.beam_abi_version() == 3
 
 
 def test_zero_tokens_is_ok_without_launch(lib):

@@ -458,3 +458,157 @@ def test_moe_forward_large_full_size(T, packed):
     if T == 8192:
         assert 0.15 < kept.mean() / 8 < 0.25        # Beta(2,8): mean ~20%
         assert kept.max() >= 7 and kept.min() == 0  # heavy tail
+
+
+# ---------------------------------------------------------------------------
+# beam_moe_block_forward: residual + routed experts + shared expert (App. A.3)
+# ---------------------------------------------------------------------------
+BLOCK_SMALL = synth.LayerConfig("block_small", 6, T=97, H=512, N=12, K=3, I=128, dtype="bf16",
+                                keep=0.4, S=2, shared_gate=True)
+BLOCK_F32 = synth.LayerConfig("block_f32", 7, T=33, H=64, N=6, K=2, I=24, dtype="f32", keep=0.5,
+                              S=3, shared_gate=True)
+# tiled GEMMs, four-tokens-per-wavefront Top-K with appended slots, tiled logits
+# with 2N = 40 columns (narrower than a column tile)
+BLOCK_PREFILL = synth.LayerConfig("block_prefill", 8, T=1300, H=512, N=20, K=4, I=256,
+                                  dtype="bf16", keep=0.3, router_skew="zipf", S=1)
+
+
+def _block_ref(cfg, d, x=None, residual=None, use_gate=True, use_residual=True, S=None):
+    S = cfg.S if S is None else S
+    x = d["x"] if x is None else x
+    residual = d["residual"] if residual is None else residual
+    return oracle.block_forward(
+        x, d["w_router"], d["b_router"], d["w_mask"], d["b_mask"], d["w_gate_up"], d["w_down"],
+        cfg.K, w_sh_gate_up=d["w_sh_gate_up"] if S > 0 else None,
+        w_sh_down=d["w_sh_down"] if S > 0 else None,
+        w_sh_gate=d["w_sh_gate"] if (use_gate and S > 0) else None,
+        residual=residual if use_residual else None)
+
+
+def _check_block_slots(cfg, res, ids_o, g_o, msk_o, g_shared, S):
+    K, N, T = cfg.K, cfg.N, ids_o.shape[0]
+    assert np.array_equal(res["topk_ids"][:, :K], ids_o)
+    assert np.array_equal(res["masked_ids"][:, :K], msk_o)
+    np.testing.assert_allclose(res["topk_weights"][:, :K], g_o, atol=2e-6, rtol=0)
+    shared_ids = np.broadcast_to(N + np.arange(S, dtype=np.int32), (T, S))
+    assert np.array_equal(res["topk_ids"][:, K:], shared_ids)
+    assert np.array_equal(res["masked_ids"][:, K:], shared_ids)      # never masked
+    np.testing.assert_allclose(res["topk_weights"][:, K:],
+                               np.broadcast_to(g_shared[:, None], (T, S)), atol=2e-6, rtol=0)
+    assert res["num_pairs"] == int((msk_o >= 0).sum()) + T * S
+
+
+@pytest.mark.parametrize("cfg,use_gate,use_residual,packed", [
+    (BLOCK_SMALL, True, True, False), (BLOCK_SMALL, False, False, False),
+    (BLOCK_SMALL, True, True, True), (BLOCK_SMALL.with_(T=3), True, True, False),
+    (BLOCK_F32, True, True, False), (BLOCK_F32, False, True, False),
+    (BLOCK_PREFILL, False, True, False), (BLOCK_PREFILL, False, True, True),
+    (BLOCK_PREFILL.with_(shared_gate=True, S=3, T=1029), True, False, True),
+], ids=lambda v: getattr(v, "name", str(v)))
+def test_moe_block_forward_small(cfg, use_gate, use_residual, packed):
+    _log(f"moe_block_forward {cfg} gate={use_gate} residual={use_residual} packed={packed}")
+    d = hp.make_tie_free(cfg)
+    ref = _block_ref(cfg, d, use_gate=use_gate, use_residual=use_residual)
+    res = hp.block_forward(cfg, d, packed=packed, use_gate=use_gate, use_residual=use_residual)
+    _check_block_slots(cfg, res, ref["topk_ids"], ref["topk_weights"], ref["masked_ids"],
+                       ref["g_shared"], cfg.S)
+    literal, ratio = hp.output_error(res["out"], ref["out"], cfg.dtype)
+    _log(f"  max|err|/RMS={literal:.4f} worst/bound={ratio:.3f}")
+    assert ratio <= 1.0
+    if use_residual:
+        # the residual must not hide the experts' part: same bound on out - h, measured
+        # against the RMS of the experts' part (one more bf16 rounding of a value ~|h|)
+        part = ref["out"] - d["residual"].astype(np.float64)
+        err = np.abs(res["out"] - ref["out"])
+        tol = 2e-2 * np.sqrt((part ** 2).mean()) + 2.0 ** -8 * np.abs(ref["out"])
+        assert (err <= tol).all() or cfg.dtype == "f32"
+
+
+def test_moe_block_forward_zero_activation():
+    """Every routed expert masked (App. A.3): with a shared expert the block is
+    h + g_sh E_sh(x); without one the token bypasses the block, out == h bit for bit."""
+    cfg = BLOCK_SMALL.with_(keep=0.0)
+    d = hp.make_tie_free(cfg)
+    ref = _block_ref(cfg, d)
+    assert (ref["masked_ids"] == -1).all()
+    res = hp.block_forward(cfg, d)
+    assert (res["masked_ids"][:, :cfg.K] == -1).all() and res["num_pairs"] == cfg.T * cfg.S
+    _, ratio = hp.output_error(res["out"], ref["out"], cfg.dtype)
+    assert ratio <= 1.0
+    res0 = hp.block_forward(cfg, d, S=0)
+    assert res0["num_pairs"] == 0
+    assert np.array_equal(res0["out"], d["residual"].astype(np.float64))
+
+
+def test_moe_block_forward_without_shared_expert_is_layer_plus_residual():
+    cfg = BLOCK_SMALL
+    d = hp.make_tie_free(cfg)
+    ref = _block_ref(cfg, d, S=0)
+    res = hp.block_forward(cfg, d, S=0)
+    assert np.array_equal(res["masked_ids"], ref["masked_ids"])
+    _, ratio = hp.output_error(res["out"], ref["out"], cfg.dtype)
+    assert ratio <= 1.0
+    # and with neither it is beam_moe_forward
+    plain = hp.forward(cfg, hp.upload(cfg, d))
+    res_plain = hp.block_forward(cfg, d, S=0, use_residual=False)
+    assert np.array_equal(res_plain["out"], plain["out"])
+
+
+def test_moe_block_forward_argument_checks():
+    cfg = BLOCK_SMALL
+    s = hp.shape_of(cfg)
+    assert beam.beam_block_workspace_bytes(s, -1) == 0
+    assert beam.beam_block_workspace_bytes(s, 250) == 0          # N + S > 256
+    assert beam.beam_block_workspace_bytes(s, 2) >= beam.beam_workspace_bytes(s)
+    d = hp.make_tie_free(cfg)
+    g = hp.upload(cfg, d)
+    nb = beam.beam_block_workspace_bytes(s, 0)
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    out = hp.out_tensor(cfg)
+    gate = hp.dev(d["w_sh_gate"], cfg.dtype)
+    # a gate vector without a shared expert is an error; so is a short workspace for S = 2
+    st = beam.beam_moe_block_forward(s, 0, g["x"], g["w_router"], g["b_router"], g["w_mask"],
+                                     g["b_mask"], g["w_gate_up"], g["w_down"], gate, None, out,
+                                     None, None, None, None, ws, nb, hp.stream_ptr(), check=False)
+    assert st == beam.binding.BEAM_ERR_INVALID_ARG
+    st = beam.beam_moe_block_forward(s, 2, g["x"], g["w_router"], g["b_router"], g["w_mask"],
+                                     g["b_mask"], g["w_gate_up"], g["w_down"], gate, None, out,
+                                     None, None, None, None, ws, nb, hp.stream_ptr(), check=False)
+    assert st == beam.binding.BEAM_ERR_WORKSPACE
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name,T,packed", [("qwen15_moe", 64, False), ("qwen15_moe", 1, False),
+                                           ("dsv2_lite", 64, False), ("dsv2_lite", 4096, True),
+                                           ("qwen15_moe", 2048, True)])
+def test_moe_block_forward_full_size(name, T, packed):
+    """The two shared-expert models of the paper's evaluation at full layer size."""
+    cfg = CFG[name].with_(T=T)
+    _log(f"moe_block_forward full size {cfg} packed={packed}")
+    d = hp.make_tie_free(cfg)
+    ids_o, g_o, msk_o = oracle.route_mask(d["router_logits"], d["mask_logits"], cfg.K)
+    res = hp.block_forward(cfg, d, packed=packed)
+    kept = (msk_o >= 0).sum(axis=1)
+    if T <= 64:
+        sub = np.arange(T)
+    else:
+        rng = np.random.default_rng(T)
+        pick = set(np.argsort(-kept, kind="stable")[:4].tolist())
+        pick.update(np.flatnonzero(kept == 0)[:4].tolist())
+        pick.update(rng.choice(T, size=16, replace=False).tolist())
+        sub = np.array(sorted(pick))
+    ref = _block_ref(cfg, d, x=d["x"][sub], residual=d["residual"][sub])
+    g_sh = np.ones(T)
+    if cfg.shared_gate:                      # sigma(x . w) for every token, fp64
+        z = d["x"].astype(np.float64) @ d["w_sh_gate"].astype(np.float64)
+        g_sh = 1.0 / (1.0 + np.exp(-z))
+        np.testing.assert_allclose(g_sh[sub], ref["g_shared"], atol=1e-12, rtol=0)
+    _check_block_slots(cfg, res, ids_o, g_o, msk_o, g_sh, cfg.S)
+    literal, ratio = hp.output_error(res["out"][sub], ref["out"], cfg.dtype)
+    part = ref["out"] - d["residual"][sub].astype(np.float64)
+    err = np.abs(res["out"][sub] - ref["out"])
+    tol = 2e-2 * np.sqrt((part ** 2).mean()) + 2.0 ** -8 * np.abs(ref["out"])
+    _log(f"  {name} T={T}: P={res['num_pairs']} kept/token mean {kept.mean():.2f}; {sub.size} "
+         f"tokens max|err|/RMS={literal:.4f} worst/bound={ratio:.3f} "
+         f"experts-part worst/bound={float((err / tol).max()):.3f}")
+    assert ratio <= 1.0 and (err <= tol).all()
