@@ -56,24 +56,28 @@ def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp, packed
     packed: the weight sets are in matrix-core fragment order (beam_pack_weights)."""
     import numpy as np
     s = hp.shape_of(cfg, packed=packed)
-    ws, nb = hp.workspace(s)
+    S = cfg.S     # shared-expert blocks (App. A.3 workloads): the block entry point runs
+    nb = beam.beam_block_workspace_bytes(s, S)
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
     out = hp.out_tensor(cfg)
-    mids = torch.empty((cfg.T, cfg.K), dtype=torch.int32, device="cuda")
+    mids = torch.empty((cfg.T, cfg.K + S), dtype=torch.int32, device="cuda")
     npairs = torch.zeros((1,), dtype=torch.int32, device="cuda")
     stream = hp.stream_ptr()
     nsets = len(weight_sets)
+    gate, res = g.get("w_sh_gate"), g.get("residual")
 
     def step(i, want_ids=False):
         wgu, wd = weight_sets[i % nsets]
-        beam.beam_moe_forward(s, g["x"], g["w_router"], g["b_router"], g["w_mask"], g["b_mask"],
-                              wgu, wd, out, None, None, mids if want_ids else None,
-                              npairs if want_ids else None, ws, nb, stream)
+        beam.beam_moe_block_forward(s, S, g["x"], g["w_router"], g["b_router"], g["w_mask"],
+                                    g["b_mask"], wgu, wd, gate, res, out, None, None,
+                                    mids if want_ids else None, npairs if want_ids else None,
+                                    ws, nb, stream)
 
     step(0, want_ids=True)
     torch.cuda.synchronize()
     m = mids.cpu().numpy()
-    P = int(npairs.item())
-    U = int(np.unique(m[m >= 0]).size)
+    P = int(npairs.item())                     # kept routed pairs + T*S shared slots
+    U = int(np.unique(m[m >= 0]).size)         # experts touched, shared blocks included
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
@@ -89,8 +93,9 @@ def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp, packed
     acc = [0.0] * beam.binding.BEAM_NUM_STAGES
     for i in range(nprof):
         wgu, wd = weight_sets[i % nsets]
-        _, st = beam.beam_moe_forward_timed(s, g["x"], g["w_router"], g["b_router"], g["w_mask"],
-                                            g["b_mask"], wgu, wd, out, ws, nb, stream)
+        _, st = beam.beam_moe_block_forward_timed(s, S, g["x"], g["w_router"], g["b_router"],
+                                                  g["w_mask"], g["b_mask"], wgu, wd, gate, res,
+                                                  out, ws, nb, stream)
         acc = [a + b for a, b in zip(acc, st)]
     stage_us = {n: 1e3 * a / nprof for n, a in zip(beam.binding.STAGE_NAMES, acc)}
 
@@ -98,7 +103,9 @@ def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp, packed
     H, I, N, T = cfg.H, cfg.I, cfg.N, cfg.T
     # algorithmic traffic: each touched expert's weights once (3*H*I elements:
     # 2I x H gate/up + H x I down), both routing heads, x in, out out
-    layer_bytes = U * 3 * H * I * esz + 2 * N * H * esz + 2 * T * H * esz
+    # (a shared expert of width S*I counts as its S blocks in U and T*S pairs in P;
+    # the residual is one more read of T*H)
+    layer_bytes = U * 3 * H * I * esz + 2 * N * H * esz + (3 if res is not None else 2) * T * H * esz
     layer_flops = P * 6 * H * I + 4 * T * H * N
     gate_up_bytes = U * 2 * H * I * esz + T * H * esz
     gate_up_flops = P * 4 * H * I
@@ -115,6 +122,18 @@ def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp, packed
         "gate_up": {"bytes": gate_up_bytes, "flops": gate_up_flops, "us": stage_us["gate_up"]},
         "ms_per_step": ms,
     }
+
+
+def upload_layer(cfg, d, hp, synth):
+    """Device buffers of a layer; with a shared expert its S blocks are appended
+    to the expert arrays and the gate vector and residual come along."""
+    g = hp.upload(cfg, d)
+    if cfg.S > 0:
+        gu, dn = synth.append_shared_blocks(cfg, d)
+        g["w_gate_up"], g["w_down"] = hp.dev(gu, cfg.dtype), hp.dev(dn, cfg.dtype)
+        g["w_sh_gate"] = hp.dev(d["w_sh_gate"], cfg.dtype)
+        g["residual"] = hp.dev(d["residual"], cfg.dtype)
+    return g
 
 
 def roofline_of(pt):
@@ -158,7 +177,7 @@ def main():
 
     t_gen = time.perf_counter()
     d = synth.make_layer(cfg)
-    g = hp.upload(cfg, d)
+    g = upload_layer(cfg, d, hp, synth)
     sets = [(g["w_gate_up"], g["w_down"])]
     for _ in range(max(1, args.weight_sets) - 1):
         sets.append((g["w_gate_up"].clone(), g["w_down"].clone()))
@@ -178,7 +197,7 @@ def main():
     def get_packed_sets():
         nonlocal packed_sets
         if packed_sets is None:
-            packed_sets = [hp.pack_weights(cfg, a, b) for a, b in sets]
+            packed_sets = [hp.pack_weights(cfg.with_(N=cfg.N + cfg.S), a, b) for a, b in sets]
             torch.cuda.synchronize()
         return packed_sets
 
@@ -200,6 +219,16 @@ def main():
             gg = {**hp.upload(c, dd), "w_gate_up": g["w_gate_up"], "w_down": g["w_down"]}
             points.append(measure_point(c, dd, gg, get_packed_sets(), n, 3, torch, beam, hp,
                                         packed=True))
+        # the two shared-expert model shapes (whole block: residual + routed + shared)
+        packed_sets = None           # free the repacked Qwen3 copies
+        for name in ("qwen15_moe", "dsv2_lite"):
+            c = synth.CONFIGS[name]
+            dd = synth.make_layer(c)
+            gg = upload_layer(c, dd, hp, synth)
+            bsets = [(gg["w_gate_up"], gg["w_down"]),
+                     (gg["w_gate_up"].clone(), gg["w_down"].clone())]
+            points.append(measure_point(c, dd, gg, bsets, psteps, 10, torch, beam, hp))
+            del dd, gg, bsets
     for p in points:
         p["roofline"] = roofline_of(p)
         p.pop("gate_up")
@@ -212,6 +241,12 @@ def main():
         xs = d["x"][:Ts]
 
         def run():
+            if cfg.S > 0:
+                return oracle.block_forward(xs, d["w_router"], d["b_router"], d["w_mask"],
+                                            d["b_mask"], d["w_gate_up"], d["w_down"], cfg.K,
+                                            w_sh_gate_up=d["w_sh_gate_up"],
+                                            w_sh_down=d["w_sh_down"], w_sh_gate=d["w_sh_gate"],
+                                            residual=d["residual"][:Ts], nthreads=nthreads)
             return oracle.moe_forward(xs, d["w_router"], d["b_router"], d["w_mask"], d["b_mask"],
                                       d["w_gate_up"], d["w_down"], cfg.K, nthreads=nthreads)
         run()
@@ -232,7 +267,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} H={cfg.H} N={cfg.N} K={cfg.K} I={cfg.I} "
-                               f"keep~{cfg.keep}", "kept_pairs": main_pt["P"],
+                               f"keep~{cfg.keep}" + (f" shared={cfg.S}x{cfg.I}" if cfg.S else ""),
+                   "kept_pairs": main_pt["P"],
                    "experts_touched": main_pt["U"], "weight_sets_rotated": len(sets),
                    "weights": main_pt["weights"],
                    "input_setup_s": round(t_gen, 1)},

@@ -244,6 +244,17 @@ beam_status beam_moe_forward_timed(const beam_shape *shape, const void *x, const
                                    size_t workspace_bytes, void *hip_stream,
                                    float *stage_ms_host);
 
+/* The same measurement aid for beam_moe_block_forward (the shared-gate kernel,
+ * if any, is counted in stage 0). */
+beam_status beam_moe_block_forward_timed(const beam_shape *shape, int32_t num_shared,
+                                         const void *x, const void *w_router,
+                                         const float *router_bias, const void *w_mask,
+                                         const float *mask_bias, const void *w_gate_up,
+                                         const void *w_down, const void *w_shared_gate,
+                                         const void *residual, void *out, void *workspace,
+                                         size_t workspace_bytes, void *hip_stream,
+                                         float *stage_ms_host);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,7 +29,7 @@ BEAM_WEIGHTS_PACKED = 1
 EXPORTS = ("beam_abi_version", "beam_status_string", "beam_workspace_bytes", "beam_route_mask",
            "beam_permute", "beam_expert_ffn", "beam_combine", "beam_moe_forward",
            "beam_moe_forward_timed", "beam_pack_weights", "beam_block_workspace_bytes",
-           "beam_moe_block_forward")
+           "beam_moe_block_forward", "beam_moe_block_forward_timed")
 BEAM_NUM_STAGES = 6
 STAGE_NAMES = ("logits", "topk_mask", "permute", "gate_up", "down", "combine")
 
@@ -80,6 +80,9 @@ def load() -> ctypes.CDLL:
         lib.beam_block_workspace_bytes.argtypes = [sp, ctypes.c_int32]
         lib.beam_moe_block_forward.restype = ctypes.c_int
         lib.beam_moe_block_forward.argtypes = [sp, ctypes.c_int32] + [vp] * 15 + [sz, vp]
+        lib.beam_moe_block_forward_timed.restype = ctypes.c_int
+        lib.beam_moe_block_forward_timed.argtypes = [sp, ctypes.c_int32] + [vp] * 11 + [
+            sz, vp, ctypes.POINTER(ctypes.c_float)]
         lib.beam_pack_weights.restype = ctypes.c_int
         lib.beam_pack_weights.argtypes = [sp] + [vp] * 5
         lib.beam_moe_forward_timed.restype = ctypes.c_int
@@ -214,3 +217,16 @@ def beam_moe_forward_timed(shape, x, w_router, router_bias, w_mask, mask_bias, w
                                        _p(out), _p(workspace), int(workspace_bytes),
                                        _p(hip_stream), ms)
     return _check("beam_moe_forward_timed", st, check), [float(v) for v in ms]
+
+
+def beam_moe_block_forward_timed(shape, num_shared, x, w_router, router_bias, w_mask, mask_bias,
+                                 w_gate_up, w_down, w_shared_gate, residual, out, workspace,
+                                 workspace_bytes, hip_stream=None, check: bool = True):
+    """-> (status, [ms per stage]); synchronises the stream (measurement aid)."""
+    s = _shape(shape)
+    ms = (ctypes.c_float * BEAM_NUM_STAGES)()
+    st = load().beam_moe_block_forward_timed(
+        ctypes.byref(s), int(num_shared), _p(x), _p(w_router), _p(router_bias), _p(w_mask),
+        _p(mask_bias), _p(w_gate_up), _p(w_down), _p(w_shared_gate), _p(residual), _p(out),
+        _p(workspace), int(workspace_bytes), _p(hip_stream), ms)
+    return _check("beam_moe_block_forward_timed", st, check), [float(v) for v in ms]

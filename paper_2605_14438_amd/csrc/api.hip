@@ -383,19 +383,19 @@ beam_status beam_moe_block_forward(const beam_shape *shape, int32_t num_shared, 
                             workspace_bytes, hip_stream, nullptr);
 }
 
-beam_status beam_moe_forward_timed(const beam_shape *shape, const void *x, const void *w_router,
-                                   const float *router_bias, const void *w_mask,
-                                   const float *mask_bias, const void *w_gate_up,
-                                   const void *w_down, void *out, void *workspace,
-                                   size_t workspace_bytes, void *hip_stream,
-                                   float *stage_ms_host) {
+static beam_status timed_impl(const beam_shape *shape, int32_t num_shared, const void *x,
+                              const void *w_router, const float *router_bias, const void *w_mask,
+                              const float *mask_bias, const void *w_gate_up, const void *w_down,
+                              const void *w_shared_gate, const void *residual, void *out,
+                              void *workspace, size_t workspace_bytes, void *hip_stream,
+                              float *stage_ms_host) {
     if (!stage_ms_host) return BEAM_ERR_INVALID_ARG;
     hipEvent_t ev[BEAM_NUM_STAGES + 1];
     for (int i = 0; i <= BEAM_NUM_STAGES; ++i) BEAM_TRY_HIP(hipEventCreate(&ev[i]));
-    beam_status st = moe_forward_impl(shape, 0, x, w_router, router_bias, w_mask, mask_bias,
-                                      w_gate_up, w_down, nullptr, nullptr, out, nullptr, nullptr,
-                                      nullptr, nullptr, workspace, workspace_bytes, hip_stream,
-                                      ev);
+    beam_status st = moe_forward_impl(shape, num_shared, x, w_router, router_bias, w_mask,
+                                      mask_bias, w_gate_up, w_down, w_shared_gate, residual, out,
+                                      nullptr, nullptr, nullptr, nullptr, workspace,
+                                      workspace_bytes, hip_stream, ev);
     if (st == BEAM_OK && shape->T > 0) {
         if (hipEventSynchronize(ev[BEAM_NUM_STAGES]) != hipSuccess) st = BEAM_ERR_HIP;
         for (int i = 0; st == BEAM_OK && i < BEAM_NUM_STAGES; ++i)
@@ -406,6 +406,30 @@ beam_status beam_moe_forward_timed(const beam_shape *shape, const void *x, const
     }
     for (int i = 0; i <= BEAM_NUM_STAGES; ++i) (void)hipEventDestroy(ev[i]);
     return st;
+}
+
+beam_status beam_moe_forward_timed(const beam_shape *shape, const void *x, const void *w_router,
+                                   const float *router_bias, const void *w_mask,
+                                   const float *mask_bias, const void *w_gate_up,
+                                   const void *w_down, void *out, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream,
+                                   float *stage_ms_host) {
+    return timed_impl(shape, 0, x, w_router, router_bias, w_mask, mask_bias, w_gate_up, w_down,
+                      nullptr, nullptr, out, workspace, workspace_bytes, hip_stream,
+                      stage_ms_host);
+}
+
+beam_status beam_moe_block_forward_timed(const beam_shape *shape, int32_t num_shared,
+                                         const void *x, const void *w_router,
+                                         const float *router_bias, const void *w_mask,
+                                         const float *mask_bias, const void *w_gate_up,
+                                         const void *w_down, const void *w_shared_gate,
+                                         const void *residual, void *out, void *workspace,
+                                         size_t workspace_bytes, void *hip_stream,
+                                         float *stage_ms_host) {
+    return timed_impl(shape, num_shared, x, w_router, router_bias, w_mask, mask_bias, w_gate_up,
+                      w_down, w_shared_gate, residual, out, workspace, workspace_bytes,
+                      hip_stream, stage_ms_host);
 }
 
 }  // extern "C"
