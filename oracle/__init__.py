@@ -47,6 +47,8 @@ def _load() -> ctypes.CDLL:
         lib.beam_oracle_pair_outputs.restype = ctypes.c_int64
         lib.beam_oracle_moe_forward.restype = ctypes.c_int64
         lib.beam_oracle_block_forward.restype = ctypes.c_int64
+        lib.beam_oracle_route_rule.restype = None
+        lib.beam_oracle_moe_forward_rule.restype = ctypes.c_int64
         _lib = lib
     return _lib
 
@@ -160,6 +162,51 @@ def moe_forward(x, w_router, b_router, w_mask, b_mask, w_gate_up, w_down, K: int
         T, H, N, K, I, _ptr(x, _f32p), _ptr(wr, _f32p), _ptr(br, _f32p), _ptr(wm, _f32p),
         _ptr(bm, _f32p), _ptr(wgu, _f32p), _ptr(wd, _f32p), _ptr(out, _f64p), _ptr(ids, _i32p),
         _ptr(g, _f64p), _ptr(msk, _i32p), int(nthreads))
+    return {"out": out, "topk_ids": ids, "topk_weights": g, "masked_ids": msk,
+            "pair_evals": int(n)}
+
+
+RULE_THRESHOLD = 0    # param = theta = ln(tau / (1 - tau)): keep iff a >= theta
+RULE_CUMPROB = 1      # param = phi: activate ranks until the cumulative softmax-over-N exceeds phi
+
+
+def route_rule(router_logits, mask_logits, K: int, kind: int, param: float):
+    """route_mask under another activation rule -> (topk_ids, topk_weights, masked_ids)."""
+    r = _f32(router_logits)
+    a = _f32(mask_logits)
+    T, N = r.shape
+    assert a.shape == (T, N) and 1 <= K <= N
+    ids = np.empty((T, K), dtype=np.int32)
+    g = np.empty((T, K), dtype=np.float64)
+    msk = np.empty((T, K), dtype=np.int32)
+    _load().beam_oracle_route_rule(T, N, K, _ptr(r, _f32p), _ptr(a, _f32p), int(kind),
+                                   ctypes.c_float(param), _ptr(ids, _i32p), _ptr(g, _f64p),
+                                   _ptr(msk, _i32p))
+    return ids, g, msk
+
+
+def moe_forward_rule(x, w_router, b_router, w_mask, b_mask, w_gate_up, w_down, K: int,
+                     kind: int, param: float, nthreads: int = 0):
+    """moe_forward under another activation rule."""
+    x = _f32(x)
+    wr = _f32(w_router)
+    wm = _f32(w_mask)
+    br = None if b_router is None else _f32(b_router)
+    bm = None if b_mask is None else _f32(b_mask)
+    wgu = _f32(w_gate_up)
+    wd = _f32(w_down)
+    T, H = x.shape
+    N, H2, I = wd.shape
+    assert H2 == H and wr.shape == (N, H) and wm.shape == (N, H) and wgu.shape == (N, 2 * I, H)
+    assert 1 <= K <= N
+    out = np.empty((T, H), dtype=np.float64)
+    ids = np.empty((T, K), dtype=np.int32)
+    g = np.empty((T, K), dtype=np.float64)
+    msk = np.empty((T, K), dtype=np.int32)
+    n = _load().beam_oracle_moe_forward_rule(
+        T, H, N, K, I, _ptr(x, _f32p), _ptr(wr, _f32p), _ptr(br, _f32p), _ptr(wm, _f32p),
+        _ptr(bm, _f32p), _ptr(wgu, _f32p), _ptr(wd, _f32p), int(kind), ctypes.c_float(param),
+        _ptr(out, _f64p), _ptr(ids, _i32p), _ptr(g, _f64p), _ptr(msk, _i32p), int(nthreads))
     return {"out": out, "topk_ids": ids, "topk_weights": g, "masked_ids": msk,
             "pair_evals": int(n)}
 

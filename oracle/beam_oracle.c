@@ -31,6 +31,16 @@
  *   - delta in the GLU expert (Eq. 3) is SiLU.
  *   - Pairs are grouped by expert with a stable order (ascending flat pair
  *     index t*K+k inside an expert); dropped pairs carry id -1 (App. A.4).
+ *   - Other activation rules on the same Top-K slots (Sec. 4.1 baselines, Sec. 4.4
+ *     ablation), each yielding masked ids; the routing weights stay those of
+ *     Eq. 4 and are never renormalised:
+ *       threshold tau: keep iff sigma(a) >= tau iff a >= theta = ln(tau/(1-tau));
+ *         the caller passes theta as an fp32 number and the comparison is a >= theta;
+ *       cumulative probability phi: with p = softmax of r over ALL N experts,
+ *         experts are activated in rank order until their cumulative p exceeds
+ *         phi, i.e. slot k is kept iff sum_{j<k} p_ids[j] <= phi (the first slot
+ *         always is); at most the K slots exist.  The paper names the rule and
+ *         its threshold only; this is the reading taken.
  *   - Whole block (App. A.3): the layer input x is the already normalised
  *     hidden state, the residual h is a separate input; the shared expert is
  *     one GLU expert of its own width; its weight g_sh, for which the paper
@@ -254,6 +264,92 @@ int64_t beam_oracle_moe_forward(int T, int H, int N, int K, int I, const float *
         beam_oracle_logits(1, H, N, xt, w_mask, b_mask, a);
         route_mask_token(N, K, r, a, ids, g, msk);
 
+        double *o = out + (size_t)t * H;
+        for (int c = 0; c < H; ++c)
+            o[c] = 0.0;
+        for (int k = 0; k < K; ++k) {
+            if (msk[k] < 0)
+                continue;
+            int e = msk[k];
+            beam_oracle_expert_ffn(H, I, xt, w_gate_up + (size_t)e * 2 * I * H,
+                                   w_down + (size_t)e * H * I, y);
+            for (int c = 0; c < H; ++c)
+                o[c] += g[k] * y[c];
+            evals += 1;
+        }
+        for (int k = 0; k < K; ++k) {
+            if (topk_ids)
+                topk_ids[(size_t)t * K + k] = ids[k];
+            if (topk_weights)
+                topk_weights[(size_t)t * K + k] = g[k];
+            if (masked_ids)
+                masked_ids[(size_t)t * K + k] = msk[k];
+        }
+        free(r); free(a); free(ids); free(msk); free(g); free(y);
+    }
+    return evals;
+}
+
+/* Activation rules other than the default mask (see the header): kind 0 =
+ * threshold on the mask pre-activation, param = theta; kind 1 = cumulative
+ * routing probability, param = phi.  Same outputs as beam_oracle_route_mask;
+ * kind 0 with theta = 0 is that function.                                   */
+static void route_rule_token(int N, int K, const float *r, const float *a, int kind,
+                             float param, int32_t *ids, double *g, int32_t *masked)
+{
+    route_mask_token(N, K, r, a, ids, g, masked);   /* Top-K order and Eq. 4 weights */
+    if (kind == 0) {
+        for (int k = 0; k < K; ++k)
+            masked[k] = (a[ids[k]] >= param) ? ids[k] : -1;
+    } else {
+        double top = (double)r[ids[0]];
+        double z = 0.0;
+        for (int e = 0; e < N; ++e)
+            z += exp((double)r[e] - top);
+        double cum = 0.0;                            /* probability of the ranks before k */
+        for (int k = 0; k < K; ++k) {
+            masked[k] = (cum <= (double)param) ? ids[k] : -1;
+            cum += exp((double)r[ids[k]] - top) / z;
+        }
+    }
+}
+
+void beam_oracle_route_rule(int T, int N, int K, const float *router_logits,
+                            const float *mask_logits, int kind, float param,
+                            int32_t *topk_ids, double *topk_weights, int32_t *masked_ids)
+{
+    for (int t = 0; t < T; ++t)
+        route_rule_token(N, K, router_logits + (size_t)t * N, mask_logits + (size_t)t * N, kind,
+                         param, topk_ids + (size_t)t * K, topk_weights + (size_t)t * K,
+                         masked_ids + (size_t)t * K);
+}
+
+/* The layer of beam_oracle_moe_forward under one of those rules.            */
+int64_t beam_oracle_moe_forward_rule(int T, int H, int N, int K, int I, const float *x,
+                                     const float *w_router, const float *b_router,
+                                     const float *w_mask, const float *b_mask,
+                                     const float *w_gate_up, const float *w_down, int kind,
+                                     float param, double *out, int32_t *topk_ids,
+                                     double *topk_weights, int32_t *masked_ids, int nthreads)
+{
+    int64_t evals = 0;
+    (void)nthreads;
+#ifdef _OPENMP
+    if (nthreads < 1)
+        nthreads = omp_get_max_threads();
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads) reduction(+ : evals)
+#endif
+    for (int t = 0; t < T; ++t) {
+        float *r = (float *)malloc(sizeof(float) * (size_t)N);
+        float *a = (float *)malloc(sizeof(float) * (size_t)N);
+        int32_t *ids = (int32_t *)malloc(sizeof(int32_t) * (size_t)K);
+        int32_t *msk = (int32_t *)malloc(sizeof(int32_t) * (size_t)K);
+        double *g = (double *)malloc(sizeof(double) * (size_t)K);
+        double *y = (double *)malloc(sizeof(double) * (size_t)H);
+        const float *xt = x + (size_t)t * H;
+        beam_oracle_logits(1, H, N, xt, w_router, b_router, r);
+        beam_oracle_logits(1, H, N, xt, w_mask, b_mask, a);
+        route_rule_token(N, K, r, a, kind, param, ids, g, msk);
         double *o = out + (size_t)t * H;
         for (int c = 0; c < H; ++c)
             o[c] = 0.0;

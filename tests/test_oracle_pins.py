@@ -466,3 +466,91 @@ def test_decision_margin_flags_near_ties():
     assert m[0] < 1e-5 and m[1] < 1e-5
     m = oracle.decision_margin(r[1:], np.ones((1, 4), np.float32), 2)
     assert m[0] == 1.0
+
+
+# --------------------------------------------------------------------------
+# other activation rules on the Top-K slots (Sec. 4.1 baselines, Sec. 4.4 ablation)
+# --------------------------------------------------------------------------
+def test_threshold_rule_is_sigmoid_threshold_tau():
+    """keep iff sigma(a) >= tau, taken on the pre-activation: a >= ln(tau / (1 - tau))."""
+    rng = np.random.default_rng(3)
+    T, N, K = 200, 16, 5
+    r = rng.standard_normal((T, N)).astype(np.float32)
+    a = (2.0 * rng.standard_normal((T, N))).astype(np.float32)
+    ids0, g0, m0 = oracle.route_mask(r, a, K)
+    kept_prev = None
+    for tau in (0.1, 0.3, 0.5, 0.7, 0.9):
+        theta = float(np.log(tau / (1.0 - tau)))
+        ids, g, m = oracle.route_rule(r, a, K, oracle.RULE_THRESHOLD, theta)
+        assert np.array_equal(ids, ids0) and np.array_equal(g, g0)   # routing itself unchanged
+        a_sel = np.take_along_axis(a.astype(np.float64), ids.astype(np.int64), axis=1)
+        sig = 1.0 / (1.0 + np.exp(-a_sel))
+        clear = np.abs(sig - tau) > 1e-6                 # away from the boundary both forms agree
+        assert np.array_equal((m >= 0)[clear], (sig >= tau)[clear])
+        assert np.array_equal(m[m >= 0], ids[m >= 0])
+        if tau == 0.5:
+            assert np.array_equal(m, m0)                 # theta = 0 is Eq. 6
+        kept = m >= 0
+        if kept_prev is not None:                        # raising tau only ever drops experts
+            assert not (kept & ~kept_prev).any()
+        kept_prev = kept
+    # exactly on the threshold keeps (>=)
+    ids, g, m = oracle.route_rule(np.array([[2.0, 1.0]], np.float32),
+                                  np.array([[0.25, 0.2499]], np.float32), 2,
+                                  oracle.RULE_THRESHOLD, 0.25)
+    assert m.tolist() == [[0, -1]]
+
+
+def test_cumulative_probability_rule_closed_form_and_brute_force():
+    """Ranks are activated until the cumulative softmax-over-N probability exceeds phi."""
+    r = np.log(np.array([[4.0, 2.0, 1.0, 1.0]], dtype=np.float64)).astype(np.float32)
+    a = np.zeros_like(r)                                 # p = (1/2, 1/4, 1/8, 1/8)
+    for phi, n_kept in ((0.0, 1), (0.4, 1), (0.49, 1), (0.51, 2), (0.74, 2), (0.76, 3),
+                        (0.87, 3), (0.88, 4), (0.99, 4)):
+        ids, g, m = oracle.route_rule(r, a, 4, oracle.RULE_CUMPROB, phi)
+        assert ids.tolist() == [[0, 1, 2, 3]]
+        assert (m >= 0).sum() == n_kept and (m[0, :n_kept] == ids[0, :n_kept]).all(), phi
+    # "exceeds": a cumulative probability exactly equal to phi does not stop the rule
+    # (two equal logits give p = (1/2, 1/2) exactly)
+    ids, g, m = oracle.route_rule(np.zeros((1, 2), np.float32), np.zeros((1, 2), np.float32), 2,
+                                  oracle.RULE_CUMPROB, 0.5)
+    assert m.tolist() == [[0, 1]]
+    ids, g, m = oracle.route_rule(np.zeros((1, 2), np.float32), np.zeros((1, 2), np.float32), 2,
+                                  oracle.RULE_CUMPROB, 0.4999)
+    assert m.tolist() == [[0, -1]]
+    # K smaller than the rule would take: capped at the K slots
+    ids, g, m = oracle.route_rule(r, a, 2, oracle.RULE_CUMPROB, 0.99)
+    assert m.tolist() == [[0, 1]]
+    # brute force with library routines on random logits
+    from scipy.special import softmax
+    rng = np.random.default_rng(11)
+    T, N, K = 300, 24, 6
+    r = (1.5 * rng.standard_normal((T, N))).astype(np.float32)
+    a = rng.standard_normal((T, N)).astype(np.float32)
+    ids0, g0, _ = oracle.route_mask(r, a, K)
+    for phi in (0.1, 0.3, 0.6):
+        ids, g, m = oracle.route_rule(r, a, K, oracle.RULE_CUMPROB, phi)
+        assert np.array_equal(ids, ids0) and np.array_equal(g, g0)
+        p = np.sort(softmax(r.astype(np.float64), axis=1), axis=1)[:, ::-1]
+        csum = np.cumsum(p, axis=1)
+        t_star = 1 + (csum <= phi).sum(axis=1)           # smallest prefix whose sum exceeds phi
+        near = np.abs(csum[:, :K] - phi).min(axis=1) < 1e-9
+        want = np.minimum(t_star, K)
+        assert np.array_equal((m >= 0).sum(axis=1)[~near], want[~near])
+        first = (m >= 0).cumsum(axis=1) == np.arange(1, K + 1)       # kept slots are a prefix
+        assert np.array_equal(first, m >= 0)
+        assert (m[:, 0] >= 0).all()                      # the top expert is never dropped
+
+
+def test_moe_forward_rule_is_layer_on_the_rule_mask():
+    d = _rand_layer(9, 7, 24, 6, 3, 10)
+    base = _fwd(d, 3)
+    same = oracle.moe_forward_rule(d["x"], d["w_router"], None, d["w_mask"], None, d["w_gate_up"],
+                                   d["w_down"], 3, oracle.RULE_THRESHOLD, 0.0)
+    assert np.array_equal(same["out"], base["out"]) and same["pair_evals"] == base["pair_evals"]
+    res = oracle.moe_forward_rule(d["x"], d["w_router"], None, d["w_mask"], None, d["w_gate_up"],
+                                  d["w_down"], 3, oracle.RULE_CUMPROB, 0.5)
+    y, n = oracle.pair_outputs(d["x"], d["w_gate_up"], d["w_down"], res["masked_ids"])
+    ref = (res["topk_weights"][:, :, None] * y.reshape(7, 3, 24)).sum(axis=1)
+    assert n == res["pair_evals"] == int((res["masked_ids"] >= 0).sum())
+    np.testing.assert_allclose(res["out"], ref, atol=1e-12 * np.abs(ref).max(), rtol=0)
