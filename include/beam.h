@@ -190,6 +190,46 @@ beam_status beam_moe_forward(const beam_shape *shape, const void *x, const void 
                              size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Other activation rules on the same Top-K slots (the paper's ablation on the
+ * binarisation threshold, Sec. 4.4, and the cumulative-probability baseline of
+ * Sec. 4.1).  A rule only decides which of the K ranked slots are kept, i.e. what
+ * masked_ids holds; topk_ids and topk_weights (Eq. 4) are the same under every
+ * rule and the weights are never renormalised.
+ *   BEAM_RULE_MASK     keep iff a >= param.  For a threshold tau on sigma(a) pass
+ *                      param = ln(tau / (1 - tau)); param = 0 is Eq. 6 (tau = 0.5),
+ *                      i.e. what the entry points without a rule do.
+ *   BEAM_RULE_CUMPROB  with p the softmax of the router logits over all N experts,
+ *                      ranks are activated in order until their cumulative p
+ *                      exceeds param = phi: slot k is kept iff the slots before
+ *                      it sum to at most phi (the first always is; at most the K
+ *                      slots exist).  The mask head is not used: w_mask may be
+ *                      NULL.  Sums are fp32.
+ * "Reduce K at inference" needs no rule: call any entry point with the smaller K.
+ * beam_route_rule / beam_moe_forward_rule are beam_route_mask / beam_moe_forward
+ * with the rule as second argument (NULL rule: BEAM_ERR_INVALID_ARG; unknown kind
+ * or NaN param: BEAM_ERR_INVALID_ARG).
+ */
+typedef enum { BEAM_RULE_MASK = 0, BEAM_RULE_CUMPROB = 1 } beam_rule_kind;
+typedef struct {
+    int32_t kind; /* beam_rule_kind */
+    float param;
+} beam_rule;
+
+beam_status beam_route_rule(const beam_shape *shape, const beam_rule *rule, const void *x,
+                            const void *w_router, const float *router_bias, const void *w_mask,
+                            const float *mask_bias, int32_t *topk_ids, float *topk_weights,
+                            int32_t *masked_ids, float *router_logits_dbg,
+                            float *mask_logits_dbg, void *workspace, size_t workspace_bytes,
+                            void *hip_stream);
+beam_status beam_moe_forward_rule(const beam_shape *shape, const beam_rule *rule, const void *x,
+                                  const void *w_router, const float *router_bias,
+                                  const void *w_mask, const float *mask_bias,
+                                  const void *w_gate_up, const void *w_down, void *out,
+                                  int32_t *topk_ids_opt, float *topk_weights_opt,
+                                  int32_t *masked_ids_opt, int32_t *num_pairs_opt,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * The whole MoE block of App. A.3 in one call: residual, routed experts under the
  * binary mask, and the shared expert,
  *   out[t,:] = h[t,:] + sum_i g^_i E_i(x_t) + g_sh[t] E_sh(x_t),

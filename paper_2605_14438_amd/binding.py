@@ -29,7 +29,10 @@ BEAM_WEIGHTS_PACKED = 1
 EXPORTS = ("beam_abi_version", "beam_status_string", "beam_workspace_bytes", "beam_route_mask",
            "beam_permute", "beam_expert_ffn", "beam_combine", "beam_moe_forward",
            "beam_moe_forward_timed", "beam_pack_weights", "beam_block_workspace_bytes",
-           "beam_moe_block_forward", "beam_moe_block_forward_timed")
+           "beam_moe_block_forward", "beam_moe_block_forward_timed", "beam_route_rule",
+           "beam_moe_forward_rule")
+BEAM_RULE_MASK = 0
+BEAM_RULE_CUMPROB = 1
 BEAM_NUM_STAGES = 6
 STAGE_NAMES = ("logits", "topk_mask", "permute", "gate_up", "down", "combine")
 
@@ -38,6 +41,10 @@ class beam_shape(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32),
                 ("K", ctypes.c_int32), ("I", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("weight_layout", ctypes.c_int32)]
+
+
+class beam_rule(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("param", ctypes.c_float)]
 
 
 class BeamError(RuntimeError):
@@ -76,6 +83,11 @@ def load() -> ctypes.CDLL:
         lib.beam_combine.argtypes = [sp] + [vp] * 6
         lib.beam_moe_forward.restype = ctypes.c_int
         lib.beam_moe_forward.argtypes = [sp] + [vp] * 13 + [sz, vp]
+        rp = ctypes.POINTER(beam_rule)
+        lib.beam_route_rule.restype = ctypes.c_int
+        lib.beam_route_rule.argtypes = [sp, rp] + [vp] * 11 + [sz, vp]
+        lib.beam_moe_forward_rule.restype = ctypes.c_int
+        lib.beam_moe_forward_rule.argtypes = [sp, rp] + [vp] * 13 + [sz, vp]
         lib.beam_block_workspace_bytes.restype = sz
         lib.beam_block_workspace_bytes.argtypes = [sp, ctypes.c_int32]
         lib.beam_moe_block_forward.restype = ctypes.c_int
@@ -230,3 +242,38 @@ def beam_moe_block_forward_timed(shape, num_shared, x, w_router, router_bias, w_
         _p(mask_bias), _p(w_gate_up), _p(w_down), _p(w_shared_gate), _p(residual), _p(out),
         _p(workspace), int(workspace_bytes), _p(hip_stream), ms)
     return _check("beam_moe_block_forward_timed", st, check), [float(v) for v in ms]
+
+
+def _rule(rule):
+    """None, a beam_rule, or a (kind, param) pair -> ctypes argument."""
+    if rule is None:
+        return None
+    if not isinstance(rule, beam_rule):
+        rule = beam_rule(int(rule[0]), float(rule[1]))
+    return ctypes.byref(rule)
+
+
+def beam_route_rule(shape, rule, x, w_router, router_bias, w_mask, mask_bias, topk_ids,
+                    topk_weights, masked_ids, router_logits_dbg, mask_logits_dbg, workspace,
+                    workspace_bytes, hip_stream=None, check: bool = True) -> int:
+    s = _shape(shape)
+    st = load().beam_route_rule(ctypes.byref(s), _rule(rule), _p(x), _p(w_router),
+                                _p(router_bias), _p(w_mask), _p(mask_bias), _p(topk_ids),
+                                _p(topk_weights), _p(masked_ids), _p(router_logits_dbg),
+                                _p(mask_logits_dbg), _p(workspace), int(workspace_bytes),
+                                _p(hip_stream))
+    return _check("beam_route_rule", st, check)
+
+
+def beam_moe_forward_rule(shape, rule, x, w_router, router_bias, w_mask, mask_bias, w_gate_up,
+                          w_down, out, topk_ids_opt, topk_weights_opt, masked_ids_opt,
+                          num_pairs_opt, workspace, workspace_bytes, hip_stream=None,
+                          check: bool = True) -> int:
+    s = _shape(shape)
+    st = load().beam_moe_forward_rule(ctypes.byref(s), _rule(rule), _p(x), _p(w_router),
+                                      _p(router_bias), _p(w_mask), _p(mask_bias), _p(w_gate_up),
+                                      _p(w_down), _p(out), _p(topk_ids_opt),
+                                      _p(topk_weights_opt), _p(masked_ids_opt),
+                                      _p(num_pairs_opt), _p(workspace), int(workspace_bytes),
+                                      _p(hip_stream))
+    return _check("beam_moe_forward_rule", st, check)

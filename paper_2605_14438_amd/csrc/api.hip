@@ -174,14 +174,29 @@ beam_status beam_pack_weights(const beam_shape *shape, const void *w_gate_up, co
     return BEAM_OK;
 }
 
-beam_status beam_route_mask(const beam_shape *shape, const void *x, const void *w_router,
-                            const float *router_bias, const void *w_mask, const float *mask_bias,
-                            int32_t *topk_ids, float *topk_weights, int32_t *masked_ids,
-                            float *router_logits_dbg, float *mask_logits_dbg, void *workspace,
-                            size_t workspace_bytes, void *hip_stream) {
+static beam_status check_rule(const beam_rule *rule, RouteOpts *opt) {
+    if (!rule) return BEAM_OK;  // Eq. 6: mask pre-activation >= 0
+    if (rule->kind != BEAM_RULE_MASK && rule->kind != BEAM_RULE_CUMPROB)
+        return BEAM_ERR_INVALID_ARG;
+    if (!(rule->param == rule->param)) return BEAM_ERR_INVALID_ARG;  // NaN
+    opt->rule = rule->kind;
+    opt->param = rule->param;
+    return BEAM_OK;
+}
+
+static beam_status route_impl(const beam_shape *shape, const beam_rule *rule, const void *x,
+                              const void *w_router, const float *router_bias, const void *w_mask,
+                              const float *mask_bias, int32_t *topk_ids, float *topk_weights,
+                              int32_t *masked_ids, float *router_logits_dbg,
+                              float *mask_logits_dbg, void *workspace, size_t workspace_bytes,
+                              void *hip_stream) {
     beam_status st = check_shape(shape);
     if (st != BEAM_OK) return st;
     const beam_shape &s = *shape;
+    RouteOpts opt;
+    st = check_rule(rule, &opt);
+    if (st != BEAM_OK) return st;
+    if (!w_mask && opt.rule == BEAM_RULE_CUMPROB) w_mask = w_router;  // head computed, not used
     if (!x || !w_router || !w_mask || !topk_ids || !topk_weights || !masked_ids)
         return BEAM_ERR_INVALID_ARG;
     if (misaligned(x) || misaligned(w_router) || misaligned(w_mask)) return BEAM_ERR_INVALID_ARG;
@@ -194,9 +209,31 @@ beam_status beam_route_mask(const beam_shape *shape, const void *x, const void *
     float *ml = mask_logits_dbg ? mask_logits_dbg : (float *)(ws + L.mask_logits);
     hipStream_t stream = (hipStream_t)hip_stream;
     BEAM_TRY_HIP(launch_logits(s, x, w_router, router_bias, w_mask, mask_bias, rl, ml, stream));
-    BEAM_TRY_HIP(launch_topk_mask(s, rl, ml, nullptr, nullptr, s.N, 0, nullptr, topk_ids,
-                                  topk_weights, masked_ids, stream));
+    BEAM_TRY_HIP(launch_topk_mask(s, rl, ml, nullptr, nullptr, s.N, opt, topk_ids, topk_weights,
+                                  masked_ids, stream));
     return BEAM_OK;
+}
+
+beam_status beam_route_mask(const beam_shape *shape, const void *x, const void *w_router,
+                            const float *router_bias, const void *w_mask, const float *mask_bias,
+                            int32_t *topk_ids, float *topk_weights, int32_t *masked_ids,
+                            float *router_logits_dbg, float *mask_logits_dbg, void *workspace,
+                            size_t workspace_bytes, void *hip_stream) {
+    return route_impl(shape, nullptr, x, w_router, router_bias, w_mask, mask_bias, topk_ids,
+                      topk_weights, masked_ids, router_logits_dbg, mask_logits_dbg, workspace,
+                      workspace_bytes, hip_stream);
+}
+
+beam_status beam_route_rule(const beam_shape *shape, const beam_rule *rule, const void *x,
+                            const void *w_router, const float *router_bias, const void *w_mask,
+                            const float *mask_bias, int32_t *topk_ids, float *topk_weights,
+                            int32_t *masked_ids, float *router_logits_dbg,
+                            float *mask_logits_dbg, void *workspace, size_t workspace_bytes,
+                            void *hip_stream) {
+    if (!rule) return BEAM_ERR_INVALID_ARG;
+    return route_impl(shape, rule, x, w_router, router_bias, w_mask, mask_bias, topk_ids,
+                      topk_weights, masked_ids, router_logits_dbg, mask_logits_dbg, workspace,
+                      workspace_bytes, hip_stream);
 }
 
 beam_status beam_permute(const beam_shape *shape, const int32_t *masked_ids, int32_t *expert_counts,
@@ -265,8 +302,8 @@ beam_status beam_combine(const beam_shape *shape, const float *y_pairs, const fl
 // experts (App. A.3) follow them in the weight arrays and ride the same grouped
 // kernels as experts N .. N+S-1 with S always-kept slots per token, so from
 // grouping on everything runs at N+S experts and K+S slots.
-static beam_status moe_forward_impl(const beam_shape *shape, int S, const void *x,
-                                    const void *w_router, const float *router_bias,
+static beam_status moe_forward_impl(const beam_shape *shape, int S, const beam_rule *rule,
+                                    const void *x, const void *w_router, const float *router_bias,
                                     const void *w_mask, const float *mask_bias,
                                     const void *w_gate_up, const void *w_down,
                                     const void *w_shared_gate, const void *residual, void *out,
@@ -278,6 +315,10 @@ static beam_status moe_forward_impl(const beam_shape *shape, int S, const void *
     if (st != BEAM_OK) return st;
     const beam_shape &s = *shape;
     if (S < 0) return BEAM_ERR_INVALID_ARG;
+    RouteOpts opt;
+    st = check_rule(rule, &opt);
+    if (st != BEAM_OK) return st;
+    if (!w_mask && opt.rule == BEAM_RULE_CUMPROB) w_mask = w_router;  // head computed, not used
     beam_shape se = s;  // experts and slots including the shared ones
     se.N = s.N + S;
     se.K = s.K + S;
@@ -313,6 +354,8 @@ static beam_status moe_forward_impl(const beam_shape *shape, int S, const void *
     float *y_pairs = (float *)(ws + L.y_pairs);
     float *g_shared = w_shared_gate ? (float *)(ws + L.g_shared) : nullptr;
     const WorkList wl = work_list(ws + L.work, se, L.max_tiles);
+    opt.S = S;
+    opt.g_shared = g_shared;
 
 #define BEAM_STAGE_MARK(i)                                      \
     do {                                                        \
@@ -324,13 +367,13 @@ static beam_status moe_forward_impl(const beam_shape *shape, int S, const void *
         // prefill: both heads as one tiled GEMM into a [T,2N] array; biases join at Top-K
         BEAM_TRY_HIP(launch_logits_tiled(s, x, w_router, w_mask, ws + L.packed_heads, rl, stream));
         BEAM_STAGE_MARK(1);
-        BEAM_TRY_HIP(launch_topk_mask(s, rl, rl + s.N, router_bias, mask_bias, 2 * s.N, S,
-                                      g_shared, ids, gw, mids, stream));
+        BEAM_TRY_HIP(launch_topk_mask(s, rl, rl + s.N, router_bias, mask_bias, 2 * s.N, opt, ids,
+                                      gw, mids, stream));
     } else {
         BEAM_TRY_HIP(launch_logits(s, x, w_router, router_bias, w_mask, mask_bias, rl, ml, stream));
         BEAM_STAGE_MARK(1);
-        BEAM_TRY_HIP(launch_topk_mask(s, rl, ml, nullptr, nullptr, s.N, S, g_shared, ids, gw,
-                                      mids, stream));
+        BEAM_TRY_HIP(launch_topk_mask(s, rl, ml, nullptr, nullptr, s.N, opt, ids, gw, mids,
+                                      stream));
     }
     BEAM_STAGE_MARK(2);
     BEAM_TRY_HIP(launch_permute(se, mids, counts, offsets, perm, inv, np,
@@ -353,10 +396,24 @@ beam_status beam_moe_forward(const beam_shape *shape, const void *x, const void 
                              int32_t *topk_ids_opt, float *topk_weights_opt,
                              int32_t *masked_ids_opt, int32_t *num_pairs_opt, void *workspace,
                              size_t workspace_bytes, void *hip_stream) {
-    return moe_forward_impl(shape, 0, x, w_router, router_bias, w_mask, mask_bias, w_gate_up,
-                            w_down, nullptr, nullptr, out, topk_ids_opt, topk_weights_opt,
-                            masked_ids_opt, num_pairs_opt, workspace, workspace_bytes, hip_stream,
-                            nullptr);
+    return moe_forward_impl(shape, 0, nullptr, x, w_router, router_bias, w_mask, mask_bias,
+                            w_gate_up, w_down, nullptr, nullptr, out, topk_ids_opt,
+                            topk_weights_opt, masked_ids_opt, num_pairs_opt, workspace,
+                            workspace_bytes, hip_stream, nullptr);
+}
+
+beam_status beam_moe_forward_rule(const beam_shape *shape, const beam_rule *rule, const void *x,
+                                  const void *w_router, const float *router_bias,
+                                  const void *w_mask, const float *mask_bias,
+                                  const void *w_gate_up, const void *w_down, void *out,
+                                  int32_t *topk_ids_opt, float *topk_weights_opt,
+                                  int32_t *masked_ids_opt, int32_t *num_pairs_opt,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (!rule) return BEAM_ERR_INVALID_ARG;
+    return moe_forward_impl(shape, 0, rule, x, w_router, router_bias, w_mask, mask_bias,
+                            w_gate_up, w_down, nullptr, nullptr, out, topk_ids_opt,
+                            topk_weights_opt, masked_ids_opt, num_pairs_opt, workspace,
+                            workspace_bytes, hip_stream, nullptr);
 }
 
 size_t beam_block_workspace_bytes(const beam_shape *shape, int32_t num_shared) {
@@ -377,8 +434,8 @@ beam_status beam_moe_block_forward(const beam_shape *shape, int32_t num_shared, 
                                    int32_t *topk_ids_opt, float *topk_weights_opt,
                                    int32_t *masked_ids_opt, int32_t *num_pairs_opt,
                                    void *workspace, size_t workspace_bytes, void *hip_stream) {
-    return moe_forward_impl(shape, num_shared, x, w_router, router_bias, w_mask, mask_bias,
-                            w_gate_up, w_down, w_shared_gate, residual, out, topk_ids_opt,
+    return moe_forward_impl(shape, num_shared, nullptr, x, w_router, router_bias, w_mask,
+                            mask_bias, w_gate_up, w_down, w_shared_gate, residual, out, topk_ids_opt,
                             topk_weights_opt, masked_ids_opt, num_pairs_opt, workspace,
                             workspace_bytes, hip_stream, nullptr);
 }
@@ -392,7 +449,7 @@ static beam_status timed_impl(const beam_shape *shape, int32_t num_shared, const
     if (!stage_ms_host) return BEAM_ERR_INVALID_ARG;
     hipEvent_t ev[BEAM_NUM_STAGES + 1];
     for (int i = 0; i <= BEAM_NUM_STAGES; ++i) BEAM_TRY_HIP(hipEventCreate(&ev[i]));
-    beam_status st = moe_forward_impl(shape, num_shared, x, w_router, router_bias, w_mask,
+    beam_status st = moe_forward_impl(shape, num_shared, nullptr, x, w_router, router_bias, w_mask,
                                       mask_bias, w_gate_up, w_down, w_shared_gate, residual, out,
                                       nullptr, nullptr, nullptr, nullptr, workspace,
                                       workspace_bytes, hip_stream, ev);

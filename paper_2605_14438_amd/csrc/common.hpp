@@ -106,9 +106,18 @@ hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_route
                          float *router_logits, float *mask_logits, hipStream_t st);
 hipError_t launch_shared_gate(const beam_shape &s, const void *x, const void *w_shared_gate,
                               float *g_shared, hipStream_t st);
+// What the Top-K stage appends and decides beyond Eq. 4: S shared-expert slots
+// with per-token weight g_shared (NULL = 1), and the activation rule (0: mask
+// pre-activation >= param; 1: cumulative routing probability, param = phi).
+struct RouteOpts {
+    int S = 0;
+    const float *g_shared = nullptr;
+    int rule = 0;
+    float param = 0.0f;
+};
 hipError_t launch_topk_mask(const beam_shape &s, const float *router_logits,
                             const float *mask_logits, const float *b_router, const float *b_mask,
-                            int row_stride, int S, const float *g_shared, int32_t *topk_ids,
+                            int row_stride, const RouteOpts &opt, int32_t *topk_ids,
                             float *topk_w, int32_t *masked_ids, hipStream_t st);
 bool logits_tiled_supported(const beam_shape &s);
 hipError_t launch_logits_tiled(const beam_shape &s, const void *x, const void *w_router,

@@ -232,62 +232,78 @@ hipError_t launch_shared_gate(const beam_shape &s, const void *x, const void *w_
 // S > 0 appends the shared-expert slots: output rows have K + S entries and
 // g_shared (NULL = 1) holds the per-token weight of those slots.
 // ---------------------------------------------------------------------------
+template <int RULE>
 __global__ __launch_bounds__(256) void topk_mask_kernel(
     const float *__restrict__ router_logits, const float *__restrict__ mask_logits,
     const float *__restrict__ b_router, const float *__restrict__ b_mask, int row_stride,
-    const float *__restrict__ g_shared, int32_t *__restrict__ topk_ids,
+    const float *__restrict__ g_shared, float param, int32_t *__restrict__ topk_ids,
     float *__restrict__ topk_w, int32_t *__restrict__ masked_ids, int Tn, int N, int K, int S) {
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= Tn) return;  // wave-uniform
     const size_t f = (size_t)t * (K + S);
     const float gs = (S > 0 && g_shared) ? g_shared[t] : 1.0f;
-    wave_route_token(router_logits + (size_t)t * row_stride, mask_logits + (size_t)t * row_stride,
-                     b_router, b_mask, N, K, S, gs, topk_ids + f, topk_w + f, masked_ids + f);
+    wave_route_token<RULE>(router_logits + (size_t)t * row_stride,
+                           mask_logits + (size_t)t * row_stride, b_router, b_mask, N, K, S, gs,
+                           param, topk_ids + f, topk_w + f, masked_ids + f);
 }
 
 // Large batches: four tokens per wavefront (one per 16-lane row), 16 per workgroup.
-template <int NPL>
+template <int NPL, int RULE>
 __global__ __launch_bounds__(256) void topk_mask_rows_kernel(
     const float *__restrict__ router_logits, const float *__restrict__ mask_logits,
     const float *__restrict__ b_router, const float *__restrict__ b_mask, int row_stride,
-    const float *__restrict__ g_shared, int32_t *__restrict__ topk_ids,
+    const float *__restrict__ g_shared, float param, int32_t *__restrict__ topk_ids,
     float *__restrict__ topk_w, int32_t *__restrict__ masked_ids, int Tn, int N, int K, int S) {
     const int t = blockIdx.x * 16 + (threadIdx.x >> 4);
     const bool valid = t < Tn;
     const int tc = valid ? t : Tn - 1;
     const size_t f = (size_t)tc * (K + S);
     const float gs = (S > 0 && g_shared) ? g_shared[tc] : 1.0f;
-    row_route_token<NPL>(router_logits + (size_t)tc * row_stride,
-                         mask_logits + (size_t)tc * row_stride, b_router, b_mask, N, K, S, gs,
-                         valid, topk_ids + f, topk_w + f, masked_ids + f);
+    row_route_token<NPL, RULE>(router_logits + (size_t)tc * row_stride,
+                               mask_logits + (size_t)tc * row_stride, b_router, b_mask, N, K, S,
+                               gs, param, valid, topk_ids + f, topk_w + f, masked_ids + f);
 }
 
 // Logits live as two [T,N] arrays that already include the biases, or (row_stride
 // = 2N, biases still to add) as one [T,2N] array: router columns, then mask columns.
-// s.N and s.K count the routed experts; S shared-expert slots are appended.
-hipError_t launch_topk_mask(const beam_shape &s, const float *router_logits,
-                            const float *mask_logits, const float *b_router, const float *b_mask,
-                            int row_stride, int S, const float *g_shared, int32_t *topk_ids,
-                            float *topk_w, int32_t *masked_ids, hipStream_t st) {
+// s.N and s.K count the routed experts; opt.S shared-expert slots are appended.
+template <int RULE>
+static hipError_t launch_topk_rule(const beam_shape &s, const float *router_logits,
+                                   const float *mask_logits, const float *b_router,
+                                   const float *b_mask, int row_stride, const RouteOpts &opt,
+                                   int32_t *topk_ids, float *topk_w, int32_t *masked_ids,
+                                   hipStream_t st) {
     // The row variant does four tokens per wavefront at about the cost of one; the
     // wave variant has the shorter latency chain for decode-sized batches.
     const bool aligned = ((uintptr_t)router_logits | (uintptr_t)mask_logits |
                           (uintptr_t)b_router | (uintptr_t)b_mask) % 16 == 0;
+    const int S = opt.S;
 #define BEAM_TOPK_ARGS                                                                          \
-    router_logits, mask_logits, b_router, b_mask, row_stride, g_shared, topk_ids, topk_w,       \
-        masked_ids, s.T, s.N, s.K, S
+    router_logits, mask_logits, b_router, b_mask, row_stride, opt.g_shared, opt.param,          \
+        topk_ids, topk_w, masked_ids, s.T, s.N, s.K, S
     if (s.T >= 512 && s.K + S <= 16 && s.N % 4 == 0 && row_stride % 4 == 0 && s.N <= 256 &&
         aligned) {
         dim3 grid((s.T + 15) / 16);
-        if (s.N <= 64) topk_mask_rows_kernel<4><<<grid, 256, 0, st>>>(BEAM_TOPK_ARGS);
-        else if (s.N <= 128) topk_mask_rows_kernel<8><<<grid, 256, 0, st>>>(BEAM_TOPK_ARGS);
-        else topk_mask_rows_kernel<16><<<grid, 256, 0, st>>>(BEAM_TOPK_ARGS);
+        if (s.N <= 64) topk_mask_rows_kernel<4, RULE><<<grid, 256, 0, st>>>(BEAM_TOPK_ARGS);
+        else if (s.N <= 128) topk_mask_rows_kernel<8, RULE><<<grid, 256, 0, st>>>(BEAM_TOPK_ARGS);
+        else topk_mask_rows_kernel<16, RULE><<<grid, 256, 0, st>>>(BEAM_TOPK_ARGS);
         return hipGetLastError();
     }
     dim3 grid((s.T + 3) / 4);
-    topk_mask_kernel<<<grid, 256, 0, st>>>(BEAM_TOPK_ARGS);
+    topk_mask_kernel<RULE><<<grid, 256, 0, st>>>(BEAM_TOPK_ARGS);
 #undef BEAM_TOPK_ARGS
     return hipGetLastError();
+}
+
+hipError_t launch_topk_mask(const beam_shape &s, const float *router_logits,
+                            const float *mask_logits, const float *b_router, const float *b_mask,
+                            int row_stride, const RouteOpts &opt, int32_t *topk_ids,
+                            float *topk_w, int32_t *masked_ids, hipStream_t st) {
+    if (opt.rule == kRuleCumProb)
+        return launch_topk_rule<kRuleCumProb>(s, router_logits, mask_logits, b_router, b_mask,
+                                              row_stride, opt, topk_ids, topk_w, masked_ids, st);
+    return launch_topk_rule<kRuleMask>(s, router_logits, mask_logits, b_router, b_mask,
+                                       row_stride, opt, topk_ids, topk_w, masked_ids, st);
 }
 
 }  // namespace beam

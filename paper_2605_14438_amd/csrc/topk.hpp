@@ -68,24 +68,37 @@ __device__ __forceinline__ float key_logit(uint64_t key) {
 // include them).
 // Shared experts (App. A.3): lanes K .. K+S-1 append S always-kept slots for the
 // experts N .. N+S-1 with weight g_shared; the three outputs are rows of K+S.
+// RULE picks what decides "kept" (the routing weights are Eq. 4's either way):
+//   kRuleMask     a >= param; param = ln(tau/(1-tau)) for a threshold tau on
+//                 sigma(a), 0 for the paper's tau = 0.5 (Eq. 6, Sec. 4.4)
+//   kRuleCumProb  the cumulative-probability baseline of Sec. 4.1: with p the
+//                 softmax of r over all N experts, slot k is kept iff the ranks
+//                 before it sum to at most param (= phi)
+constexpr int kRuleMask = 0;
+constexpr int kRuleCumProb = 1;
+
+template <int RULE>
 __device__ __forceinline__ void wave_route_token(const float *__restrict__ r,
                                                  const float *__restrict__ a,
                                                  const float *__restrict__ br,
                                                  const float *__restrict__ bm, int N, int K,
-                                                 int S, float g_shared,
+                                                 int S, float g_shared, float param,
                                                  int32_t *__restrict__ ids_out,
                                                  float *__restrict__ w_out,
                                                  int32_t *__restrict__ masked_out) {
     const int lane = threadIdx.x & 63;
     uint64_t key[4];
+    float logit[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int e = lane + 64 * i;
         key[i] = 0ull;
+        logit[i] = -INFINITY;
         if (e < N) {
             const float rv = br ? r[e] + br[e] : r[e];
             const float av = bm ? a[e] + bm[e] : a[e];
-            key[i] = topk_key(rv, e, av >= 0.0f);
+            key[i] = topk_key(rv, e, av >= param);
+            logit[i] = rv;
         }
     }
     uint64_t mine = 0;
@@ -103,10 +116,23 @@ __device__ __forceinline__ void wave_route_token(const float *__restrict__ r,
     const float top = __shfl(my_r, 0);
     const float ex = lane < K ? expf(my_r - top) : 0.0f;
     const float denom = wave_sum(ex);
+    bool keep = key_keep(mine);
+    if constexpr (RULE == kRuleCumProb) {
+        float zl = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) zl += expf(logit[i] - top);   // exp(-inf) = 0 past N
+        const float p = ex / wave_sum(zl);
+        float before = 0.0f;                 // probability of the ranks ahead of this slot
+        for (int q = 0; q < K; ++q) {
+            const float pq = __shfl(p, q);
+            before += q < lane ? pq : 0.0f;
+        }
+        keep = before <= param;
+    }
     if (lane < K) {
         ids_out[lane] = my_id;
         w_out[lane] = ex / denom;
-        masked_out[lane] = key_keep(mine) ? my_id : -1;
+        masked_out[lane] = keep ? my_id : -1;
     } else if (lane < K + S) {
         ids_out[lane] = N + lane - K;
         w_out[lane] = g_shared;
@@ -137,18 +163,19 @@ __device__ __forceinline__ float row_sum_f32(float v) {
     return v;
 }
 
-template <int NPL>
+template <int NPL, int RULE>
 __device__ __forceinline__ void row_route_token(const float *__restrict__ r,
                                                 const float *__restrict__ a,
                                                 const float *__restrict__ br,
                                                 const float *__restrict__ bm, int N, int K,
-                                                int S, float g_shared, bool valid,
+                                                int S, float g_shared, float param, bool valid,
                                                 int32_t *__restrict__ ids_out,
                                                 float *__restrict__ w_out,
                                                 int32_t *__restrict__ masked_out) {
     static_assert(NPL % 4 == 0, "candidates are loaded four at a time");
     const int j = threadIdx.x & 15;
     uint64_t key[NPL];
+    float logit[RULE == kRuleCumProb ? NPL : 1];  // kRuleCumProb needs the softmax over all N
 #pragma unroll
     for (int q = 0; q < NPL / 4; ++q) {
         const int e0 = j * NPL + q * 4;
@@ -166,10 +193,16 @@ __device__ __forceinline__ void row_route_token(const float *__restrict__ r,
                 av.x += b.x, av.y += b.y, av.z += b.z, av.w += b.w;
             }
         }
-        key[q * 4 + 0] = in ? topk_key(rv.x, e0 + 0, av.x >= 0.0f) : 0ull;
-        key[q * 4 + 1] = in ? topk_key(rv.y, e0 + 1, av.y >= 0.0f) : 0ull;
-        key[q * 4 + 2] = in ? topk_key(rv.z, e0 + 2, av.z >= 0.0f) : 0ull;
-        key[q * 4 + 3] = in ? topk_key(rv.w, e0 + 3, av.w >= 0.0f) : 0ull;
+        key[q * 4 + 0] = in ? topk_key(rv.x, e0 + 0, av.x >= param) : 0ull;
+        key[q * 4 + 1] = in ? topk_key(rv.y, e0 + 1, av.y >= param) : 0ull;
+        key[q * 4 + 2] = in ? topk_key(rv.z, e0 + 2, av.z >= param) : 0ull;
+        key[q * 4 + 3] = in ? topk_key(rv.w, e0 + 3, av.w >= param) : 0ull;
+        if constexpr (RULE == kRuleCumProb) {
+            logit[q * 4 + 0] = in ? rv.x : -INFINITY;
+            logit[q * 4 + 1] = in ? rv.y : -INFINITY;
+            logit[q * 4 + 2] = in ? rv.z : -INFINITY;
+            logit[q * 4 + 3] = in ? rv.w : -INFINITY;
+        }
     }
     uint64_t mine = 0;
     for (int k = 0; k < K; ++k) {
@@ -186,10 +219,23 @@ __device__ __forceinline__ void row_route_token(const float *__restrict__ r,
     const float top = __shfl(my_r, threadIdx.x & 48);  // lane 0 of this row (wave-relative)
     const float ex = j < K ? expf(my_r - top) : 0.0f;
     const float denom = row_sum_f32(ex);
+    bool keep = key_keep(mine);
+    if constexpr (RULE == kRuleCumProb) {
+        float zl = 0.0f;
+#pragma unroll
+        for (int i = 0; i < NPL; ++i) zl += expf(logit[i] - top);   // exp(-inf) = 0 past N
+        const float p = ex / row_sum_f32(zl);
+        float before = 0.0f;
+        for (int q = 0; q < K; ++q) {
+            const float pq = __shfl(p, (threadIdx.x & 48) + q);
+            before += q < j ? pq : 0.0f;
+        }
+        keep = before <= param;
+    }
     if (valid && j < K) {
         ids_out[j] = my_id;
         w_out[j] = ex / denom;
-        masked_out[j] = key_keep(mine) ? my_id : -1;
+        masked_out[j] = keep ? my_id : -1;
     } else if (valid && j < K + S) {
         ids_out[j] = N + j - K;
         w_out[j] = g_shared;

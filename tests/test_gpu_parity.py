@@ -612,3 +612,133 @@ def test_moe_block_forward_full_size(name, T, packed):
          f"tokens max|err|/RMS={literal:.4f} worst/bound={ratio:.3f} "
          f"experts-part worst/bound={float((err / tol).max()):.3f}")
     assert ratio <= 1.0 and (err <= tol).all()
+
+
+# ---------------------------------------------------------------------------
+# other activation rules on the Top-K slots: threshold tau (Sec. 4.4) and the
+# cumulative-probability baseline (Sec. 4.1)
+# ---------------------------------------------------------------------------
+def _route_rule_gpu(cfg, g, rule, use_mask=True):
+    s = hp.shape_of(cfg)
+    ws, nb = hp.workspace(s)
+    T, K = cfg.T, cfg.K
+    ids = torch.full((T, K), -7, dtype=torch.int32, device="cuda")
+    gw = torch.zeros((T, K), dtype=torch.float32, device="cuda")
+    mids = torch.full((T, K), -7, dtype=torch.int32, device="cuda")
+    beam.beam_route_rule(s, rule, g["x"], g["w_router"], g["b_router"],
+                         g["w_mask"] if use_mask else None, g["b_mask"] if use_mask else None,
+                         ids, gw, mids, None, None, ws, nb, hp.stream_ptr())
+    torch.cuda.synchronize()
+    return ids.cpu().numpy(), gw.cpu().numpy(), mids.cpu().numpy()
+
+
+RULE_ROUTE_CASES = [
+    CFG["qwen3_decode"].with_(T=37),                      # one wavefront per token
+    CFG["qwen3_prefill"].with_(T=1500),                   # four tokens per wavefront, 8 per lane
+    PREFILL_SMALL,                                        # 4 candidates per lane
+    synth.LayerConfig("wide_router", 4, T=601, H=512, N=256, K=16, I=64, dtype="bf16", keep=0.3),
+    CFG["tiny"],
+]
+
+
+@pytest.mark.parametrize("cfg", RULE_ROUTE_CASES, ids=lambda c: f"{c.name}-T{c.T}")
+@pytest.mark.parametrize("tau", [0.1, 0.9])
+def test_route_rule_threshold_tau(cfg, tau):
+    """keep iff sigma(a) >= tau: the guard-banded layer with its mask bias moved by theta."""
+    theta = float(np.float32(np.log(tau / (1.0 - tau))))
+    d = hp.make_tie_free(cfg, with_experts=False)
+    bm = d["b_mask"] if d["b_mask"] is not None else np.zeros((cfg.N,), np.float32)
+    d["b_mask"] = (bm + np.float32(theta)).astype(np.float32)   # a' = a + theta: margins carry over
+    a_new = oracle.logits(d["x"], d["w_mask"], d["b_mask"])
+    ids_o, g_o, msk_o = oracle.route_rule(d["router_logits"], a_new, cfg.K,
+                                          oracle.RULE_THRESHOLD, theta)
+    ids0, _, msk0 = oracle.route_mask(d["router_logits"], d["mask_logits"], cfg.K)
+    assert np.array_equal(msk_o, msk0)                    # same decisions as a >= 0 before the move
+    ids, gw, mids = _route_rule_gpu(cfg, hp.upload(cfg, d), (beam.BEAM_RULE_MASK, theta))
+    assert np.array_equal(ids, ids_o) and np.array_equal(mids, msk_o)
+    np.testing.assert_allclose(gw, g_o, atol=2e-6, rtol=0)
+    # and without the move the threshold really changes the kept set
+    d["b_mask"] = bm
+    _, _, mids_t = _route_rule_gpu(cfg, hp.upload(cfg, d), (beam.BEAM_RULE_MASK, theta))
+    kept0, kept_t = (msk0 >= 0), (mids_t >= 0)
+    assert not (kept_t & ~kept0).any() if tau > 0.5 else not (kept0 & ~kept_t).any()
+
+
+def _cumprob_margin(r, K, phi):
+    """Per token: distance of phi from the nearest cumulative probability the rule compares."""
+    from scipy.special import softmax
+    p = np.sort(softmax(r.astype(np.float64), axis=1), axis=1)[:, ::-1]
+    csum = np.cumsum(p, axis=1)[:, :max(K - 1, 1)]
+    return np.abs(csum - phi).min(axis=1)
+
+
+@pytest.mark.parametrize("cfg", RULE_ROUTE_CASES, ids=lambda c: f"{c.name}-T{c.T}")
+@pytest.mark.parametrize("phi", [0.05, 0.3])
+def test_route_rule_cumulative_probability(cfg, phi):
+    d = hp.make_tie_free(cfg, with_experts=False)
+    ids_o, g_o, msk_o = oracle.route_rule(d["router_logits"], d["mask_logits"], cfg.K,
+                                          oracle.RULE_CUMPROB, phi)
+    ids, gw, mids = _route_rule_gpu(cfg, hp.upload(cfg, d), (beam.BEAM_RULE_CUMPROB, phi),
+                                    use_mask=False)
+    assert np.array_equal(ids, ids_o)
+    np.testing.assert_allclose(gw, g_o, atol=2e-6, rtol=0)
+    clear = _cumprob_margin(d["router_logits"], cfg.K, phi) > 1e-5    # fp32 vs fp64 sums
+    assert clear.mean() > 0.97
+    assert np.array_equal(mids[clear], msk_o[clear])
+    kept = (mids >= 0).sum(axis=1)
+    assert (mids[:, 0] >= 0).all() and kept.min() >= 1
+    _log(f"  {cfg.name} phi={phi}: kept/token mean {kept.mean():.2f} max {kept.max()}; "
+         f"{int((~clear).sum())} tokens inside the guard band")
+
+
+@pytest.mark.parametrize("cfg", [SMALL_BF16, PREFILL_SMALL, CFG["tiny"]],
+                         ids=lambda c: f"{c.name}-T{c.T}")
+def test_moe_forward_rule(cfg):
+    d = hp.make_tie_free(cfg)
+    g = hp.upload(cfg, d)
+    s = hp.shape_of(cfg)
+    ws, nb = hp.workspace(s)
+    for kind_o, rule, label in ((oracle.RULE_CUMPROB, (beam.BEAM_RULE_CUMPROB, 0.4), "cumprob"),
+                                (oracle.RULE_THRESHOLD, (beam.BEAM_RULE_MASK, 0.0), "mask")):
+        ref = oracle.moe_forward_rule(d["x"], d["w_router"], d["b_router"], d["w_mask"],
+                                      d["b_mask"], d["w_gate_up"], d["w_down"], cfg.K, kind_o,
+                                      rule[1])
+        out = hp.out_tensor(cfg)
+        mids = torch.full((cfg.T, cfg.K), -7, dtype=torch.int32, device="cuda")
+        npairs = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+        beam.beam_moe_forward_rule(s, rule, g["x"], g["w_router"], g["b_router"], g["w_mask"],
+                                   g["b_mask"], g["w_gate_up"], g["w_down"], out, None, None,
+                                   mids, npairs, ws, nb, hp.stream_ptr())
+        torch.cuda.synchronize()
+        clear = np.ones(cfg.T, bool) if label == "mask" else \
+            _cumprob_margin(d["router_logits"], cfg.K, rule[1]) > 1e-5
+        assert clear.mean() > 0.95
+        assert np.array_equal(mids.cpu().numpy()[clear], ref["masked_ids"][clear])
+        got = out.float().cpu().numpy().astype(np.float64)
+        _, ratio = hp.output_error(got[clear], ref["out"][clear], cfg.dtype)
+        _log(f"  forward_rule {cfg.name} {label}: P={int(npairs.item())} worst/bound={ratio:.3f}")
+        assert ratio <= 1.0
+        if label == "mask":                               # theta = 0 is beam_moe_forward
+            plain = hp.forward(cfg, g)
+            assert np.array_equal(got, plain["out"])
+
+
+def test_rule_argument_checks():
+    cfg = SMALL_BF16
+    d = hp.make_tie_free(cfg, with_experts=False)
+    g = hp.upload(cfg, d)
+    s = hp.shape_of(cfg)
+    ws, nb = hp.workspace(s)
+    ids = torch.empty((cfg.T, cfg.K), dtype=torch.int32, device="cuda")
+    gw = torch.empty((cfg.T, cfg.K), dtype=torch.float32, device="cuda")
+    args = (g["x"], g["w_router"], g["b_router"], g["w_mask"], g["b_mask"], ids, gw, ids.clone(),
+            None, None, ws, nb, hp.stream_ptr())
+    bad = beam.binding.BEAM_ERR_INVALID_ARG
+    assert beam.beam_route_rule(s, None, *args, check=False) == bad
+    assert beam.beam_route_rule(s, (7, 0.0), *args, check=False) == bad
+    assert beam.beam_route_rule(s, (beam.BEAM_RULE_MASK, float("nan")), *args, check=False) == bad
+    # the mask head may be left out only under the cumulative-probability rule
+    no_mask = (g["x"], g["w_router"], g["b_router"], None, None) + args[5:]
+    assert beam.beam_route_rule(s, (beam.BEAM_RULE_MASK, 0.0), *no_mask, check=False) == bad
+    assert beam.beam_route_rule(s, (beam.BEAM_RULE_CUMPROB, 0.5), *no_mask, check=False) == 0
+    torch.cuda.synchronize()
