@@ -124,6 +124,49 @@ def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp, packed
     }
 
 
+def measure_rules(cfg, g, weight_sets, steps, torch, beam, hp):
+    """The same layer under other activation rules (Sec. 4.1 baselines, Sec. 4.4
+    ablation), same inputs and weights: us per layer and kept pairs per token.
+    Layer time follows the experts touched, whatever rule chose them."""
+    import math
+    T, K = cfg.T, cfg.K
+    s = hp.shape_of(cfg)
+    ws, nb = hp.workspace(s)
+    out = hp.out_tensor(cfg)
+    npairs = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    stream = hp.stream_ptr()
+    all_kept = torch.full((cfg.N,), 1.0e4, dtype=torch.float32, device="cuda")
+    cases = [("mask tau=0.5 (the paper's rule)", s, (beam.BEAM_RULE_MASK, 0.0), g["b_mask"])]
+    for tau in (0.3, 0.7):
+        cases.append((f"mask tau={tau}", s, (beam.BEAM_RULE_MASK, math.log(tau / (1 - tau))),
+                      g["b_mask"]))
+    for phi in (0.02, 0.05, 0.1):
+        cases.append((f"cumulative probability phi={phi}", s, (beam.BEAM_RULE_CUMPROB, phi),
+                      g["b_mask"]))
+    for k2 in (1, 2, K):
+        cases.append((f"top-{k2} of the same router, nothing masked", hp.shape_of(cfg.with_(K=k2)),
+                      (beam.BEAM_RULE_MASK, 0.0), all_kept))
+    res = []
+    for label, shape, rule, b_mask in cases:
+        def step(i, want=False):
+            wgu, wd = weight_sets[i % len(weight_sets)]
+            beam.beam_moe_forward_rule(shape, rule, g["x"], g["w_router"], g["b_router"],
+                                       g["w_mask"], b_mask, wgu, wd, out, None, None, None,
+                                       npairs if want else None, ws, nb, stream)
+        step(0, want=True)
+        for i in range(5):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(i)
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) * 1e6 / steps
+        res.append({"rule": label, "us_per_layer": us, "kept_pairs_per_token":
+                    int(npairs.item()) / T})
+    return res
+
+
 def upload_layer(cfg, d, hp, synth):
     """Device buffers of a layer; with a shared expert its S blocks are appended
     to the expert arrays and the gate vector and residual come along."""
@@ -229,6 +272,9 @@ def main():
                      (gg["w_gate_up"].clone(), gg["w_down"].clone())]
             points.append(measure_point(c, dd, gg, bsets, psteps, 10, torch, beam, hp))
             del dd, gg, bsets
+    rules = []
+    if not args.no_points and args.workload == "qwen3_decode":
+        rules = measure_rules(cfg, g, sets, max(20, args.steps // 4), torch, beam, hp)
     for p in points:
         p["roofline"] = roofline_of(p)
         p.pop("gate_up")
@@ -277,6 +323,7 @@ def main():
         "roofline": roofline_of(main_pt),
         "cpu_baseline": cpu,
         "points": points,
+        "rules": rules,
     }
     print(json.dumps(rec))
 
