@@ -45,6 +45,8 @@ def parse_args():
     ap.add_argument("--packed", action="store_true",
                     help="run the main workload from weights repacked once by beam_pack_weights "
                          "(the prefill points always do)")
+    ap.add_argument("--stack-layers", type=int, default=48,
+                    help="depth of the decode stack replayed under one HIP graph (0 = skip)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="also run a plain device copy of this many MiB a few times (a kernel of "
                          "known traffic, to calibrate rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -167,6 +169,91 @@ def measure_rules(cfg, g, weight_sets, steps, torch, beam, hp):
     return res
 
 
+def measure_decode_stack(cfg, n_layers, batches, torch, beam, hp, synth):
+    """A stack of n_layers masked-MoE blocks (h' = h + layer(h), App. A.3 without a
+    shared expert) with their own weights, run for one decode step: eager launches
+    against one HIP graph replay.  Keep rate per layer rises linearly with depth
+    around the workload's mean (deeper layers keep more in decode, Sec. 4.4).
+    Weights are drawn on the device (N(0, 0.02^2), bf16): this is a timing run; the
+    per-layer arithmetic is what the parity tests cover."""
+    dt = torch.bfloat16
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.seed_for(cfg, 99))
+
+    def rnd(*shape, std=0.02):
+        return (torch.randn(*shape, generator=gen, device="cuda", dtype=torch.float32) * std).to(dt)
+
+    layers = []
+    for l in range(n_layers):
+        keep = cfg.keep * (0.4 + 1.2 * l / max(1, n_layers - 1))
+        bm = torch.full((cfg.N,), synth.mask_bias_value(cfg.with_(keep=keep)),
+                        dtype=torch.float32, device="cuda")
+        layers.append((rnd(cfg.N, cfg.H), rnd(cfg.N, cfg.H), bm, rnd(cfg.N, 2 * cfg.I, cfg.H),
+                       rnd(cfg.N, cfg.H, cfg.I)))
+    res = []
+    for T in batches:
+        c = cfg.with_(T=T)
+        s = hp.shape_of(c)
+        nb = beam.beam_block_workspace_bytes(s, 0)
+        ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+        x0 = rnd(T, cfg.H, std=1.0)
+        bufs = [torch.empty_like(x0), torch.empty_like(x0)]
+        npairs = torch.zeros((n_layers,), dtype=torch.int32, device="cuda")
+
+        def run_stack(count_pairs=False):
+            h = x0
+            for l, (wr, wm, bm, wgu, wd) in enumerate(layers):
+                out = bufs[l & 1]
+                beam.beam_moe_block_forward(s, 0, h, wr, None, wm, bm, wgu, wd, None, h, out,
+                                            None, None, None,
+                                            npairs[l:l + 1] if count_pairs else None, ws, nb,
+                                            torch.cuda.current_stream().cuda_stream)
+                h = out
+            return h
+
+        final = run_stack(count_pairs=True).clone()
+        torch.cuda.synchronize()
+        kept = npairs.cpu().numpy()
+        reps = 10
+        for _ in range(2):
+            run_stack()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            run_stack()
+        torch.cuda.synchronize()
+        eager_us = (time.perf_counter() - t0) * 1e6 / reps
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            run_stack()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                h_graph = run_stack()
+        torch.cuda.synchronize()
+        same = True
+        for _ in range(3):                      # every replay must equal the eager result
+            graph.replay()
+            torch.cuda.synchronize()
+            same = same and bool(torch.equal(h_graph, final))
+            run_stack()                         # eager work between replays
+            torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - t0) * 1e6 / reps
+        res.append({"T": T, "layers": n_layers, "eager_us_per_step": eager_us,
+                    "graph_us_per_step": graph_us, "graph_us_per_layer": graph_us / n_layers,
+                    "tokens_per_s_graph": T / (graph_us * 1e-6),
+                    "kept_pairs_per_token_first_last": [float(kept[0]) / T, float(kept[-1]) / T],
+                    "kept_pairs_per_token_mean": float(kept.mean()) / T,
+                    "graph_replays_equal_eager": same})
+        del graph
+    return res
+
+
 def upload_layer(cfg, d, hp, synth):
     """Device buffers of a layer; with a shared expert its S blocks are appended
     to the expert arrays and the gate vector and residual come along."""
@@ -275,6 +362,9 @@ def main():
     rules = []
     if not args.no_points and args.workload == "qwen3_decode":
         rules = measure_rules(cfg, g, sets, max(20, args.steps // 4), torch, beam, hp)
+    stack = []
+    if not args.no_points and args.workload == "qwen3_decode" and args.stack_layers > 0:
+        stack = measure_decode_stack(cfg, args.stack_layers, (1, 8, 64), torch, beam, hp, synth)
     for p in points:
         p["roofline"] = roofline_of(p)
         p.pop("gate_up")
@@ -324,6 +414,7 @@ def main():
         "cpu_baseline": cpu,
         "points": points,
         "rules": rules,
+        "decode_stack": stack,
     }
     print(json.dumps(rec))
 

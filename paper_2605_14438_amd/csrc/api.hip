@@ -363,6 +363,20 @@ static beam_status moe_forward_impl(const beam_shape *shape, int S, const beam_r
     } while (0)
     BEAM_STAGE_MARK(0);
     if (g_shared) BEAM_TRY_HIP(launch_shared_gate(s, x, w_shared_gate, g_shared, stream));
+    if (tiny_decode_supported(se, 0) && stream_ffn_supported(s)) {
+        // A handful of pairs: three kernels, routing recomputed where it is needed,
+        // pairs addressed by flat index, aggregation folded into the down projection.
+        BEAM_TRY_HIP(launch_logits(s, x, w_router, router_bias, w_mask, mask_bias, rl, ml, stream,
+                                   num_pairs_opt));
+        for (int i = 1; i <= 3; ++i) BEAM_STAGE_MARK(i);
+        BEAM_TRY_HIP(launch_tiny_gate_up(s, opt, x, rl, ml, w_gate_up, ws + L.hidden, stream));
+        BEAM_STAGE_MARK(4);
+        BEAM_TRY_HIP(launch_tiny_down_combine(s, opt, rl, ml, ws + L.hidden, w_down, residual,
+                                              out, topk_ids_opt, topk_weights_opt,
+                                              masked_ids_opt, num_pairs_opt, stream));
+        for (int i = 5; i <= 6; ++i) BEAM_STAGE_MARK(i);
+        return BEAM_OK;
+    }
     if (logits_tiled_supported(s)) {
         // prefill: both heads as one tiled GEMM into a [T,2N] array; biases join at Top-K
         BEAM_TRY_HIP(launch_logits_tiled(s, x, w_router, w_mask, ws + L.packed_heads, rl, stream));

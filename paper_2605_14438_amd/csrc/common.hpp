@@ -101,11 +101,6 @@ struct WorkList {
 WorkList work_list(void *base, const beam_shape &s, int max_tiles);
 
 // ---- launchers (each returns hipGetLastError() after enqueueing) ----------
-hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_router,
-                         const float *b_router, const void *w_mask, const float *b_mask,
-                         float *router_logits, float *mask_logits, hipStream_t st);
-hipError_t launch_shared_gate(const beam_shape &s, const void *x, const void *w_shared_gate,
-                              float *g_shared, hipStream_t st);
 // What the Top-K stage appends and decides beyond Eq. 4: S shared-expert slots
 // with per-token weight g_shared (NULL = 1), and the activation rule (0: mask
 // pre-activation >= param; 1: cumulative routing probability, param = phi).
@@ -115,6 +110,24 @@ struct RouteOpts {
     int rule = 0;
     float param = 0.0f;
 };
+// zero_word: an int32 the MFMA logits kernels reset to 0 (bf16, H % 128 == 0 only;
+// NULL: none), for a counter that a later kernel of the same call adds to
+hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_router,
+                         const float *b_router, const void *w_mask, const float *b_mask,
+                         float *router_logits, float *mask_logits, hipStream_t st,
+                         int32_t *zero_word = nullptr);
+bool tiny_decode_supported(const beam_shape &s, int S);
+hipError_t launch_tiny_gate_up(const beam_shape &s, const RouteOpts &opt, const void *x,
+                               const float *router_logits, const float *mask_logits,
+                               const void *w_gate_up, void *hidden, hipStream_t st);
+hipError_t launch_tiny_down_combine(const beam_shape &s, const RouteOpts &opt,
+                                    const float *router_logits, const float *mask_logits,
+                                    const void *hidden, const void *w_down, const void *residual,
+                                    void *out, int32_t *topk_ids_opt, float *topk_w_opt,
+                                    int32_t *masked_ids_opt, int32_t *num_pairs_opt,
+                                    hipStream_t st);
+hipError_t launch_shared_gate(const beam_shape &s, const void *x, const void *w_shared_gate,
+                              float *g_shared, hipStream_t st);
 hipError_t launch_topk_mask(const beam_shape &s, const float *router_logits,
                             const float *mask_logits, const float *b_router, const float *b_mask,
                             int row_stride, const RouteOpts &opt, int32_t *topk_ids,

@@ -15,37 +15,32 @@
 // More than 16 rows in an expert loops over row tiles (weights re-read through
 // L2); the tiled GEMM takes over when that becomes the common case.
 #include "common.hpp"
+#include "topk.hpp"
 
 namespace beam {
 
-// hidden[row, j] = bf16( SiLU(x_t . W_gate[j]) * (x_t . W_up[j]) )
-// grid (I/16, max active experts); 4 wavefronts split the reduction over H.
-__global__ __launch_bounds__(256) void gate_up_stream_kernel(
-    const bf16_t *__restrict__ x, const bf16_t *__restrict__ w_gate_up,
-    const int32_t *__restrict__ perm, WorkList wl, bf16_t *__restrict__ hidden, int H, int K,
-    int I) {
-    const int u = blockIdx.y;
-    // one round trip: the four words are independent loads
-    const int n_active = wl.hdr[0];
-    const int e = wl.active[u];
-    const int row_beg = wl.active_beg[u];
-    const int row_end = wl.active_end[u];
-    if (u >= n_active) return;
+// Rows [row_beg, row_end) of the hidden activation for the 16 gate and 16 up
+// features j0.. of expert e:  hidden[row, j] = bf16(SiLU(x_t . W_gate[j]) * (x_t . W_up[j])),
+// t = token_of(row).  The workgroup's 4 wavefronts split the reduction over H.
+template <typename TokenOf>
+__device__ __forceinline__ void gate_up_rows(const bf16_t *__restrict__ x,
+                                             const bf16_t *__restrict__ w_gate_up, int e,
+                                             int row_beg, int row_end, TokenOf token_of,
+                                             bf16_t *__restrict__ hidden, int H, int I, int j0,
+                                             float (*red)[8][64]) {
     const int lane = threadIdx.x & 63;
     const int ks = threadIdx.x >> 6;
     const int l16 = lane & 15;
     const int g = lane >> 4;
-    const int j0 = blockIdx.x * 16;
     const int klen = H >> 2;
     const int kbeg = ks * klen + g * 8;
     const bf16_t *gp = w_gate_up + ((size_t)e * 2 * I + j0 + l16) * H + kbeg;
     const bf16_t *up = gp + (size_t)I * H;
-    __shared__ float red[3][8][64];
 
     for (int row0 = row_beg; row0 < row_end; row0 += 16) {
         int row = row0 + l16;
         row = row < row_end ? row : row_end - 1;
-        const int t = perm[row] / K;
+        const int t = token_of(row);
         const bf16_t *xp = x + (size_t)t * H + kbeg;
         f32x4 ag = {0.f, 0.f, 0.f, 0.f};
         f32x4 au = {0.f, 0.f, 0.f, 0.f};
@@ -121,6 +116,193 @@ __global__ __launch_bounds__(256) void gate_up_stream_kernel(
             }
         }
         __syncthreads();
+    }
+}
+
+// grid (I/16, max active experts): expert-sorted rows from the work list.
+__global__ __launch_bounds__(256) void gate_up_stream_kernel(
+    const bf16_t *__restrict__ x, const bf16_t *__restrict__ w_gate_up,
+    const int32_t *__restrict__ perm, WorkList wl, bf16_t *__restrict__ hidden, int H, int K,
+    int I) {
+    const int u = blockIdx.y;
+    // one round trip: the four words are independent loads
+    const int n_active = wl.hdr[0];
+    const int e = wl.active[u];
+    const int row_beg = wl.active_beg[u];
+    const int row_end = wl.active_end[u];
+    if (u >= n_active) return;
+    __shared__ float red[3][8][64];
+    gate_up_rows(x, w_gate_up, e, row_beg, row_end, [&](int row) { return perm[row] / K; },
+                 hidden, H, I, blockIdx.x * 16, red);
+}
+
+// ---------------------------------------------------------------------------
+// Tiny batches (T * slots <= kTinySlots, single-token decode above all): the layer is
+// bound by the number of kernels, each a few microseconds of launch, drain and
+// first-touch latency however little it does.  So the Top-K / mask / grouping
+// kernels are dropped: every workgroup that needs a routing decision recomputes
+// it from the logits (one wavefront, about a microsecond), pairs are addressed
+// by their flat index f = t * slots + k instead of being sorted by expert, and
+// the aggregation is folded into the down projection.  Three kernels instead of
+// six.  An expert kept by two tokens is streamed twice, which at these sizes
+// (about one pair per touched expert) costs less than a kernel does.
+//
+// gate_up_slot_kernel: grid (I/16, T * slots); hidden[f, :] for kept pair f.
+// ---------------------------------------------------------------------------
+template <int RULE>
+__global__ __launch_bounds__(256) void gate_up_slot_kernel(
+    const bf16_t *__restrict__ x, const bf16_t *__restrict__ w_gate_up,
+    const float *__restrict__ router_logits, const float *__restrict__ mask_logits,
+    const float *__restrict__ g_shared, float param, bf16_t *__restrict__ hidden, int H, int N,
+    int K, int S, int I) {
+    __shared__ float red[3][8][64];
+    __shared__ int32_t ids_s[64], masked_s[64];
+    __shared__ float w_s[64];
+    const int slots = K + S;
+    const int f = blockIdx.y;
+    const int t = f / slots;
+    if (threadIdx.x < 64)
+        wave_route_token<RULE>(router_logits + (size_t)t * N, mask_logits + (size_t)t * N, nullptr,
+                               nullptr, N, K, S, (S > 0 && g_shared) ? g_shared[t] : 1.0f, param,
+                               ids_s, w_s, masked_s);
+    __syncthreads();
+    const int e = masked_s[f - t * slots];
+    if (e < 0) return;  // uniform over the workgroup
+    gate_up_rows(x, w_gate_up, e, f, f + 1, [&](int) { return t; }, hidden, H, I,
+                 blockIdx.x * 16, red);
+}
+
+// down_combine_token_kernel: grid (H / (16*FT), T); a workgroup owns 16*FT
+// output features of one token.  out[t, c] = (h[t, c] +) sum over the token's kept
+// slots, in slot order, of g_k * (hidden[f_k, :] . W_down[e_k][c, :]).  The four
+// wavefronts take the kept slots round-robin (each runs the reduction of
+// down_stream_kernel for its slot) and park the fp32 results in LDS; wavefront 0
+// then adds them up in slot order, exactly the running sum of the combine kernel,
+// and rounds once.  Every wavefront recomputes the token's routing; workgroup 0
+// of a token also reports it.
+template <int FT, int RULE>
+__global__ __launch_bounds__(256) void down_combine_token_kernel(
+    const bf16_t *__restrict__ hidden, const bf16_t *__restrict__ w_down,
+    const float *__restrict__ router_logits, const float *__restrict__ mask_logits,
+    const float *__restrict__ g_shared, float param, const bf16_t *__restrict__ residual,
+    bf16_t *__restrict__ out, int32_t *__restrict__ topk_ids_opt, float *__restrict__ topk_w_opt,
+    int32_t *__restrict__ masked_ids_opt, int32_t *__restrict__ num_pairs_opt, int H, int N, int K,
+    int S, int I) {
+    __shared__ int32_t ids_s[4][64], masked_s[4][64];
+    __shared__ float w_s[4][64];
+    __shared__ float y_s[64][FT][4][4];  // [kept slot ordinal][tile][feature group g][r]
+    const int slots = K + S;
+    const int t = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int l16 = lane & 15;
+    const int g = lane >> 4;
+    wave_route_token<RULE>(router_logits + (size_t)t * N, mask_logits + (size_t)t * N, nullptr,
+                           nullptr, N, K, S, (S > 0 && g_shared) ? g_shared[t] : 1.0f, param,
+                           ids_s[wave], w_s[wave], masked_s[wave]);
+    __builtin_amdgcn_wave_barrier();  // a wavefront reads back only its own copy
+    const bool in = lane < slots;
+    const uint64_t kept = __ballot(in && masked_s[wave][in ? lane : 0] >= 0);
+    if (blockIdx.x == 0 && wave == 0) {
+        const size_t f = (size_t)t * slots + lane;
+        if (in && topk_ids_opt) topk_ids_opt[f] = ids_s[0][lane];
+        if (in && topk_w_opt) topk_w_opt[f] = w_s[0][lane];
+        if (in && masked_ids_opt) masked_ids_opt[f] = masked_s[0][lane];
+        // the logits kernel of this call has zeroed the counter
+        if (num_pairs_opt && lane == 0) atomicAdd(num_pairs_opt, __popcll(kept));
+    }
+    const int c0 = blockIdx.x * (16 * FT);
+    const bf16_t *wrow[FT];
+#pragma unroll
+    for (int f = 0; f < FT; ++f) {
+        int c = c0 + f * 16 + l16;
+        c = c < H ? c : H - 1;
+        wrow[f] = w_down + (size_t)c * I + g * 8;
+    }
+    int ord = 0;
+    for (uint64_t m = kept; m; m &= m - 1, ++ord) {
+        if ((ord & 3) != wave) continue;  // wave-uniform
+        const int k = __builtin_ctzll(m);
+        const int e = masked_s[wave][k];
+        const bf16_t *hp = hidden + ((size_t)t * slots + k) * I + g * 8;
+        const size_t eoff = (size_t)e * H * I;
+        f32x4 acc[FT];
+#pragma unroll
+        for (int f = 0; f < FT; ++f) acc[f] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // same two-deep software pipeline as the streaming kernels
+        uint4 w[2][FT][4], hv[2][4];
+        auto load = [&](int b, int kk) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                for (int f = 0; f < FT; ++f)
+                    w[b][f][j] = *(const uint4 *)(wrow[f] + eoff + kk + j * 32);
+                hv[b][j] = *(const uint4 *)(hp + kk + j * 32);
+            }
+        };
+        auto mma = [&](int b) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int f = 0; f < FT; ++f)
+                    acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8, w[b][f][j]), __builtin_bit_cast(bf16x8, hv[b][j]),
+                        acc[f], 0, 0, 0);
+        };
+        load(0, 0);
+        int kk = 0;
+        for (; kk + 256 < I; kk += 256) {
+            load(1, kk + 128);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(0);
+            __builtin_amdgcn_sched_barrier(0);
+            load(0, kk + 256);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (kk + 128 < I) {
+            load(1, kk + 128);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(0);
+            mma(1);
+        } else {
+            mma(0);
+        }
+        // every column of the MFMA result is the same hidden row: lanes with l16 == 0
+        // hold features 4*g .. 4*g+3 of each tile
+        if (l16 == 0) {
+#pragma unroll
+            for (int f = 0; f < FT; ++f)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) y_s[ord][f][g][r] = acc[f][r];
+        }
+    }
+    __syncthreads();
+    if (wave == 0 && l16 == 0) {
+#pragma unroll
+        for (int f = 0; f < FT; ++f) {
+            const int c = c0 + f * 16 + g * 4;
+            if (c >= H) continue;
+            float tot[4] = {0.f, 0.f, 0.f, 0.f};
+            if (residual) {
+                const uint2 q = *(const uint2 *)(residual + (size_t)t * H + c);
+                tot[0] = __uint_as_float(q.x << 16);
+                tot[1] = __uint_as_float(q.x & 0xffff0000u);
+                tot[2] = __uint_as_float(q.y << 16);
+                tot[3] = __uint_as_float(q.y & 0xffff0000u);
+            }
+            int j = 0;
+            for (uint64_t m = kept; m; m &= m - 1, ++j) {
+                const float gk = w_s[0][__builtin_ctzll(m)];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) tot[r] = fmaf(gk, y_s[j][f][g][r], tot[r]);
+            }
+            uint2 q;
+            q.x = (uint32_t)f32_to_bf16(tot[0]) | ((uint32_t)f32_to_bf16(tot[1]) << 16);
+            q.y = (uint32_t)f32_to_bf16(tot[2]) | ((uint32_t)f32_to_bf16(tot[3]) << 16);
+            *(uint2 *)(out + (size_t)t * H + c) = q;
+        }
     }
 }
 
@@ -238,6 +420,50 @@ hipError_t launch_down_stream(const beam_shape &s, const void *hidden, const voi
     (void)offsets;
     down_stream_kernel<FT><<<grid, 256, 0, st>>>((const bf16_t *)hidden, (const bf16_t *)w_down, wl,
                                                  y_pairs, s.H, s.I);
+    return hipGetLastError();
+}
+
+// The three-kernel path above.  Logits [T,N] x 2 with biases already added.
+constexpr int kTinySlots = 24;
+bool tiny_decode_supported(const beam_shape &s, int S) {
+    // Measured against the six-kernel path (Qwen3-shaped layer, 8 slots per token): 19.6 vs
+    // 28.9 us at T = 1, 27.4 vs 30.6 at T = 3, level at T = 4, slower from there on, because
+    // every slot's workgroups pay for a routing pass before most of them find their slot
+    // masked.
+    return stream_ffn_supported(s) && s.weight_layout == BEAM_WEIGHTS_PLAIN &&
+           (long)s.T * (s.K + S) <= kTinySlots && s.K + S <= 64;
+}
+
+hipError_t launch_tiny_gate_up(const beam_shape &s, const RouteOpts &opt, const void *x,
+                               const float *router_logits, const float *mask_logits,
+                               const void *w_gate_up, void *hidden, hipStream_t st) {
+    const dim3 grid(s.I / 16, s.T * (s.K + opt.S));
+#define BEAM_TINY(RULE)                                                                         \
+    gate_up_slot_kernel<RULE><<<grid, 256, 0, st>>>(                                            \
+        (const bf16_t *)x, (const bf16_t *)w_gate_up, router_logits, mask_logits, opt.g_shared, \
+        opt.param, (bf16_t *)hidden, s.H, s.N, s.K, opt.S, s.I)
+    if (opt.rule == kRuleCumProb) BEAM_TINY(kRuleCumProb);
+    else BEAM_TINY(kRuleMask);
+#undef BEAM_TINY
+    return hipGetLastError();
+}
+
+hipError_t launch_tiny_down_combine(const beam_shape &s, const RouteOpts &opt,
+                                    const float *router_logits, const float *mask_logits,
+                                    const void *hidden, const void *w_down, const void *residual,
+                                    void *out, int32_t *topk_ids_opt, float *topk_w_opt,
+                                    int32_t *masked_ids_opt, int32_t *num_pairs_opt,
+                                    hipStream_t st) {
+    constexpr int FT = 2;
+    const dim3 grid((s.H + 16 * FT - 1) / (16 * FT), s.T);
+#define BEAM_TINY(RULE)                                                                         \
+    down_combine_token_kernel<FT, RULE><<<grid, 256, 0, st>>>(                                  \
+        (const bf16_t *)hidden, (const bf16_t *)w_down, router_logits, mask_logits,             \
+        opt.g_shared, opt.param, (const bf16_t *)residual, (bf16_t *)out, topk_ids_opt,         \
+        topk_w_opt, masked_ids_opt, num_pairs_opt, s.H, s.N, s.K, opt.S, s.I)
+    if (opt.rule == kRuleCumProb) BEAM_TINY(kRuleCumProb);
+    else BEAM_TINY(kRuleMask);
+#undef BEAM_TINY
     return hipGetLastError();
 }
 

@@ -58,7 +58,9 @@ __global__ __launch_bounds__(64 * WAVES_N * KSPLIT) void logits_mfma_kernel(
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ w_router,
     const float *__restrict__ b_router, const bf16_t *__restrict__ w_mask,
     const float *__restrict__ b_mask, float *__restrict__ router_logits,
-    float *__restrict__ mask_logits, int Tn, int H, int N) {
+    float *__restrict__ mask_logits, int Tn, int H, int N, int32_t *__restrict__ zero_word) {
+    // a counter a later kernel of the same call accumulates into (NULL: none)
+    if (zero_word && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *zero_word = 0;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int wn = wave % WAVES_N;
@@ -158,7 +160,8 @@ __global__ __launch_bounds__(64 * WAVES_N * KSPLIT) void logits_mfma_kernel(
 
 hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_router,
                          const float *b_router, const void *w_mask, const float *b_mask,
-                         float *router_logits, float *mask_logits, hipStream_t st) {
+                         float *router_logits, float *mask_logits, hipStream_t st,
+                         int32_t *zero_word) {
     const int T = s.T, H = s.H, N = s.N;
     if (s.dtype == BEAM_BF16 && H % 128 == 0) {
         const bf16_t *xb = (const bf16_t *)x;
@@ -167,15 +170,15 @@ hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_route
         if (T <= 512 && H % 2048 == 0) {
             dim3 grid((T + 15) / 16, (2 * N + 15) / 16);
             logits_mfma_kernel<1, 1, 1, 16><<<grid, 1024, 0, st>>>(
-                xb, wr, b_router, wm, b_mask, router_logits, mask_logits, T, H, N);
+                xb, wr, b_router, wm, b_mask, router_logits, mask_logits, T, H, N, zero_word);
         } else if (T <= 512 && H % 512 == 0) {
             dim3 grid((T + 15) / 16, (2 * N + 15) / 16);
             logits_mfma_kernel<1, 1, 1, 4><<<grid, 256, 0, st>>>(
-                xb, wr, b_router, wm, b_mask, router_logits, mask_logits, T, H, N);
+                xb, wr, b_router, wm, b_mask, router_logits, mask_logits, T, H, N, zero_word);
         } else {
             dim3 grid((T + 31) / 32, (2 * N + 255) / 256);
             logits_mfma_kernel<2, 4, 4, 1><<<grid, 256, 0, st>>>(
-                xb, wr, b_router, wm, b_mask, router_logits, mask_logits, T, H, N);
+                xb, wr, b_router, wm, b_mask, router_logits, mask_logits, T, H, N, zero_word);
         }
     } else {
         dim3 grid(T, (2 * N + 3) / 4);

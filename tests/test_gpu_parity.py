@@ -742,3 +742,95 @@ def test_rule_argument_checks():
     assert beam.beam_route_rule(s, (beam.BEAM_RULE_MASK, 0.0), *no_mask, check=False) == bad
     assert beam.beam_route_rule(s, (beam.BEAM_RULE_CUMPROB, 0.5), *no_mask, check=False) == 0
     torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------------------
+# the three-kernel path of the fused entry points for T * slots <= 24
+# ---------------------------------------------------------------------------
+def _staged(cfg, g):
+    """The layer through the four staged entry points (the six-kernel path)."""
+    s = hp.shape_of(cfg)
+    ws, nb = hp.workspace(s)
+    T, K, N = cfg.T, cfg.K, cfg.N
+    ids = torch.empty((T, K), dtype=torch.int32, device="cuda")
+    gw = torch.empty((T, K), dtype=torch.float32, device="cuda")
+    mids = torch.empty((T, K), dtype=torch.int32, device="cuda")
+    counts = torch.empty((N,), dtype=torch.int32, device="cuda")
+    offsets = torch.empty((N + 1,), dtype=torch.int32, device="cuda")
+    perm = torch.empty((T * K,), dtype=torch.int32, device="cuda")
+    inv = torch.empty((T * K,), dtype=torch.int32, device="cuda")
+    P = torch.empty((1,), dtype=torch.int32, device="cuda")
+    y = torch.empty((T * K, cfg.H), dtype=torch.float32, device="cuda")
+    out = hp.out_tensor(cfg)
+    st = hp.stream_ptr()
+    beam.beam_route_mask(s, g["x"], g["w_router"], g["b_router"], g["w_mask"], g["b_mask"], ids,
+                         gw, mids, None, None, ws, nb, st)
+    beam.beam_permute(s, mids, counts, offsets, perm, inv, P, ws, nb, st)
+    beam.beam_expert_ffn(s, g["x"], g["w_gate_up"], g["w_down"], offsets, perm, P, y, ws, nb, st)
+    beam.beam_combine(s, y, gw, mids, inv, out, st)
+    torch.cuda.synchronize()
+    return out, mids.cpu().numpy(), int(P.item())
+
+
+@pytest.mark.parametrize("T,keep", [(1, 0.15), (1, 1.0), (2, 0.5), (3, 0.15), (3, 1.0), (3, 0.0),
+                                    (4, 0.5)])
+def test_tiny_batch_path_equals_staged_path_bit_for_bit(T, keep):
+    """Same reductions in the same order: the three-kernel path (T <= 3 here) must
+    reproduce the six-kernel path exactly, and both the oracle within the output
+    bound.  T = 4 is the first size back on the six-kernel path."""
+    cfg = CFG["qwen3_decode"].with_(T=T, keep=keep)
+    _log(f"tiny path {cfg}")
+    d = hp.make_tie_free(cfg)
+    g = hp.upload(cfg, d)
+    res = hp.forward(cfg, g)                              # all optional outputs requested
+    out_staged, mids_staged, P_staged = _staged(cfg, g)
+    assert torch.equal(res["out_raw"], out_staged)
+    assert np.array_equal(res["masked_ids"], mids_staged) and res["num_pairs"] == P_staged
+    ref = oracle.moe_forward(d["x"], d["w_router"], d["b_router"], d["w_mask"], d["b_mask"],
+                             d["w_gate_up"], d["w_down"], cfg.K)
+    _check_forward(cfg, d, res, ref)
+    # without any optional output (what a serving loop calls)
+    s = hp.shape_of(cfg)
+    ws, nb = hp.workspace(s)
+    out2 = hp.out_tensor(cfg)
+    beam.beam_moe_forward(s, g["x"], g["w_router"], g["b_router"], g["w_mask"], g["b_mask"],
+                          g["w_gate_up"], g["w_down"], out2, None, None, None, None, ws, nb,
+                          hp.stream_ptr())
+    torch.cuda.synchronize()
+    assert torch.equal(out2, out_staged)
+
+
+def test_tiny_batch_path_rules_and_block():
+    cfg = CFG["qwen3_decode"].with_(T=3, keep=0.5)
+    d = hp.make_tie_free(cfg)
+    g = hp.upload(cfg, d)
+    s = hp.shape_of(cfg)
+    ws, nb = hp.workspace(s)
+    phi = 0.04
+    ref = oracle.moe_forward_rule(d["x"], d["w_router"], d["b_router"], d["w_mask"], d["b_mask"],
+                                  d["w_gate_up"], d["w_down"], cfg.K, oracle.RULE_CUMPROB, phi)
+    out = hp.out_tensor(cfg)
+    mids = torch.full((cfg.T, cfg.K), -7, dtype=torch.int32, device="cuda")
+    npairs = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    beam.beam_moe_forward_rule(s, (beam.BEAM_RULE_CUMPROB, phi), g["x"], g["w_router"],
+                               g["b_router"], None, None, g["w_gate_up"], g["w_down"], out, None,
+                               None, mids, npairs, ws, nb, hp.stream_ptr())
+    torch.cuda.synchronize()
+    assert (_cumprob_margin(d["router_logits"], cfg.K, phi) > 1e-5).all()
+    assert np.array_equal(mids.cpu().numpy(), ref["masked_ids"])
+    assert int(npairs.item()) == ref["pair_evals"]
+    _, ratio = hp.output_error(out.float().cpu().numpy().astype(np.float64), ref["out"], cfg.dtype)
+    assert ratio <= 1.0
+    # whole block with a gated shared expert and a residual at T * (K + S) <= 24
+    bcfg = CFG["dsv2_lite"].with_(T=3, shared_gate=True)
+    assert bcfg.T * (bcfg.K + bcfg.S) <= 24
+    bd = hp.make_tie_free(bcfg)
+    bref = _block_ref(bcfg, bd)
+    bres = hp.block_forward(bcfg, bd)
+    _check_block_slots(bcfg, bres, bref["topk_ids"], bref["topk_weights"], bref["masked_ids"],
+                       bref["g_shared"], bcfg.S)
+    _, ratio = hp.output_error(bres["out"], bref["out"], bcfg.dtype)
+    assert ratio <= 1.0
+    part = bref["out"] - bd["residual"].astype(np.float64)
+    err = np.abs(bres["out"] - bref["out"])
+    assert (err <= 2e-2 * np.sqrt((part ** 2).mean()) + 2.0 ** -8 * np.abs(bref["out"])).all()
