@@ -48,6 +48,7 @@ def _load() -> ctypes.CDLL:
         lib.beam_oracle_moe_forward.restype = ctypes.c_int64
         lib.beam_oracle_block_forward.restype = ctypes.c_int64
         lib.beam_oracle_route_rule.restype = None
+        lib.beam_oracle_train_step.restype = None
         lib.beam_oracle_moe_forward_rule.restype = ctypes.c_int64
         _lib = lib
     return _lib
@@ -253,6 +254,37 @@ def block_forward(x, w_router, b_router, w_mask, b_mask, w_gate_up, w_down, K: i
         _ptr(g, _f64p), _ptr(msk, _i32p), _ptr(gsh, _f64p), int(nthreads))
     return {"out": out, "topk_ids": ids, "topk_weights": g, "masked_ids": msk,
             "g_shared": gsh, "pair_evals": int(n)}
+
+
+def train_step(x, w_router, b_router, w_mask, b_mask, w_gate_up, w_down, K: int, grad_out,
+               reg_coeff: float):
+    """Training-mode forward and the mask router's backward (Sec. 3.3, Eq. 9-12) ->
+    dict(out [T,H], grad_a [T,K], grad_w_mask [N,H], loss_reg [T], topk_ids, masked_ids)."""
+    x = _f32(x)
+    wr = _f32(w_router)
+    wm = _f32(w_mask)
+    br = None if b_router is None else _f32(b_router)
+    bm = None if b_mask is None else _f32(b_mask)
+    wgu = _f32(w_gate_up)
+    wd = _f32(w_down)
+    dy = _f32(grad_out)
+    T, H = x.shape
+    N, H2, I = wd.shape
+    assert H2 == H and wr.shape == (N, H) and wm.shape == (N, H) and wgu.shape == (N, 2 * I, H)
+    assert dy.shape == (T, H) and 1 <= K <= N
+    out = np.empty((T, H), dtype=np.float64)
+    ga = np.empty((T, K), dtype=np.float64)
+    gw = np.empty((N, H), dtype=np.float64)
+    lr = np.empty((T,), dtype=np.float64)
+    ids = np.empty((T, K), dtype=np.int32)
+    msk = np.empty((T, K), dtype=np.int32)
+    _load().beam_oracle_train_step(
+        T, H, N, K, I, _ptr(x, _f32p), _ptr(wr, _f32p), _ptr(br, _f32p), _ptr(wm, _f32p),
+        _ptr(bm, _f32p), _ptr(wgu, _f32p), _ptr(wd, _f32p), _ptr(dy, _f32p),
+        ctypes.c_double(reg_coeff), _ptr(out, _f64p), _ptr(ga, _f64p), _ptr(gw, _f64p),
+        _ptr(lr, _f64p), _ptr(ids, _i32p), _ptr(msk, _i32p))
+    return {"out": out, "grad_a": ga, "grad_w_mask": gw, "loss_reg": lr, "topk_ids": ids,
+            "masked_ids": msk}
 
 
 def decision_margin(router_logits, mask_logits, K: int) -> np.ndarray:

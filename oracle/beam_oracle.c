@@ -41,6 +41,11 @@
  *         phi, i.e. slot k is kept iff sum_{j<k} p_ids[j] <= phi (the first slot
  *         always is); at most the K slots exist.  The paper names the rule and
  *         its threshold only; this is the reading taken.
+ *   - Training (Sec. 3.3): every Top-K expert is evaluated whatever the mask says
+ *     and the output uses the binary mask; the mask router's gradient is Eq. 12
+ *     with dL_lm/dg^_i = <dL/dy, E_i(x)> (y is linear in g^); L_reg is returned
+ *     per token, and the coefficient c that multiplies 1/K in Eq. 12 is an
+ *     input (beta, or beta/T for a batch mean: the paper fixes no reduction).
  *   - Whole block (App. A.3): the layer input x is the already normalised
  *     hidden state, the residual h is a separate input; the shared expert is
  *     one GLU expert of its own width; its weight g_sh, for which the paper
@@ -50,7 +55,9 @@
  * micro case, all-ones / all-zero mask, dense library evaluation, brute force
  * over mask patterns, special cases K=1 / K=N / N=K=1, permutation invariants;
  * for the whole block: the zero-activation forms of App. A.3, a dense library
- * evaluation and the micro case extended by a shared expert and a residual).
+ * evaluation and the micro case extended by a shared expert and a residual;
+ * for the mask-router gradient: central differences of the soft surrogate
+ * under a linear loss, the zero rows of Theorem 1, and a closed form).
  */
 #include <math.h>
 #include <stdint.h>
@@ -428,4 +435,67 @@ int64_t beam_oracle_block_forward(int T, int H, int N, int K, int I, const float
             g_shared[t] = gsh;
     }
     return evals;
+}
+
+/* Training mode (Sec. 3.3), one batch.
+ * Forward: Top-K, g and the binary mask as in inference, but E_i(x_t) is
+ * evaluated for EVERY Top-K slot (Sec. 3.3.1); out[t] = sum_k m_k g_k E_k(x_t).
+ * Backward for the mask router under the straight-through estimator (Eq. 9):
+ *   dL/dg^_k  = <grad_out[t,:], E_k(x_t)>                       (y = sum g^_k E_k)
+ *   grad_a[t,k] = (dL/dg^_k * g_k + c / K) * sigma'(a_k)        (Eq. 12, i in T_K)
+ *   grad_w_mask[e,:] = sum over (t,k) with ids[t,k] = e of grad_a[t,k] * x[t,:]
+ *   loss_reg[t] = (1/K) * sum_k sigma(a_k)                      (Eq. 10)
+ * with a_k the mask pre-activation of the slot's expert, sigma'(a) =
+ * sigma(a)(1 - sigma(a)).  Experts outside the Top-K set of a token get no
+ * gradient from it (Theorem 1).  Outputs: out [T,H], grad_a [T,K],
+ * grad_w_mask [N,H], loss_reg [T], all fp64; topk_ids / masked_ids optional. */
+void beam_oracle_train_step(int T, int H, int N, int K, int I, const float *x,
+                            const float *w_router, const float *b_router, const float *w_mask,
+                            const float *b_mask, const float *w_gate_up, const float *w_down,
+                            const float *grad_out, double reg_coeff, double *out,
+                            double *grad_a, double *grad_w_mask, double *loss_reg,
+                            int32_t *topk_ids, int32_t *masked_ids)
+{
+    for (size_t i = 0; i < (size_t)N * H; ++i)
+        grad_w_mask[i] = 0.0;
+    float *r = (float *)malloc(sizeof(float) * (size_t)N);
+    float *a = (float *)malloc(sizeof(float) * (size_t)N);
+    int32_t *ids = (int32_t *)malloc(sizeof(int32_t) * (size_t)K);
+    int32_t *msk = (int32_t *)malloc(sizeof(int32_t) * (size_t)K);
+    double *g = (double *)malloc(sizeof(double) * (size_t)K);
+    double *y = (double *)malloc(sizeof(double) * (size_t)H);
+    for (int t = 0; t < T; ++t) {
+        const float *xt = x + (size_t)t * H;
+        const float *dy = grad_out + (size_t)t * H;
+        beam_oracle_logits(1, H, N, xt, w_router, b_router, r);
+        beam_oracle_logits(1, H, N, xt, w_mask, b_mask, a);
+        route_mask_token(N, K, r, a, ids, g, msk);
+        double *o = out + (size_t)t * H;
+        for (int c = 0; c < H; ++c)
+            o[c] = 0.0;
+        double reg = 0.0;
+        for (int k = 0; k < K; ++k) {
+            int e = ids[k];
+            beam_oracle_expert_ffn(H, I, xt, w_gate_up + (size_t)e * 2 * I * H,
+                                   w_down + (size_t)e * H * I, y);
+            if (msk[k] >= 0)
+                for (int c = 0; c < H; ++c)
+                    o[c] += g[k] * y[c];
+            double dot = 0.0;
+            for (int c = 0; c < H; ++c)
+                dot += (double)dy[c] * y[c];
+            double sig = 1.0 / (1.0 + exp(-(double)a[e]));
+            double ga = (dot * g[k] + reg_coeff / (double)K) * sig * (1.0 - sig);
+            grad_a[(size_t)t * K + k] = ga;
+            reg += sig;
+            for (int h = 0; h < H; ++h)
+                grad_w_mask[(size_t)e * H + h] += ga * (double)xt[h];
+            if (topk_ids)
+                topk_ids[(size_t)t * K + k] = ids[k];
+            if (masked_ids)
+                masked_ids[(size_t)t * K + k] = msk[k];
+        }
+        loss_reg[t] = reg / (double)K;
+    }
+    free(r); free(a); free(ids); free(msk); free(g); free(y);
 }

@@ -554,3 +554,87 @@ def test_moe_forward_rule_is_layer_on_the_rule_mask():
     ref = (res["topk_weights"][:, :, None] * y.reshape(7, 3, 24)).sum(axis=1)
     assert n == res["pair_evals"] == int((res["masked_ids"] >= 0).sum())
     np.testing.assert_allclose(res["out"], ref, atol=1e-12 * np.abs(ref).max(), rtol=0)
+
+
+# --------------------------------------------------------------------------
+# training mode: straight-through gradient of the mask router (Sec. 3.3, Eq. 9-12)
+# --------------------------------------------------------------------------
+def _soft_surrogate(d, K, w_mask, c_lin, reg_coeff):
+    """sum_t <c_t, sum_{i in T_K} g_i sigma(a_i) E_i(x_t)> + reg_coeff/K sum sigma(a_i): the smooth
+    function whose exact gradient the straight-through rule reproduces when the loss is linear
+    in y (then dL/dy does not depend on the mask)."""
+    x = d["x"].astype(np.float64)
+    ids, g, _ = oracle.route_mask(oracle.logits(d["x"], d["w_router"]),
+                                  np.zeros((x.shape[0], d["w_router"].shape[0]), np.float32), K)
+    a = x @ w_mask.astype(np.float64).T
+    total = 0.0
+    for t in range(x.shape[0]):
+        for k in range(K):
+            e = int(ids[t, k])
+            sig = 1.0 / (1.0 + np.exp(-a[t, e]))
+            y = oracle.expert_ffn(d["x"][t], d["w_gate_up"][e], d["w_down"][e])
+            total += g[t, k] * sig * float(c_lin[t].astype(np.float64) @ y) + reg_coeff / K * sig
+    return total
+
+
+def test_mask_router_gradient_matches_finite_differences_of_the_soft_surrogate():
+    T, H, N, K, I = 5, 12, 6, 3, 7
+    d = _rand_layer(21, T, H, N, K, I, mask_scale=2.0)
+    rng = np.random.default_rng(5)
+    c_lin = rng.standard_normal((T, H)).astype(np.float32)
+    beta = 0.37
+    res = oracle.train_step(d["x"], d["w_router"], None, d["w_mask"], None, d["w_gate_up"],
+                            d["w_down"], K, c_lin, beta)
+    # finite differences on a sample of W_m entries (float64 perturbations of the fp32 weights)
+    wm = d["w_mask"].astype(np.float64)
+    for (e, h) in [(0, 0), (1, 5), (2, 11), (3, 3), (4, 7), (5, 1)]:
+        eps = 1e-5
+        wp, wn = wm.copy(), wm.copy()
+        wp[e, h] += eps
+        wn[e, h] -= eps
+        fd = (_soft_surrogate(d, K, wp, c_lin, beta) - _soft_surrogate(d, K, wn, c_lin, beta)) / (2 * eps)
+        assert abs(res["grad_w_mask"][e, h] - fd) <= 1e-6 * max(1.0, abs(fd)), (e, h)
+    # forward: all Top-K evaluated, output uses the binary mask == the inference layer
+    inf = _fwd(d, K)
+    np.testing.assert_allclose(res["out"], inf["out"], atol=1e-12 * np.abs(inf["out"]).max(), rtol=0)
+    assert np.array_equal(res["masked_ids"], inf["masked_ids"])
+    # L_reg = (1/K) sum over the Top-K set of sigma(a)  (Eq. 10)
+    a = oracle.logits(d["x"], d["w_mask"]).astype(np.float64)
+    sig = 1.0 / (1.0 + np.exp(-np.take_along_axis(a, res["topk_ids"].astype(np.int64), axis=1)))
+    np.testing.assert_allclose(res["loss_reg"], sig.mean(axis=1), atol=1e-12, rtol=0)
+
+
+def test_mask_router_gradient_selective_propagation_and_closed_form():
+    """Theorem 1: an expert outside every token's Top-K set gets exactly no gradient; and
+    grad_a = (<dy, E> g + c/K) sigma'(a) checked by hand on the micro case."""
+    T, H, N, K, I = 6, 8, 10, 2, 5
+    d = _rand_layer(33, T, H, N, K, I)
+    dy = np.random.default_rng(2).standard_normal((T, H)).astype(np.float32)
+    res = oracle.train_step(d["x"], d["w_router"], None, d["w_mask"], None, d["w_gate_up"],
+                            d["w_down"], K, dy, 0.5)
+    never = np.setdiff1d(np.arange(N), np.unique(res["topk_ids"]))
+    assert never.size > 0 and (res["grad_w_mask"][never] == 0).all()
+    chosen = np.unique(res["topk_ids"])
+    assert (np.abs(res["grad_w_mask"][chosen]).sum(axis=1) > 0).all()
+    # micro case (tests/golden/micro_case.json): token A = (1,0): ids (0,1), g = (3/4, 1/4),
+    # a = (1, -1); E_0(A) = y0 from the fixture's derivation, dy = (1, 0) picks its first entry
+    with open(os.path.join(GOLDEN, "micro_case.json")) as fh:
+        c = json.load(fh)
+    ln3 = np.log(3.0)
+    s1 = 1.0 / (1.0 + np.exp(-1.0))
+    hid = np.array([2 * s1, -0.75 * ln3])
+    y0 = np.array([hid[0] + 2 * hid[1], -hid[0] + 0.5 * hid[1]])          # expert 0 on A
+    res = oracle.train_step(np.array(c["x"][:1]), np.array(c["w_router"]), None,
+                            np.array(c["w_mask"]), None, np.array(c["w_gate_up"]),
+                            np.array(c["w_down"]), 2, np.array([[1.0, 0.0]]), 0.2)
+    sp1 = s1 * (1 - s1)                                                   # sigma'(1) = sigma'(-1)
+    want0 = (y0[0] * 0.75 + 0.2 / 2) * sp1
+    np.testing.assert_allclose(res["grad_a"][0, 0], want0, atol=1e-7, rtol=1e-6)
+    # slot 1 is masked (a = -1) but still evaluated and still receives a gradient
+    y1 = oracle.expert_ffn(np.array(c["x"][0]), np.array(c["w_gate_up"][1]), np.array(c["w_down"][1]))
+    np.testing.assert_allclose(res["grad_a"][0, 1], (y1[0] * 0.25 + 0.1) * sp1, atol=1e-7, rtol=1e-6)
+    np.testing.assert_allclose(res["loss_reg"][0], 0.5 * (s1 + (1 - s1)), atol=1e-12, rtol=0)
+    # grad_w_mask = grad_a (x) x: token A = (1, 0) touches column 0 of rows 0 and 1 only
+    gw = res["grad_w_mask"]
+    np.testing.assert_allclose(gw[:2, 0], res["grad_a"][0], atol=1e-12, rtol=0)
+    assert (gw[:, 1] == 0).all() and (gw[2] == 0).all()
