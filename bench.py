@@ -126,6 +126,59 @@ def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp, packed
     }
 
 
+def measure_training_step(cfg, g, wgu, wd, packed, steps, torch, beam, hp):
+    """Training mode (Sec. 3.3) at a prefill-sized batch: the forward evaluates every
+    Top-K expert and applies the mask in the sum (staged entry points), then the
+    mask router's straight-through backward (Eq. 9-12) with L_reg.  Times both."""
+    T, K, N, H = cfg.T, cfg.K, cfg.N, cfg.H
+    s = hp.shape_of(cfg, packed=packed)
+    ws, nb = hp.workspace(s)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    f32 = dict(dtype=torch.float32, device="cuda")
+    ids, mids = torch.empty((T, K), **i32), torch.empty((T, K), **i32)
+    gw, ml = torch.empty((T, K), **f32), torch.empty((T, N), **f32)
+    counts, offsets = torch.empty((N,), **i32), torch.empty((N + 1,), **i32)
+    perm, inv, P = torch.empty((T * K,), **i32), torch.empty((T * K,), **i32), torch.empty((1,), **i32)
+    y = torch.empty((T * K, H), **f32)
+    out = hp.out_tensor(cfg)
+    dy = torch.randn((T, H), device="cuda").to(out.dtype)
+    grad_a, grad_w = torch.empty((T, K), **f32), torch.empty((N, H), **f32)
+    loss_reg = torch.empty((T,), **f32)
+    st = hp.stream_ptr()
+
+    def forward():
+        beam.beam_route_mask(s, g["x"], g["w_router"], g["b_router"], g["w_mask"], g["b_mask"],
+                             ids, gw, mids, None, ml, ws, nb, st)
+        beam.beam_permute(s, ids, counts, offsets, perm, inv, P, ws, nb, st)
+        beam.beam_expert_ffn(s, g["x"], wgu, wd, offsets, perm, P, y, ws, nb, st)
+        beam.beam_combine(s, y, gw, mids, inv, out, st)
+
+    def backward():
+        beam.beam_mask_router_backward(s, g["x"], ids, gw, ml, y, offsets, perm, inv, dy, 1e-3,
+                                       grad_a, grad_w, loss_reg, ws, nb, st)
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e6 / steps
+
+    fwd_us = timed(forward)
+    bwd_us = timed(backward)
+    esz = 2 if cfg.dtype == "bf16" else 4
+    # the backward reads every expert output row once (fp32), dL/dy and x per token
+    # (re-read per slot from cache), and writes grad_a and grad_w_mask
+    bwd_bytes = T * K * H * 4 + 2 * T * H * esz + T * K * 4 * 3 + N * H * 4
+    return {"workload": f"{cfg.name} T={T} keep={cfg.keep}, all Top-K evaluated",
+            "forward_us": fwd_us, "mask_router_backward_us": bwd_us,
+            "backward_GBs": bwd_bytes / (bwd_us * 1e-6) / 1e9,
+            "backward_frac_hbm": bwd_bytes / (bwd_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+
+
 def measure_rules(cfg, g, weight_sets, steps, torch, beam, hp):
     """The same layer under other activation rules (Sec. 4.1 baselines, Sec. 4.4
     ablation), same inputs and weights: us per layer and kept pairs per token.
@@ -335,6 +388,7 @@ def main():
                             args.warmup, torch, beam, hp, packed=args.packed)
 
     points = []
+    training = None
     if not args.no_points and args.workload == "qwen3_decode":
         psteps = max(20, args.steps // 4)
         for T in (1, 8, 32):
@@ -349,6 +403,12 @@ def main():
             gg = {**hp.upload(c, dd), "w_gate_up": g["w_gate_up"], "w_down": g["w_down"]}
             points.append(measure_point(c, dd, gg, get_packed_sets(), n, 3, torch, beam, hp,
                                         packed=True))
+        c = pre.with_(T=16384, keep=0.15)
+        dd = synth.make_layer(c, with_experts=False)
+        gg = hp.upload(c, dd)
+        pw = get_packed_sets()[0]
+        training = measure_training_step(c, gg, pw[0], pw[1], True, 10, torch, beam, hp)
+        del dd, gg, pw
         # the two shared-expert model shapes (whole block: residual + routed + shared)
         packed_sets = None           # free the repacked Qwen3 copies
         for name in ("qwen15_moe", "dsv2_lite"):
@@ -415,6 +475,7 @@ def main():
         "points": points,
         "rules": rules,
         "decode_stack": stack,
+        "training_step": training,
     }
     print(json.dumps(rec))
 

@@ -266,6 +266,37 @@ beam_status beam_moe_block_forward(const beam_shape *shape, int32_t num_shared, 
                                    void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Training mode (Sec. 3.3).  The forward of training evaluates EVERY Top-K expert
+ * whatever the mask says (Sec. 3.3.1) and applies the binary mask in the sum; it
+ * composes from the entry points above: beam_route_mask, beam_permute on topk_ids
+ * (not masked_ids), beam_expert_ffn, beam_combine with masked_ids and that
+ * grouping's inv_perm.  This call is the mask router's backward under the
+ * straight-through estimator (Eq. 9) with the sparsity regulariser (Eq. 10):
+ *   dL/dg^_k       = <grad_out[t,:], y_pairs[inv_perm[t*K+k], :]>
+ *   grad_a[t,k]    = (dL/dg^_k * topk_weights[t,k] + reg_coeff / K) * sigma'(a)   (Eq. 12)
+ *                    with a = mask_logits[t, topk_ids[t,k]], sigma' = sigma (1 - sigma)
+ *   grad_w_mask[e] = sum over the pairs (t,k) of expert e of grad_a[t,k] * x[t,:]
+ *   loss_reg[t]    = (1/K) sum_k sigma(a)                                          (Eq. 10)
+ * in   mask_logits [T,N] fp32 (beam_route_mask's mask_logits_dbg); y_pairs [T*K,H]
+ *      fp32, expert_offsets [N+1], perm, inv_perm [T*K]: expert outputs and grouping
+ *      of ALL Top-K pairs; grad_out [T,H] dtype = dL/dy; reg_coeff = the factor of
+ *      L_reg in the loss (beta, or beta/T if the caller averages over tokens: the
+ *      paper fixes no reduction).
+ * out  grad_a [T,K] fp32; grad_w_mask [N,H] fp32 (rows of experts that no token
+ *      selected are zero: Theorem 1); loss_reg [T] fp32.
+ * fp32 arithmetic, fixed summation order (per 128-row tile, then per expert): the
+ * result is reproducible run to run.  T = 0 writes nothing.
+ */
+beam_status beam_mask_router_backward(const beam_shape *shape, const void *x,
+                                      const int32_t *topk_ids, const float *topk_weights,
+                                      const float *mask_logits, const float *y_pairs,
+                                      const int32_t *expert_offsets, const int32_t *perm,
+                                      const int32_t *inv_perm, const void *grad_out,
+                                      float reg_coeff, float *grad_a, float *grad_w_mask,
+                                      float *loss_reg, void *workspace, size_t workspace_bytes,
+                                      void *hip_stream);
+
+/*
  * Measurement aid, not part of the layer: beam_moe_forward with a HIP event
  * recorded on `hip_stream` before and after every stage.  Unlike every other
  * entry point this one creates and destroys events and WAITS for the stream;

@@ -30,7 +30,7 @@ EXPORTS = ("beam_abi_version", "beam_status_string", "beam_workspace_bytes", "be
            "beam_permute", "beam_expert_ffn", "beam_combine", "beam_moe_forward",
            "beam_moe_forward_timed", "beam_pack_weights", "beam_block_workspace_bytes",
            "beam_moe_block_forward", "beam_moe_block_forward_timed", "beam_route_rule",
-           "beam_moe_forward_rule")
+           "beam_moe_forward_rule", "beam_mask_router_backward")
 BEAM_RULE_MASK = 0
 BEAM_RULE_CUMPROB = 1
 BEAM_NUM_STAGES = 6
@@ -88,6 +88,9 @@ def load() -> ctypes.CDLL:
         lib.beam_route_rule.argtypes = [sp, rp] + [vp] * 11 + [sz, vp]
         lib.beam_moe_forward_rule.restype = ctypes.c_int
         lib.beam_moe_forward_rule.argtypes = [sp, rp] + [vp] * 13 + [sz, vp]
+        lib.beam_mask_router_backward.restype = ctypes.c_int
+        lib.beam_mask_router_backward.argtypes = [sp] + [vp] * 9 + [ctypes.c_float] + [vp] * 4 + [
+            sz, vp]
         lib.beam_block_workspace_bytes.restype = sz
         lib.beam_block_workspace_bytes.argtypes = [sp, ctypes.c_int32]
         lib.beam_moe_block_forward.restype = ctypes.c_int
@@ -277,3 +280,16 @@ def beam_moe_forward_rule(shape, rule, x, w_router, router_bias, w_mask, mask_bi
                                       _p(num_pairs_opt), _p(workspace), int(workspace_bytes),
                                       _p(hip_stream))
     return _check("beam_moe_forward_rule", st, check)
+
+
+def beam_mask_router_backward(shape, x, topk_ids, topk_weights, mask_logits, y_pairs,
+                              expert_offsets, perm, inv_perm, grad_out, reg_coeff, grad_a,
+                              grad_w_mask, loss_reg, workspace, workspace_bytes, hip_stream=None,
+                              check: bool = True) -> int:
+    s = _shape(shape)
+    st = load().beam_mask_router_backward(
+        ctypes.byref(s), _p(x), _p(topk_ids), _p(topk_weights), _p(mask_logits), _p(y_pairs),
+        _p(expert_offsets), _p(perm), _p(inv_perm), _p(grad_out), ctypes.c_float(reg_coeff),
+        _p(grad_a), _p(grad_w_mask), _p(loss_reg), _p(workspace), int(workspace_bytes),
+        _p(hip_stream))
+    return _check("beam_mask_router_backward", st, check)

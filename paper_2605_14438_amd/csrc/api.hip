@@ -29,6 +29,15 @@ hipError_t launch_down_tiled(const beam_shape &s, const void *hidden, const void
 hipError_t launch_pack_weights(const beam_shape &s, const void *w_gate_up, const void *w_down,
                                void *w_gate_up_packed, void *w_down_packed, hipStream_t st);
 
+hipError_t launch_mask_router_backward(const beam_shape &s, const void *x,
+                                       const int32_t *topk_ids, const float *topk_w,
+                                       const float *mask_logits, const float *y_pairs,
+                                       const int32_t *offsets, const int32_t *perm,
+                                       const int32_t *inv_perm, const void *grad_out,
+                                       float reg_coeff, const WorkList &wl, int max_tiles,
+                                       float *partial, float *grad_a, float *grad_w_mask,
+                                       float *loss_reg, hipStream_t st);
+
 static inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
 WsLayout ws_layout(const beam_shape &s) {
@@ -63,6 +72,7 @@ WsLayout ws_layout(const beam_shape &s) {
     L.work = take((16 + 3 * N + 2 * (size_t)L.max_tiles) * 4);
     L.hidden = take(TK * (size_t)s.I * esz);
     L.y_pairs = take(TK * (size_t)s.H * 4);
+    L.tile_partial = take((size_t)L.max_tiles * s.H * 4);
     L.total = off;
     return L;
 }
@@ -452,6 +462,38 @@ beam_status beam_moe_block_forward(const beam_shape *shape, int32_t num_shared, 
                             mask_bias, w_gate_up, w_down, w_shared_gate, residual, out, topk_ids_opt,
                             topk_weights_opt, masked_ids_opt, num_pairs_opt, workspace,
                             workspace_bytes, hip_stream, nullptr);
+}
+
+beam_status beam_mask_router_backward(const beam_shape *shape, const void *x,
+                                      const int32_t *topk_ids, const float *topk_weights,
+                                      const float *mask_logits, const float *y_pairs,
+                                      const int32_t *expert_offsets, const int32_t *perm,
+                                      const int32_t *inv_perm, const void *grad_out,
+                                      float reg_coeff, float *grad_a, float *grad_w_mask,
+                                      float *loss_reg, void *workspace, size_t workspace_bytes,
+                                      void *hip_stream) {
+    beam_status st = check_shape(shape);
+    if (st != BEAM_OK) return st;
+    const beam_shape &s = *shape;
+    if (!x || !topk_ids || !topk_weights || !mask_logits || !y_pairs || !expert_offsets || !perm ||
+        !inv_perm || !grad_out || !grad_a || !grad_w_mask || !loss_reg)
+        return BEAM_ERR_INVALID_ARG;
+    if (misaligned(x) || misaligned(y_pairs) || misaligned(grad_out) || misaligned(grad_w_mask))
+        return BEAM_ERR_INVALID_ARG;
+    if (!(reg_coeff == reg_coeff)) return BEAM_ERR_INVALID_ARG;
+    const WsLayout L = ws_layout(s);
+    st = check_ws(s, workspace, workspace_bytes, L);
+    if (st != BEAM_OK) return st;
+    if (s.T == 0) return BEAM_OK;  // nothing selected: grad_w_mask is left untouched
+    char *ws = (char *)workspace;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const WorkList wl = work_list(ws + L.work, s, L.max_tiles);
+    BEAM_TRY_HIP(launch_work_list(s, expert_offsets, wl, stream));
+    BEAM_TRY_HIP(launch_mask_router_backward(s, x, topk_ids, topk_weights, mask_logits, y_pairs,
+                                             expert_offsets, perm, inv_perm, grad_out, reg_coeff,
+                                             wl, L.max_tiles, (float *)(ws + L.tile_partial), grad_a,
+                                             grad_w_mask, loss_reg, stream));
+    return BEAM_OK;
 }
 
 static beam_status timed_impl(const beam_shape *shape, int32_t num_shared, const void *x,

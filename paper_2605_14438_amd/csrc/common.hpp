@@ -76,6 +76,7 @@ struct WsLayout {
     size_t work;           // work list, see WorkList
     size_t hidden;         // [T*K, I] dtype : SiLU(gate)*up of every grouped row
     size_t y_pairs;        // [T*K, H] f32
+    size_t tile_partial;   // [max_tiles, H] f32 : per-tile sums of the mask-router backward
     size_t total;
     int nchunk;
     int max_tiles;

@@ -834,3 +834,77 @@ def test_tiny_batch_path_rules_and_block():
     part = bref["out"] - bd["residual"].astype(np.float64)
     err = np.abs(bres["out"] - bref["out"])
     assert (err <= 2e-2 * np.sqrt((part ** 2).mean()) + 2.0 ** -8 * np.abs(bref["out"])).all()
+
+
+# ---------------------------------------------------------------------------
+# training mode (Sec. 3.3): all Top-K experts evaluated, mask applied in the sum;
+# straight-through gradient of the mask router (Eq. 9-12) and L_reg (Eq. 10)
+# ---------------------------------------------------------------------------
+def _train_step_gpu(cfg, d, g, dy_host, reg_coeff):
+    s = hp.shape_of(cfg)
+    ws, nb = hp.workspace(s)
+    T, K, N, H = cfg.T, cfg.K, cfg.N, cfg.H
+    i32 = dict(dtype=torch.int32, device="cuda")
+    f32 = dict(dtype=torch.float32, device="cuda")
+    ids, mids = torch.empty((T, K), **i32), torch.empty((T, K), **i32)
+    gw = torch.empty((T, K), **f32)
+    ml = torch.empty((T, N), **f32)
+    counts, offsets = torch.empty((N,), **i32), torch.empty((N + 1,), **i32)
+    perm, inv, P = torch.empty((T * K,), **i32), torch.empty((T * K,), **i32), torch.empty((1,), **i32)
+    y = torch.empty((T * K, H), **f32)
+    out = hp.out_tensor(cfg)
+    st = hp.stream_ptr()
+    beam.beam_route_mask(s, g["x"], g["w_router"], g["b_router"], g["w_mask"], g["b_mask"], ids,
+                         gw, mids, None, ml, ws, nb, st)
+    beam.beam_permute(s, ids, counts, offsets, perm, inv, P, ws, nb, st)       # ALL Top-K pairs
+    beam.beam_expert_ffn(s, g["x"], g["w_gate_up"], g["w_down"], offsets, perm, P, y, ws, nb, st)
+    beam.beam_combine(s, y, gw, mids, inv, out, st)                            # mask in the sum
+    dy = hp.dev(dy_host, cfg.dtype)
+    grad_a = torch.full((T, K), float("nan"), **f32)
+    grad_w = torch.full((N, H), float("nan"), **f32)
+    loss_reg = torch.full((T,), float("nan"), **f32)
+    beam.beam_mask_router_backward(s, g["x"], ids, gw, ml, y, offsets, perm, inv, dy, reg_coeff,
+                                   grad_a, grad_w, loss_reg, ws, nb, st)
+    torch.cuda.synchronize()
+    assert int(P.item()) == T * K
+    return (out, mids.cpu().numpy(), grad_a.cpu().numpy(), grad_w.cpu().numpy(),
+            loss_reg.cpu().numpy())
+
+
+@pytest.mark.parametrize("cfg", [CFG["tiny"], SMALL_BF16, PREFILL_SMALL, ODD_BF16,
+                                 CFG["qwen3_decode"].with_(T=24)],
+                         ids=lambda c: f"{c.name}-T{c.T}")
+def test_training_step_mask_router_backward(cfg):
+    _log(f"train step {cfg}")
+    d = hp.make_tie_free(cfg)
+    g = hp.upload(cfg, d)
+    rng = np.random.default_rng(synth.seed_for(cfg, 5))
+    dy = rng.standard_normal((cfg.T, cfg.H)).astype(np.float32)
+    if cfg.dtype == "bf16":
+        dy = synth.bf16_round(dy)
+    beta = 0.01
+    ref = oracle.train_step(d["x"], d["w_router"], d["b_router"], d["w_mask"], d["b_mask"],
+                            d["w_gate_up"], d["w_down"], cfg.K, dy, beta)
+    out, mids, grad_a, grad_w, loss_reg = _train_step_gpu(cfg, d, g, dy, beta)
+    assert np.array_equal(mids, ref["masked_ids"])
+    # the training forward is the inference layer computed the long way round
+    _, ratio = hp.output_error(out.float().cpu().numpy().astype(np.float64), ref["out"], cfg.dtype)
+    assert ratio <= 1.0
+    # gradients: fp32 sums over H of products with the bf16-rounded hidden activation
+    tol = 2e-2 if cfg.dtype == "bf16" else 1e-4
+    scale = np.sqrt((ref["grad_a"] ** 2).mean())
+    assert np.abs(grad_a - ref["grad_a"]).max() <= tol * scale
+    wscale = np.sqrt((ref["grad_w_mask"] ** 2).mean())
+    assert np.abs(grad_w - ref["grad_w_mask"]).max() <= tol * max(wscale, 1e-30)
+    np.testing.assert_allclose(loss_reg, ref["loss_reg"], atol=1e-6, rtol=0)
+    never = np.setdiff1d(np.arange(cfg.N), np.unique(ref["topk_ids"]))
+    assert (grad_w[never] == 0).all()                      # Theorem 1: exactly no gradient
+    # given the GPU's own grad_a, grad_w_mask is a segmented sum: exact up to fp32 order
+    x64 = d["x"].astype(np.float64)
+    want = np.zeros((cfg.N, cfg.H))
+    np.add.at(want, ref["topk_ids"].reshape(-1),
+              grad_a.reshape(-1, 1).astype(np.float64) * np.repeat(x64, cfg.K, axis=0))
+    assert np.abs(grad_w - want).max() <= 1e-5 * max(np.abs(want).max(), 1e-30)
+    # reproducible: a second run gives the same bits
+    _, _, grad_a2, grad_w2, _ = _train_step_gpu(cfg, d, g, dy, beta)
+    assert np.array_equal(grad_a, grad_a2) and np.array_equal(grad_w, grad_w2)
