@@ -215,9 +215,21 @@ static beam_status route_impl(const beam_shape *shape, const beam_rule *rule, co
     if (st != BEAM_OK) return st;
     if (s.T == 0) return BEAM_OK;
     char *ws = (char *)workspace;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (logits_tiled_supported(s)) {
+        // prefill-sized: both heads as one tiled GEMM into [T,2N]; biases join at Top-K and
+        // in the optional copies
+        float *l2 = (float *)(ws + L.router_logits);
+        BEAM_TRY_HIP(launch_logits_tiled(s, x, w_router, w_mask, ws + L.packed_heads, l2, stream));
+        BEAM_TRY_HIP(launch_topk_mask(s, l2, l2 + s.N, router_bias, mask_bias, 2 * s.N, opt,
+                                      topk_ids, topk_weights, masked_ids, stream));
+        if (router_logits_dbg || mask_logits_dbg)
+            BEAM_TRY_HIP(launch_split_logits(s, l2, router_bias, mask_bias, router_logits_dbg,
+                                             mask_logits_dbg, stream));
+        return BEAM_OK;
+    }
     float *rl = router_logits_dbg ? router_logits_dbg : (float *)(ws + L.router_logits);
     float *ml = mask_logits_dbg ? mask_logits_dbg : (float *)(ws + L.mask_logits);
-    hipStream_t stream = (hipStream_t)hip_stream;
     BEAM_TRY_HIP(launch_logits(s, x, w_router, router_bias, w_mask, mask_bias, rl, ml, stream));
     BEAM_TRY_HIP(launch_topk_mask(s, rl, ml, nullptr, nullptr, s.N, opt, topk_ids, topk_weights,
                                   masked_ids, stream));

@@ -117,6 +117,9 @@ hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_route
                          const float *b_router, const void *w_mask, const float *b_mask,
                          float *router_logits, float *mask_logits, hipStream_t st,
                          int32_t *zero_word = nullptr);
+hipError_t launch_split_logits(const beam_shape &s, const float *logits2, const float *b_router,
+                               const float *b_mask, float *router_logits, float *mask_logits,
+                               hipStream_t st);
 bool tiny_decode_supported(const beam_shape &s, int S);
 hipError_t launch_tiny_gate_up(const beam_shape &s, const RouteOpts &opt, const void *x,
                                const float *router_logits, const float *mask_logits,

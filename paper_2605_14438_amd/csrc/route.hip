@@ -195,6 +195,37 @@ hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_route
 }
 
 // ---------------------------------------------------------------------------
+// [T,2N] logits without biases (what the tiled GEMM writes) -> the two [T,N]
+// arrays with biases that callers of the staged entry point may ask for.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void split_logits_kernel(
+    const float *__restrict__ logits2, const float *__restrict__ b_router,
+    const float *__restrict__ b_mask, float *__restrict__ router_logits,
+    float *__restrict__ mask_logits, int Tn, int N) {
+    const size_t total = (size_t)Tn * 2 * N;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int c = (int)(i % (2 * N));
+        const size_t t = i / (2 * N);
+        const float v = logits2[i];
+        if (c < N) {
+            if (router_logits) router_logits[t * N + c] = b_router ? v + b_router[c] : v;
+        } else {
+            if (mask_logits) mask_logits[t * N + c - N] = b_mask ? v + b_mask[c - N] : v;
+        }
+    }
+}
+
+hipError_t launch_split_logits(const beam_shape &s, const float *logits2, const float *b_router,
+                               const float *b_mask, float *router_logits, float *mask_logits,
+                               hipStream_t st) {
+    const size_t total = (size_t)s.T * 2 * s.N;
+    const int grid = (int)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
+    split_logits_kernel<<<grid, 256, 0, st>>>(logits2, b_router, b_mask, router_logits,
+                                              mask_logits, s.T, s.N);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Weight of the shared expert (App. A.3): g_sh[t] = sigma(x_t . w), one
 // wavefront per token, fp32.
 // ---------------------------------------------------------------------------
