@@ -22,12 +22,15 @@ namespace beam {
 // Rows [row_beg, row_end) of the hidden activation for the 16 gate and 16 up
 // features j0.. of expert e:  hidden[row, j] = bf16(SiLU(x_t . W_gate[j]) * (x_t . W_up[j])),
 // t = token_of(row).  The workgroup's 4 wavefronts split the reduction over H.
-template <typename TokenOf>
+// RT row tiles of 16 rows share one pass over the weights (RT = 2 for experts
+// with more than 16 rows, a shared expert above all: one pass per 32 rows
+// instead of two; RT = 4 would halve the occupancy of every workgroup).  red: LDS, 3 * 8 * RT * 64 floats.
+template <int RT, typename TokenOf>
 __device__ __forceinline__ void gate_up_rows(const bf16_t *__restrict__ x,
                                              const bf16_t *__restrict__ w_gate_up, int e,
                                              int row_beg, int row_end, TokenOf token_of,
                                              bf16_t *__restrict__ hidden, int H, int I, int j0,
-                                             float (*red)[8][64]) {
+                                             float *red) {
     const int lane = threadIdx.x & 63;
     const int ks = threadIdx.x >> 6;
     const int l16 = lane & 15;
@@ -36,19 +39,27 @@ __device__ __forceinline__ void gate_up_rows(const bf16_t *__restrict__ x,
     const int kbeg = ks * klen + g * 8;
     const bf16_t *gp = w_gate_up + ((size_t)e * 2 * I + j0 + l16) * H + kbeg;
     const bf16_t *up = gp + (size_t)I * H;
+    auto red_at = [&](int s, int v, int l) -> float & { return red[(s * 8 * RT + v) * 64 + l]; };
 
-    for (int row0 = row_beg; row0 < row_end; row0 += 16) {
-        int row = row0 + l16;
-        row = row < row_end ? row : row_end - 1;
-        const int t = token_of(row);
-        const bf16_t *xp = x + (size_t)t * H + kbeg;
-        f32x4 ag = {0.f, 0.f, 0.f, 0.f};
-        f32x4 au = {0.f, 0.f, 0.f, 0.f};
+    for (int row0 = row_beg; row0 < row_end; row0 += 16 * RT) {
+        const bf16_t *xp[RT];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            int row = row0 + rt * 16 + l16;
+            row = row < row_end ? row : row_end - 1;
+            xp[rt] = x + (size_t)token_of(row) * H + kbeg;
+        }
+        f32x4 ag[RT], au[RT];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            ag[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            au[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
         // Software pipeline over chunks of 128 reduction indices: the loads of
         // chunk c+1 are issued before the MFMAs of chunk c, so a wavefront always
         // has 12 KB in flight.  sched_barrier keeps the compiler from sinking the
         // loads back behind the MFMAs to save registers.
-        uint4 wg[2][4], wu[2][4], xv[2][4];
+        uint4 wg[2][4], wu[2][4], xv[2][RT][4];
         auto load = [&](int b, int k) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -56,18 +67,22 @@ __device__ __forceinline__ void gate_up_rows(const bf16_t *__restrict__ x,
                 wu[b][j] = *(const uint4 *)(up + k + j * 32);
             }
 #pragma unroll
-            for (int j = 0; j < 4; ++j) xv[b][j] = *(const uint4 *)(xp + k + j * 32);
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) xv[b][rt][j] = *(const uint4 *)(xp[rt] + k + j * 32);
         };
         auto mma = [&](int b) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                ag = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wg[b][j]),
-                                                             __builtin_bit_cast(bf16x8, xv[b][j]),
-                                                             ag, 0, 0, 0);
-                au = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wu[b][j]),
-                                                             __builtin_bit_cast(bf16x8, xv[b][j]),
-                                                             au, 0, 0, 0);
-            }
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+                    ag[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8, wg[b][j]),
+                        __builtin_bit_cast(bf16x8, xv[b][rt][j]), ag[rt], 0, 0, 0);
+                    au[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8, wu[b][j]),
+                        __builtin_bit_cast(bf16x8, xv[b][rt][j]), au[rt], 0, 0, 0);
+                }
         };
         // steady state without conditionals, so the wait before each MFMA group
         // counts only the older chunk's loads; the last one or two chunks are peeled
@@ -93,26 +108,32 @@ __device__ __forceinline__ void gate_up_rows(const bf16_t *__restrict__ x,
         }
         if (ks > 0) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                red[ks - 1][r][lane] = ag[r];
-                red[ks - 1][4 + r][lane] = au[r];
-            }
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    red_at(ks - 1, rt * 8 + r, lane) = ag[rt][r];
+                    red_at(ks - 1, rt * 8 + 4 + r, lane) = au[rt][r];
+                }
         }
         __syncthreads();
         if (ks == 0) {
 #pragma unroll
-            for (int s = 0; s < 3; ++s)
+            for (int rt = 0; rt < RT; ++rt) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    ag[r] += red[s][r][lane];
-                    au[r] += red[s][4 + r][lane];
+                for (int s = 0; s < 3; ++s)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        ag[rt][r] += red_at(s, rt * 8 + r, lane);
+                        au[rt][r] += red_at(s, rt * 8 + 4 + r, lane);
+                    }
+                const int row = row0 + rt * 16 + l16;
+                if (row < row_end) {
+                    uint32_t lo = (uint32_t)f32_to_bf16(silu(ag[rt][0]) * au[rt][0]) |
+                                  ((uint32_t)f32_to_bf16(silu(ag[rt][1]) * au[rt][1]) << 16);
+                    uint32_t hi = (uint32_t)f32_to_bf16(silu(ag[rt][2]) * au[rt][2]) |
+                                  ((uint32_t)f32_to_bf16(silu(ag[rt][3]) * au[rt][3]) << 16);
+                    *(uint2 *)(hidden + (size_t)row * I + j0 + g * 4) = make_uint2(lo, hi);
                 }
-            if (row0 + l16 < row_end) {
-                uint32_t lo = (uint32_t)f32_to_bf16(silu(ag[0]) * au[0]) |
-                              ((uint32_t)f32_to_bf16(silu(ag[1]) * au[1]) << 16);
-                uint32_t hi = (uint32_t)f32_to_bf16(silu(ag[2]) * au[2]) |
-                              ((uint32_t)f32_to_bf16(silu(ag[3]) * au[3]) << 16);
-                *(uint2 *)(hidden + (size_t)(row0 + l16) * I + j0 + g * 4) = make_uint2(lo, hi);
             }
         }
         __syncthreads();
@@ -131,9 +152,14 @@ __global__ __launch_bounds__(256) void gate_up_stream_kernel(
     const int row_beg = wl.active_beg[u];
     const int row_end = wl.active_end[u];
     if (u >= n_active) return;
-    __shared__ float red[3][8][64];
-    gate_up_rows(x, w_gate_up, e, row_beg, row_end, [&](int row) { return perm[row] / K; },
-                 hidden, H, I, blockIdx.x * 16, red);
+    __shared__ float red[3 * 8 * 2 * 64];
+    auto token_of = [&](int row) { return perm[row] / K; };
+    if (row_end - row_beg > 16)  // uniform over the workgroup
+        gate_up_rows<2>(x, w_gate_up, e, row_beg, row_end, token_of, hidden, H, I,
+                        blockIdx.x * 16, red);
+    else
+        gate_up_rows<1>(x, w_gate_up, e, row_beg, row_end, token_of, hidden, H, I,
+                        blockIdx.x * 16, red);
 }
 
 // ---------------------------------------------------------------------------
@@ -155,7 +181,7 @@ __global__ __launch_bounds__(256) void gate_up_slot_kernel(
     const float *__restrict__ router_logits, const float *__restrict__ mask_logits,
     const float *__restrict__ g_shared, float param, bf16_t *__restrict__ hidden, int H, int N,
     int K, int S, int I) {
-    __shared__ float red[3][8][64];
+    __shared__ float red[3 * 8 * 64];
     __shared__ int32_t ids_s[64], masked_s[64];
     __shared__ float w_s[64];
     const int slots = K + S;
@@ -168,8 +194,8 @@ __global__ __launch_bounds__(256) void gate_up_slot_kernel(
     __syncthreads();
     const int e = masked_s[f - t * slots];
     if (e < 0) return;  // uniform over the workgroup
-    gate_up_rows(x, w_gate_up, e, f, f + 1, [&](int) { return t; }, hidden, H, I,
-                 blockIdx.x * 16, red);
+    gate_up_rows<1>(x, w_gate_up, e, f, f + 1, [&](int) { return t; }, hidden, H, I,
+                    blockIdx.x * 16, red);
 }
 
 // down_combine_token_kernel: grid (H / (16*FT), T); a workgroup owns 16*FT
@@ -309,55 +335,48 @@ __global__ __launch_bounds__(256) void down_combine_token_kernel(
 // y_pairs[row, c] = hidden[row, :] . W_down[c, :]
 // grid (H / (64*FT), max active experts); each wavefront owns FT tiles of 16
 // output features and runs the whole reduction over I.
-template <int FT>
-__global__ __launch_bounds__(256) void down_stream_kernel(
-    const bf16_t *__restrict__ hidden, const bf16_t *__restrict__ w_down, WorkList wl,
-    float *__restrict__ y_pairs, int H, int I) {
-    const int u = blockIdx.y;
-    const int n_active = wl.hdr[0];
-    const int e = wl.active[u];
-    const int row_beg = wl.active_beg[u];
-    const int row_end = wl.active_end[u];
-    if (u >= n_active) return;
+// rows [row_beg, row_end) of expert e, RT row tiles of 16 per pass over the weights
+template <int FT, int RT>
+__device__ __forceinline__ void down_rows(const bf16_t *__restrict__ hidden,
+                                          const bf16_t *const (&wp)[FT], int row_beg, int row_end,
+                                          float *__restrict__ y_pairs, int H, int I, int c0) {
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
     const int l16 = lane & 15;
     const int g = lane >> 4;
-    const int c0 = (blockIdx.x * 4 + wave) * (16 * FT);
-    if (c0 >= H) return;
-    const bf16_t *wp[FT];
+    for (int row0 = row_beg; row0 < row_end; row0 += 16 * RT) {
+        const bf16_t *hp[RT];
 #pragma unroll
-    for (int f = 0; f < FT; ++f) {
-        int c = c0 + f * 16 + l16;
-        c = c < H ? c : H - 1;
-        wp[f] = w_down + ((size_t)e * H + c) * I + g * 8;
-    }
-
-    for (int row0 = row_beg; row0 < row_end; row0 += 16) {
-        int row = row0 + l16;
-        row = row < row_end ? row : row_end - 1;
-        const bf16_t *hp = hidden + (size_t)row * I + g * 8;
-        f32x4 acc[FT];
+        for (int rt = 0; rt < RT; ++rt) {
+            int row = row0 + rt * 16 + l16;
+            row = row < row_end ? row : row_end - 1;
+            hp[rt] = hidden + (size_t)row * I + g * 8;
+        }
+        f32x4 acc[RT][FT];
 #pragma unroll
-        for (int f = 0; f < FT; ++f) acc[f] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int f = 0; f < FT; ++f) acc[rt][f] = f32x4{0.f, 0.f, 0.f, 0.f};
         // same two-deep software pipeline as the gate/up kernel
-        uint4 w[2][FT][4], hv[2][4];
+        uint4 w[2][FT][4], hv[2][RT][4];
         auto load = [&](int b, int k) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
 #pragma unroll
                 for (int f = 0; f < FT; ++f) w[b][f][j] = *(const uint4 *)(wp[f] + k + j * 32);
-                hv[b][j] = *(const uint4 *)(hp + k + j * 32);
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) hv[b][rt][j] = *(const uint4 *)(hp[rt] + k + j * 32);
             }
         };
         auto mma = [&](int b) {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
-                for (int f = 0; f < FT; ++f)
-                    acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                        __builtin_bit_cast(bf16x8, w[b][f][j]), __builtin_bit_cast(bf16x8, hv[b][j]),
-                        acc[f], 0, 0, 0);
+                for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                    for (int f = 0; f < FT; ++f)
+                        acc[rt][f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            __builtin_bit_cast(bf16x8, w[b][f][j]),
+                            __builtin_bit_cast(bf16x8, hv[b][rt][j]), acc[rt][f], 0, 0, 0);
         };
         // steady state without conditionals, so the wait before each MFMA group
         // counts only the older chunk's loads; the last one or two chunks are peeled
@@ -381,16 +400,49 @@ __global__ __launch_bounds__(256) void down_stream_kernel(
         } else {
             mma(0);
         }
-        if (row0 + l16 < row_end) {
 #pragma unroll
-            for (int f = 0; f < FT; ++f) {
-                const int c = c0 + f * 16 + g * 4;
-                if (c < H)
-                    *(float4 *)(y_pairs + (size_t)(row0 + l16) * H + c) =
-                        make_float4(acc[f][0], acc[f][1], acc[f][2], acc[f][3]);
+        for (int rt = 0; rt < RT; ++rt) {
+            const int row = row0 + rt * 16 + l16;
+            if (row < row_end) {
+#pragma unroll
+                for (int f = 0; f < FT; ++f) {
+                    const int c = c0 + f * 16 + g * 4;
+                    if (c < H)
+                        *(float4 *)(y_pairs + (size_t)row * H + c) = make_float4(
+                            acc[rt][f][0], acc[rt][f][1], acc[rt][f][2], acc[rt][f][3]);
+                }
             }
         }
     }
+}
+
+template <int FT>
+__global__ __launch_bounds__(256) void down_stream_kernel(
+    const bf16_t *__restrict__ hidden, const bf16_t *__restrict__ w_down, WorkList wl,
+    float *__restrict__ y_pairs, int H, int I) {
+    const int u = blockIdx.y;
+    const int n_active = wl.hdr[0];
+    const int e = wl.active[u];
+    const int row_beg = wl.active_beg[u];
+    const int row_end = wl.active_end[u];
+    if (u >= n_active) return;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int l16 = lane & 15;
+    const int g = lane >> 4;
+    const int c0 = (blockIdx.x * 4 + wave) * (16 * FT);
+    if (c0 >= H) return;
+    const bf16_t *wp[FT];
+#pragma unroll
+    for (int f = 0; f < FT; ++f) {
+        int c = c0 + f * 16 + l16;
+        c = c < H ? c : H - 1;
+        wp[f] = w_down + ((size_t)e * H + c) * I + g * 8;
+    }
+    if (row_end - row_beg > 16)  // uniform over the workgroup
+        down_rows<FT, 2>(hidden, wp, row_beg, row_end, y_pairs, H, I, c0);
+    else
+        down_rows<FT, 1>(hidden, wp, row_beg, row_end, y_pairs, H, I, c0);
 }
 
 bool stream_ffn_supported(const beam_shape &s) {
