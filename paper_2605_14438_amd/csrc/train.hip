@@ -65,32 +65,34 @@ __global__ __launch_bounds__(256) void mask_grad_pairs_kernel(
     }
 }
 
-// grid (tiles, ceil(H / 1024)): partial[tile, c] = sum over the tile's grouped
-// rows, in row order, of grad_a[f] * x[t_f, c].
+// grid (tiles, ceil(H / 256)), one wavefront per workgroup: partial[tile, c] =
+// sum over the tile's grouped rows, in row order, of grad_a[f] * x[t_f, c].
+// Eight independent row loads are issued before the first add: the kernel is a
+// gather and lives on memory-level parallelism.
 template <typename T>
-__global__ __launch_bounds__(256) void mask_grad_w_partial_kernel(
+__global__ __launch_bounds__(64) void mask_grad_w_partial_kernel(
     const T *__restrict__ x, const float *__restrict__ grad_a, const int32_t *__restrict__ perm,
     const int32_t *__restrict__ offsets, WorkList wl, float *__restrict__ partial, int H, int K) {
     const int tile = blockIdx.x;
     if (tile >= wl.hdr[1]) return;
-    const int c = (blockIdx.y * 256 + threadIdx.x) * 4;
+    const int c = (blockIdx.y * 64 + threadIdx.x) * 4;
     if (c >= H) return;
     const int e = wl.tile_expert[tile];
     const int row0 = wl.tile_row0[tile];
     const int row_end = min(row0 + kTileM, offsets[e + 1]);
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int r = row0; r < row_end; r += 4) {
-        float4 xv[4];
-        float ga[4];
+    for (int r = row0; r < row_end; r += 8) {
+        float4 xv[8];
+        float ga[8];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {  // four independent row loads before the first add
+        for (int i = 0; i < 8; ++i) {
             const bool in = r + i < row_end;
             const int f = perm[in ? r + i : r];
             ga[i] = in ? grad_a[f] : 0.0f;
             xv[i] = ld4(x + (size_t)(f / K) * H + c);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 8; ++i) {
             const bool in = r + i < row_end;
             acc.x = in ? fmaf(ga[i], xv[i].x, acc.x) : acc.x;
             acc.y = in ? fmaf(ga[i], xv[i].y, acc.y) : acc.y;
@@ -101,30 +103,36 @@ __global__ __launch_bounds__(256) void mask_grad_w_partial_kernel(
     *(float4 *)(partial + (size_t)tile * H + c) = acc;
 }
 
-// grid (N, ceil(H / 1024)): grad_w_mask[e, c] = sum over expert e's tiles, in
-// tile order; zero for an expert no token selected (Theorem 1: no gradient).
-__global__ __launch_bounds__(256) void mask_grad_w_reduce_kernel(
+// grid (N, ceil(H / 256)), one wavefront per workgroup: grad_w_mask[e, c] = sum
+// over expert e's tiles, in tile order (loads batched by eight, adds in order);
+// zero for an expert no token selected (Theorem 1: no gradient).
+__global__ __launch_bounds__(64) void mask_grad_w_reduce_kernel(
     const float *__restrict__ partial, const int32_t *__restrict__ offsets,
     float *__restrict__ grad_w_mask, int H, int N) {
-    __shared__ int first_tile;
     const int e = blockIdx.x;
-    if (threadIdx.x == 0) first_tile = 0;
-    __syncthreads();
-    // tiles of the experts before e (integer sum: order does not matter)
+    // tiles of the experts before e: integer sum over the wavefront
     int mine = 0;
-    for (int q = threadIdx.x; q < e; q += 256) mine += tiles_of(offsets[q + 1] - offsets[q]);
-    if (mine) atomicAdd(&first_tile, mine);
-    __syncthreads();
-    const int c = (blockIdx.y * 256 + threadIdx.x) * 4;
+    for (int q = threadIdx.x; q < e; q += 64) mine += tiles_of(offsets[q + 1] - offsets[q]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mine += __shfl_xor(mine, off);
+    const int first_tile = mine;
+    const int c = (blockIdx.y * 64 + threadIdx.x) * 4;
     if (c >= H) return;
     const int nt = tiles_of(offsets[e + 1] - offsets[e]);
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int i = 0; i < nt; ++i) {
-        const float4 p = *(const float4 *)(partial + (size_t)(first_tile + i) * H + c);
-        acc.x += p.x;
-        acc.y += p.y;
-        acc.z += p.z;
-        acc.w += p.w;
+    for (int i = 0; i < nt; i += 8) {
+        float4 p[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            p[j] = *(const float4 *)(partial + (size_t)(first_tile + (i + j < nt ? i + j : i)) * H + c);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const bool in = i + j < nt;
+            acc.x += in ? p[j].x : 0.0f;
+            acc.y += in ? p[j].y : 0.0f;
+            acc.z += in ? p[j].z : 0.0f;
+            acc.w += in ? p[j].w : 0.0f;
+        }
     }
     *(float4 *)(grad_w_mask + (size_t)e * H + c) = acc;
 }
@@ -138,22 +146,22 @@ hipError_t launch_mask_router_backward(const beam_shape &s, const void *x,
                                        float *partial, float *grad_a, float *grad_w_mask,
                                        float *loss_reg, hipStream_t st) {
     const float rk = reg_coeff / (float)s.K;
-    const dim3 gp(max_tiles, (s.H + 1023) / 1024);
-    const dim3 gr(s.N, (s.H + 1023) / 1024);
+    const dim3 gp(max_tiles, (s.H + 255) / 256);
+    const dim3 gr(s.N, (s.H + 255) / 256);
     if (s.dtype == BEAM_BF16) {
         mask_grad_pairs_kernel<bf16_t><<<s.T, 256, 0, st>>>(
             topk_ids, topk_w, mask_logits, y_pairs, inv_perm, (const bf16_t *)grad_out, rk, grad_a,
             loss_reg, s.H, s.N, s.K);
-        mask_grad_w_partial_kernel<bf16_t><<<gp, 256, 0, st>>>((const bf16_t *)x, grad_a, perm,
+        mask_grad_w_partial_kernel<bf16_t><<<gp, 64, 0, st>>>((const bf16_t *)x, grad_a, perm,
                                                                offsets, wl, partial, s.H, s.K);
     } else {
         mask_grad_pairs_kernel<float><<<s.T, 256, 0, st>>>(
             topk_ids, topk_w, mask_logits, y_pairs, inv_perm, (const float *)grad_out, rk, grad_a,
             loss_reg, s.H, s.N, s.K);
-        mask_grad_w_partial_kernel<float><<<gp, 256, 0, st>>>((const float *)x, grad_a, perm,
+        mask_grad_w_partial_kernel<float><<<gp, 64, 0, st>>>((const float *)x, grad_a, perm,
                                                               offsets, wl, partial, s.H, s.K);
     }
-    mask_grad_w_reduce_kernel<<<gr, 256, 0, st>>>(partial, offsets, grad_w_mask, s.H, s.N);
+    mask_grad_w_reduce_kernel<<<gr, 64, 0, st>>>(partial, offsets, grad_w_mask, s.H, s.N);
     return hipGetLastError();
 }
 
