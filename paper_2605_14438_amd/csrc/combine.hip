@@ -126,6 +126,7 @@ static void launch_typed(const beam_shape &s, const float *y_pairs, const float 
     combine_wave_kernel<T, CH><<<wave_grid, 64 * wpb, 0, st>>>(                                 \
         y_pairs, topk_w, masked_ids, inv_perm, residual, out, s.T, s.H, s.K)
     if (s.H % 2048 == 0) BEAM_COMBINE_WAVE(8);
+    else if (s.H % 1280 == 0) BEAM_COMBINE_WAVE(5);
     else if (s.H % 1024 == 0) BEAM_COMBINE_WAVE(4);
     else if (s.H % 512 == 0) BEAM_COMBINE_WAVE(2);
     else if (s.H % 256 == 0) BEAM_COMBINE_WAVE(1);
