@@ -43,7 +43,7 @@
  *                             (16 bytes for x, weights, out, y_pairs, workspace)
  *       BEAM_ERR_UNSUPPORTED  outside the envelope: N <= 256, K <= 64,
  *                             H % 8 == 0, I % 8 == 0, T*K < 2^24; packed weights
- *                             need bf16, H % 512 == 0 and I % 128 == 0
+ *                             need bf16, H % 256 == 0 and I % 128 == 0
  *       BEAM_ERR_WORKSPACE    workspace smaller than beam_workspace_bytes()
  *       BEAM_ERR_HIP          a launch failed (hipGetLastError() != success)
  *     T == 0 returns BEAM_OK without launching anything.
