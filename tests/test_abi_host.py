@@ -135,6 +135,51 @@ def test_zero_tokens_is_ok_without_launch(lib):
     assert beam.beam_combine(s, ok, ok, ok, ok, ok, check=False) == binding.BEAM_OK
 
 
+def test_newer_entry_points_check_arguments_on_the_host(lib):
+    """Block (App. A.3), activation-rule and mask-router-backward entry points: every
+    check happens before anything is enqueued, so fake pointers are never touched."""
+    ok = 0x1000
+    bad, unsup, short = (binding.BEAM_ERR_INVALID_ARG, binding.BEAM_ERR_UNSUPPORTED,
+                         binding.BEAM_ERR_WORKSPACE)
+    s = beam.make_shape(4, 256, 8, 2, 512, beam.BEAM_F32)
+    s0 = beam.make_shape(0, 256, 8, 2, 512, beam.BEAM_F32)
+    big = 1 << 40
+
+    def block(shape, S, gate=None, res=None, ws_bytes=big, x=ok):
+        return beam.beam_moe_block_forward(shape, S, x, ok, None, ok, None, ok, ok, gate, res, ok,
+                                           None, None, None, None, ok, ws_bytes, check=False)
+    assert beam.beam_block_workspace_bytes(s, 0) == beam.beam_workspace_bytes(s)
+    assert beam.beam_block_workspace_bytes(s, 3) > beam.beam_workspace_bytes(s)
+    assert beam.beam_block_workspace_bytes(s, -1) == 0
+    assert beam.beam_block_workspace_bytes(s, 249) == 0          # N + S > 256
+    assert block(s, -1) == bad
+    assert block(s, 249) == unsup
+    assert block(s, 0, gate=ok) == bad                           # gate vector without a shared expert
+    assert block(s, 2, gate=ok + 2) == bad and block(s, 2, res=ok + 2) == bad    # misaligned
+    assert block(s, 2, ws_bytes=beam.beam_block_workspace_bytes(s, 2) - 1) == short
+    assert block(s, 2, x=None) == bad
+    assert block(s0, 2, gate=ok, res=ok) == binding.BEAM_OK      # T = 0: nothing to do
+
+    def fwd_rule(rule, shape=s0, w_mask=ok):
+        return beam.beam_moe_forward_rule(shape, rule, ok, ok, None, w_mask, None, ok, ok, ok, None,
+                                          None, None, None, ok, big, check=False)
+    assert fwd_rule(None) == bad
+    assert fwd_rule((5, 0.0)) == bad and fwd_rule((binding.BEAM_RULE_MASK, float("nan"))) == bad
+    assert fwd_rule((binding.BEAM_RULE_MASK, 0.0), w_mask=None) == bad
+    assert fwd_rule((binding.BEAM_RULE_CUMPROB, 0.3), w_mask=None) == binding.BEAM_OK
+    assert fwd_rule((binding.BEAM_RULE_MASK, -1.5)) == binding.BEAM_OK
+
+    def backward(shape=s, grad_out=ok, reg=0.1, ws_bytes=big, grad_w=ok):
+        return beam.beam_mask_router_backward(shape, ok, ok, ok, ok, ok, ok, ok, ok, grad_out, reg,
+                                              ok, grad_w, ok, ok, ws_bytes, check=False)
+    assert backward(grad_out=None) == bad
+    assert backward(reg=float("nan")) == bad
+    assert backward(grad_w=ok + 4) == bad
+    assert backward(ws_bytes=16) == short
+    assert backward(shape=s0) == binding.BEAM_OK
+    assert backward(shape=beam.make_shape(4, 256, 8, 9, 512, beam.BEAM_F32)) == bad   # K > N
+
+
 def test_product_package_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2605_14438_amd")
     for dirpath, _, files in os.walk(pkg):

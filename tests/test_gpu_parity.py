@@ -297,6 +297,12 @@ def _check_forward(cfg, d, res, ref, token_subset=None):
 
 FWD_CASES = [
     CFG["tiny"], CFG["tiny"].with_(T=1), CFG["tiny"].with_(T=130, keep=1.0), SMALL_BF16, ODD_BF16,
+    # the envelope's corners: most experts (N = 256, 16 slots), K = N (softmax over all
+    # experts, every expert a candidate for every token), K = 64 slots
+    synth.LayerConfig("n256", 10, T=70, H=256, N=256, K=16, I=128, dtype="bf16", keep=0.3),
+    synth.LayerConfig("k_eq_n", 11, T=40, H=256, N=64, K=64, I=128, dtype="bf16", keep=0.2),
+    synth.LayerConfig("n256_prefill", 12, T=1200, H=256, N=256, K=16, I=128, dtype="bf16",
+                      keep=0.5, router_skew="zipf"),
     SMALL_BF16.with_(keep=0.0), SMALL_BF16.with_(keep=1.0),
     PREFILL_SMALL, PREFILL_SMALL.with_(T=1100, keep=1.0), PREFILL_SMALL.with_(T=2200, keep=0.7),
 ]
