@@ -178,7 +178,7 @@ FFN_CASES = [
     SMALL_BF16.with_(T=200, keep=1.0),               # streaming with > 16 rows per expert
     PREFILL_SMALL,                                   # tiled grouped GEMM, ragged tiles
     PREFILL_SMALL.with_(T=1100, keep=1.0),
-    PREFILL_SMALL.with_(T=2200, keep=0.7),           # 256-row tiles (T*K >= 512*N)
+    PREFILL_SMALL.with_(T=2200, keep=0.7),           # several row tiles per expert
 ]
 
 
