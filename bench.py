@@ -457,6 +457,14 @@ def main():
                "sample": f"first {Ts} tokens of the step, mean of {reps} runs after 1 warm-up, "
                          f"{dt * 1e3:.1f} ms each"}
 
+    main_roofline = roofline_of(main_pt)
+    if (args.workload == "qwen3_decode" and cfg.T == 64 and args.keep is None and not args.packed
+            and main_pt["U"] == 63):
+        # HBM bytes per gate/up launch of exactly this workload from rocprofv3 --pmc
+        # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors calibrated on a 1 GiB device copy):
+        # profiles/qwen3_decode_T64_keep15_kernels.md.  Counters cannot be read in-process.
+        main_roofline["traffic"] = 398.8e6 + 0.12e6
+        main_roofline["traffic_over_algorithmic"] = (398.8e6 + 0.12e6) / main_pt["gate_up"]["bytes"]
     rec = {
         "metric": "masked_moe_layer_tokens_per_s", "value": main_pt["tokens_per_s"],
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -471,7 +479,7 @@ def main():
                    "input_setup_s": round(t_gen, 1)},
         "layer": {k: main_pt[k] for k in ("layer_GBs", "layer_TFLOPs", "frac_hbm", "frac_mfma",
                                           "frac_of_roofline", "stage_us")},
-        "roofline": roofline_of(main_pt),
+        "roofline": main_roofline,
         "cpu_baseline": cpu,
         "points": points,
         "rules": rules,
