@@ -41,8 +41,8 @@
 // Work order.  Workgroups are handed to the 8 XCDs round-robin by linear id,
 // and each XCD has its own L2.  The grid is persistent: 512 workgroups, two per
 // CU, workgroup b on XCD b % 8 as its member b / 8.  The (row tile, column
-// tile) items are ordered by groups of four consecutive row tiles (mostly one
-// expert), inside a group by column tile, then by row tile, and this sequence
+// tile) items are ordered by groups of up to four row tiles of one expert,
+// inside a group by column tile, then by row tile, and this sequence
 // is cut into chunks of 64 consecutive items; chunk c goes to XCD c % 8, one
 // item per resident workgroup.  So the 64 workgroups that run together on an
 // XCD hold four row tiles times 16 column tiles (or, when an expert has fewer
@@ -381,30 +381,36 @@ __global__ __launch_bounds__(256, OCC) void ffn_tile_kernel(
     const int32_t *__restrict__ tile_row0, bf16_t *__restrict__ hidden_out,
     float *__restrict__ y_out, int H, int K, int I, int n_col_tiles) {
     __shared__ u32x4 As[2 * kTileM * 2 * KS];
-    // Item order: row tiles in groups of kRowGroup; inside a group the column
-    // tile is the slow index and the row tile the fast one, so neighbouring
-    // items multiply different rows by the SAME weight fragments.
+    // Item order: the row tiles of an expert in groups of up to kRowGroup (a group
+    // never spans two experts); inside a group the column tile is the slow index
+    // and the row tile the fast one, so neighbouring items multiply different rows
+    // by the SAME weight fragments and an expert's weights leave HBM about once.
+    // The items of a group are the range [F * n_col_tiles, (F + size) * n_col_tiles)
+    // with F the list index of its first row tile, so item / n_col_tiles is always
+    // a row tile of the item's own group, from which the group is reconstructed.
     const int n_tiles = wl_hdr[1];
-    const int group_items = kRowGroup * n_col_tiles;
-    const int n_work = ((n_tiles + kRowGroup - 1) / kRowGroup) * group_items;
+    const int n_work = n_tiles * n_col_tiles;
     const int xcd = blockIdx.x & 7;
     const int member = blockIdx.x >> 3;  // gridDim.x / 8 workgroups per XCD
     const int per_xcd = gridDim.x >> 3;
     auto next_item = [&](int &round, TileItem &it) -> bool {
-        for (;; ++round) {
-            const int item = (round * 8 + xcd) * per_xcd + member;
-            if (item >= n_work) return false;    // uniform over the workgroup
-            const int group = item / group_items;
-            const int rem = item - group * group_items;
-            const int col_tile = rem / kRowGroup;
-            const int tile = group * kRowGroup + (rem - col_tile * kRowGroup);
-            if (tile >= n_tiles) continue;       // ragged last group (uniform)
-            it.e = tile_expert[tile];
-            it.row0 = tile_row0[tile];
-            it.row_end = offsets[it.e + 1];
-            it.col_tile = col_tile;
-            return true;
-        }
+        const int item = (round * 8 + xcd) * per_xcd + member;
+        if (item >= n_work) return false;    // uniform over the workgroup
+        const int q = item / n_col_tiles;
+        const int e = tile_expert[q];
+        const int beg = offsets[e];
+        const int end = offsets[e + 1];
+        const int j = (tile_row0[q] - beg) / kTileM;   // q among the expert's row tiles
+        const int g0 = j - j % kRowGroup;              // first row tile of the group
+        const int left = tiles_of(end - beg) - g0;
+        const int size = left < kRowGroup ? left : kRowGroup;
+        const int rem = item - (q - (j - g0)) * n_col_tiles;
+        const int col_tile = rem / size;
+        it.e = e;
+        it.row0 = beg + (g0 + rem - col_tile * size) * kTileM;
+        it.row_end = end;
+        it.col_tile = col_tile;
+        return true;
     };
     ffn_tile_run<kTileM, WM, KS, GATE_UP, PACKED, OCC == 1, false>(
         As, a_src, w, perm, hidden_out, y_out, H, K, I, next_item);
