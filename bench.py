@@ -107,7 +107,8 @@ def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp, packed
     # durations are the stage figures minus a sixth of that excess; rocprofv3's kernel trace
     # of the same command agrees with the corrected figure to a fraction of a microsecond.
     # (Not applied on the three-kernel path of tiny batches, where stages are empty.)
-    tiny = cfg.T * (cfg.K + S) <= 24 and not packed
+    tiny = (cfg.T * (cfg.K + S) <= 24 and cfg.dtype == "bf16" and cfg.H % 512 == 0
+            and cfg.I % 128 == 0)
     bubble = 0.0 if tiny else max(0.0, (sum(stage_us.values()) - ms * 1e3) / len(stage_us))
     kernel_us = {n: max(v - bubble, 0.0) for n, v in stage_us.items()}
 

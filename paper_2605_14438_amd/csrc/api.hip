@@ -92,8 +92,11 @@ WorkList work_list(void *base, const beam_shape &s, int max_tiles) {
 // Row count per expert above which the tiled GEMM beats re-streaming the
 // weights once per 16 rows (worst case, every Top-K pair kept).
 static bool use_tiled(const beam_shape &s) {
-    if (s.weight_layout == BEAM_WEIGHTS_PACKED) return true;  // the only consumer of that layout
-    return tiled_ffn_supported(s) && (long)s.T * s.K > 32L * s.N;
+    if (!tiled_ffn_supported(s)) return false;
+    if ((long)s.T * s.K > 32L * s.N) return true;
+    // few rows per expert: the streaming kernels, which read either layout (packed needs
+    // their shape envelope; outside it the tiled kernel is the only reader of that layout)
+    return s.weight_layout == BEAM_WEIGHTS_PACKED && !stream_ffn_supported(s);
 }
 
 hipError_t launch_gate_up(const beam_shape &s, const void *x, const void *w_gate_up,

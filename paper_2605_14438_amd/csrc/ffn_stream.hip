@@ -445,6 +445,362 @@ __global__ __launch_bounds__(256) void down_stream_kernel(
         down_rows<FT, 1>(hidden, wp, row_beg, row_end, y_pairs, H, I, c0);
 }
 
+// ---------------------------------------------------------------------------
+// The same two streaming kernels for BEAM_WEIGHTS_PACKED (a server keeps one
+// copy of the weights, packed for prefill, and decodes from it too).  The packed
+// order is the A operand of v_mfma_f32_32x32x16_bf16: one fully coalesced 1 KiB
+// load per 32 weight rows x 16 reduction indices.
+//   A/B lane l: row/column l & 31, k = 8*(l >> 5)..+7
+//   D register r of lane l: feature 8*(r >> 2) + 4*(l >> 5) + (r & 3),
+//                           activation row l & 31
+// so up to 32 activation rows share a pass and a lane ends up with runs of four
+// consecutive features of its row.
+// ---------------------------------------------------------------------------
+typedef uint32_t u32x4s __attribute__((ext_vector_type(4)));
+// MFMA k-steps (16 indices each) per pipeline chunk: 8 for the down kernel; 4 for
+// gate/up, whose two weight streams would otherwise take every register and
+// leave one workgroup per CU
+constexpr int kPackedChunk = 8;
+constexpr int kGateUpPackedChunk = 4;
+
+// hidden rows [row_beg, row_end) x the 32 features of block q of expert e; the 4
+// wavefronts split the reduction over H.  red: LDS, 3 * 32 * 64 floats.
+template <int CH, typename TokenOf>
+__device__ __forceinline__ void gate_up_rows_packed(const bf16_t *__restrict__ x,
+                                                    const bf16_t *__restrict__ w_gate_up, int e,
+                                                    int row_beg, int row_end, TokenOf token_of,
+                                                    bf16_t *__restrict__ hidden, int H, int I,
+                                                    int q, float *red) {
+    const int lane = threadIdx.x & 63;
+    const int ks4 = threadIdx.x >> 6;
+    const int l32 = lane & 31;
+    const int kh = lane >> 5;
+    const int ksteps = H >> 4;
+    const int kper = ksteps >> 2;  // k-steps of this wavefront
+    const int k0 = ks4 * kper;
+    // blocks 2q (gate) and 2q + 1 (up) of this expert's 2I/32 row blocks
+    const bf16_t *gp =
+        w_gate_up + (((size_t)e * ((2 * I) >> 5) + 2 * q) * ksteps + k0) * 512 + lane * 8;
+    const bf16_t *up = gp + (size_t)ksteps * 512;
+
+    for (int row0 = row_beg; row0 < row_end; row0 += 32) {
+        int row = row0 + l32;
+        row = row < row_end ? row : row_end - 1;
+        const bf16_t *xp = x + (size_t)token_of(row) * H + k0 * 16 + kh * 8;
+        f32x16 ag, au;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ag[r] = au[r] = 0.0f;
+        u32x4s wg[2][CH], wu[2][CH], xv[2][CH];
+        auto load = [&](int b, int k) {
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                wg[b][j] = *(const u32x4s *)(gp + (size_t)(k + j) * 512);
+                wu[b][j] = *(const u32x4s *)(up + (size_t)(k + j) * 512);
+            }
+#pragma unroll
+            for (int j = 0; j < CH; ++j) xv[b][j] = *(const u32x4s *)(xp + (k + j) * 16);
+        };
+        auto mma = [&](int b) {
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                ag = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wg[b][j]),
+                                                             __builtin_bit_cast(bf16x8, xv[b][j]),
+                                                             ag, 0, 0, 0);
+                au = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wu[b][j]),
+                                                             __builtin_bit_cast(bf16x8, xv[b][j]),
+                                                             au, 0, 0, 0);
+            }
+        };
+        // two chunks in flight, steady state without conditionals (see gate_up_rows)
+        load(0, 0);
+        int k = 0;
+        for (; k + 2 * CH < kper; k += 2 * CH) {
+            load(1, k + CH);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(0);
+            __builtin_amdgcn_sched_barrier(0);
+            load(0, k + 2 * CH);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (k + CH < kper) {
+            load(1, k + CH);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(0);
+            mma(1);
+        } else {
+            mma(0);
+        }
+        if (ks4 > 0) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                red[((ks4 - 1) * 32 + r) * 64 + lane] = ag[r];
+                red[((ks4 - 1) * 32 + 16 + r) * 64 + lane] = au[r];
+            }
+        }
+        __syncthreads();
+        if (ks4 == 0) {
+#pragma unroll
+            for (int s = 0; s < 3; ++s)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    ag[r] += red[(s * 32 + r) * 64 + lane];
+                    au[r] += red[(s * 32 + 16 + r) * 64 + lane];
+                }
+            if (row0 + l32 < row_end) {
+                bf16_t *orow = hidden + (size_t)(row0 + l32) * I + q * 32 + kh * 4;
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg) {
+                    const int r = rg * 4;
+                    const uint32_t lo = (uint32_t)f32_to_bf16(silu(ag[r]) * au[r]) |
+                                        ((uint32_t)f32_to_bf16(silu(ag[r + 1]) * au[r + 1]) << 16);
+                    const uint32_t hi = (uint32_t)f32_to_bf16(silu(ag[r + 2]) * au[r + 2]) |
+                                        ((uint32_t)f32_to_bf16(silu(ag[r + 3]) * au[r + 3]) << 16);
+                    *(uint2 *)(orow + rg * 8) = make_uint2(lo, hi);
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// grid (I/32, max active experts)
+__global__ __launch_bounds__(256, 2) void gate_up_stream_packed_kernel(
+    const bf16_t *__restrict__ x, const bf16_t *__restrict__ w_gate_up,
+    const int32_t *__restrict__ perm, WorkList wl, bf16_t *__restrict__ hidden, int H, int K,
+    int I) {
+    const int u = blockIdx.y;
+    const int n_active = wl.hdr[0];
+    const int e = wl.active[u];
+    const int row_beg = wl.active_beg[u];
+    const int row_end = wl.active_end[u];
+    if (u >= n_active) return;
+    __shared__ float red[3 * 32 * 64];
+    gate_up_rows_packed<kGateUpPackedChunk>(x, w_gate_up, e, row_beg, row_end,
+                                            [&](int row) { return perm[row] / K; }, hidden, H, I,
+                                            blockIdx.x, red);
+}
+
+// y rows [row_beg, row_end) x the 32 output features of row block rb of expert e;
+// one wavefront runs the whole reduction over I.
+__device__ __forceinline__ void down_rows_packed(const bf16_t *__restrict__ hidden,
+                                                 const bf16_t *__restrict__ w_down, int e, int rb,
+                                                 int row_beg, int row_end,
+                                                 float *__restrict__ y_pairs, int H, int I) {
+    constexpr int CH = kPackedChunk;
+    const int lane = threadIdx.x & 63;
+    const int l32 = lane & 31;
+    const int kh = lane >> 5;
+    const int ksteps = I >> 4;
+    const bf16_t *wp = w_down + (((size_t)e * (H >> 5) + rb) * ksteps) * 512 + lane * 8;
+    for (int row0 = row_beg; row0 < row_end; row0 += 32) {
+        int row = row0 + l32;
+        row = row < row_end ? row : row_end - 1;
+        const bf16_t *hp = hidden + (size_t)row * I + kh * 8;
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+        u32x4s w[2][CH], hv[2][CH];
+        auto load = [&](int b, int k) {
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                w[b][j] = *(const u32x4s *)(wp + (size_t)(k + j) * 512);
+                hv[b][j] = *(const u32x4s *)(hp + (k + j) * 16);
+            }
+        };
+        auto mma = [&](int b) {
+#pragma unroll
+            for (int j = 0; j < CH; ++j)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w[b][j]),
+                                                              __builtin_bit_cast(bf16x8, hv[b][j]),
+                                                              acc, 0, 0, 0);
+        };
+        load(0, 0);
+        int k = 0;
+        for (; k + 2 * CH < ksteps; k += 2 * CH) {
+            load(1, k + CH);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(0);
+            __builtin_amdgcn_sched_barrier(0);
+            load(0, k + 2 * CH);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (k + CH < ksteps) {
+            load(1, k + CH);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(0);
+            mma(1);
+        } else {
+            mma(0);
+        }
+        if (row0 + l32 < row_end) {
+            float *orow = y_pairs + (size_t)(row0 + l32) * H + rb * 32 + kh * 4;
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg)
+                *(float4 *)(orow + rg * 8) = make_float4(acc[rg * 4], acc[rg * 4 + 1],
+                                                         acc[rg * 4 + 2], acc[rg * 4 + 3]);
+        }
+    }
+}
+
+// grid (H/128, max active experts): each wavefront one block of 32 output features
+__global__ __launch_bounds__(256) void down_stream_packed_kernel(
+    const bf16_t *__restrict__ hidden, const bf16_t *__restrict__ w_down, WorkList wl,
+    float *__restrict__ y_pairs, int H, int I) {
+    const int u = blockIdx.y;
+    const int n_active = wl.hdr[0];
+    const int e = wl.active[u];
+    const int row_beg = wl.active_beg[u];
+    const int row_end = wl.active_end[u];
+    if (u >= n_active) return;
+    const int rb = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (rb * 32 >= H) return;
+    down_rows_packed(hidden, w_down, e, rb, row_beg, row_end, y_pairs, H, I);
+}
+
+// The tiny-batch kernels (see gate_up_slot_kernel) for packed weights.
+// grid (I/32, T * slots)
+template <int RULE>
+__global__ __launch_bounds__(256, 2) void gate_up_slot_packed_kernel(
+    const bf16_t *__restrict__ x, const bf16_t *__restrict__ w_gate_up,
+    const float *__restrict__ router_logits, const float *__restrict__ mask_logits,
+    const float *__restrict__ g_shared, float param, bf16_t *__restrict__ hidden, int H, int N,
+    int K, int S, int I) {
+    __shared__ float red[3 * 32 * 64];
+    __shared__ int32_t ids_s[64], masked_s[64];
+    __shared__ float w_s[64];
+    const int slots = K + S;
+    const int f = blockIdx.y;
+    const int t = f / slots;
+    if (threadIdx.x < 64)
+        wave_route_token<RULE>(router_logits + (size_t)t * N, mask_logits + (size_t)t * N, nullptr,
+                               nullptr, N, K, S, (S > 0 && g_shared) ? g_shared[t] : 1.0f, param,
+                               ids_s, w_s, masked_s);
+    __syncthreads();
+    const int e = masked_s[f - t * slots];
+    if (e < 0) return;  // uniform over the workgroup
+    gate_up_rows_packed<kGateUpPackedChunk>(x, w_gate_up, e, f, f + 1, [&](int) { return t; },
+                                            hidden, H, I, blockIdx.x, red);
+}
+
+// grid (H/32, T): a workgroup owns one block of 32 output features of one token;
+// otherwise as down_combine_token_kernel.  Every column of the MFMA result is the
+// same hidden row, so lanes 0 and 32 hold the 32 features between them.
+template <int RULE>
+__global__ __launch_bounds__(256) void down_combine_token_packed_kernel(
+    const bf16_t *__restrict__ hidden, const bf16_t *__restrict__ w_down,
+    const float *__restrict__ router_logits, const float *__restrict__ mask_logits,
+    const float *__restrict__ g_shared, float param, const bf16_t *__restrict__ residual,
+    bf16_t *__restrict__ out, int32_t *__restrict__ topk_ids_opt, float *__restrict__ topk_w_opt,
+    int32_t *__restrict__ masked_ids_opt, int32_t *__restrict__ num_pairs_opt, int H, int N, int K,
+    int S, int I) {
+    constexpr int CH = kPackedChunk;
+    __shared__ int32_t ids_s[4][64], masked_s[4][64];
+    __shared__ float w_s[4][64];
+    __shared__ float y_s[64][2][16];  // [kept slot ordinal][lane half][register]
+    const int slots = K + S;
+    const int t = blockIdx.y;
+    const int rb = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int l32 = lane & 31;
+    const int kh = lane >> 5;
+    wave_route_token<RULE>(router_logits + (size_t)t * N, mask_logits + (size_t)t * N, nullptr,
+                           nullptr, N, K, S, (S > 0 && g_shared) ? g_shared[t] : 1.0f, param,
+                           ids_s[wave], w_s[wave], masked_s[wave]);
+    __builtin_amdgcn_wave_barrier();  // a wavefront reads back only its own copy
+    const bool in = lane < slots;
+    const uint64_t kept = __ballot(in && masked_s[wave][in ? lane : 0] >= 0);
+    if (blockIdx.x == 0 && wave == 0) {
+        const size_t f = (size_t)t * slots + lane;
+        if (in && topk_ids_opt) topk_ids_opt[f] = ids_s[0][lane];
+        if (in && topk_w_opt) topk_w_opt[f] = w_s[0][lane];
+        if (in && masked_ids_opt) masked_ids_opt[f] = masked_s[0][lane];
+        // the logits kernel of this call has zeroed the counter
+        if (num_pairs_opt && lane == 0) atomicAdd(num_pairs_opt, __popcll(kept));
+    }
+    const int ksteps = I >> 4;
+    int ord = 0;
+    for (uint64_t m = kept; m; m &= m - 1, ++ord) {
+        if ((ord & 3) != wave) continue;  // wave-uniform
+        const int k = __builtin_ctzll(m);
+        const int e = masked_s[wave][k];
+        const bf16_t *hp = hidden + ((size_t)t * slots + k) * I + kh * 8;
+        const bf16_t *wp = w_down + (((size_t)e * (H >> 5) + rb) * ksteps) * 512 + lane * 8;
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+        u32x4s w[2][CH], hv[2][CH];
+        auto load = [&](int b, int kk) {
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                w[b][j] = *(const u32x4s *)(wp + (size_t)(kk + j) * 512);
+                hv[b][j] = *(const u32x4s *)(hp + (kk + j) * 16);
+            }
+        };
+        auto mma = [&](int b) {
+#pragma unroll
+            for (int j = 0; j < CH; ++j)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w[b][j]),
+                                                              __builtin_bit_cast(bf16x8, hv[b][j]),
+                                                              acc, 0, 0, 0);
+        };
+        load(0, 0);
+        int kk = 0;
+        for (; kk + 2 * CH < ksteps; kk += 2 * CH) {
+            load(1, kk + CH);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(0);
+            __builtin_amdgcn_sched_barrier(0);
+            load(0, kk + 2 * CH);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (kk + CH < ksteps) {
+            load(1, kk + CH);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(0);
+            mma(1);
+        } else {
+            mma(0);
+        }
+        if (l32 == 0) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) y_s[ord][kh][r] = acc[r];
+        }
+    }
+    __syncthreads();
+    if (wave == 0 && l32 == 0) {
+        // register 4*rg + i of lane half kh is feature 8*rg + 4*kh + i of the block
+        const size_t base = (size_t)t * H + rb * 32 + kh * 4;
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+            float tot[4] = {0.f, 0.f, 0.f, 0.f};
+            if (residual) {
+                const uint2 q = *(const uint2 *)(residual + base + rg * 8);
+                tot[0] = __uint_as_float(q.x << 16);
+                tot[1] = __uint_as_float(q.x & 0xffff0000u);
+                tot[2] = __uint_as_float(q.y << 16);
+                tot[3] = __uint_as_float(q.y & 0xffff0000u);
+            }
+            int j = 0;
+            for (uint64_t m = kept; m; m &= m - 1, ++j) {
+                const float gk = w_s[0][__builtin_ctzll(m)];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) tot[i] = fmaf(gk, y_s[j][kh][rg * 4 + i], tot[i]);
+            }
+            uint2 q;
+            q.x = (uint32_t)f32_to_bf16(tot[0]) | ((uint32_t)f32_to_bf16(tot[1]) << 16);
+            q.y = (uint32_t)f32_to_bf16(tot[2]) | ((uint32_t)f32_to_bf16(tot[3]) << 16);
+            *(uint2 *)(out + base + rg * 8) = q;
+        }
+    }
+}
+
 bool stream_ffn_supported(const beam_shape &s) {
     return s.dtype == BEAM_BF16 && s.H % 512 == 0 && s.I % 128 == 0;
 }
@@ -457,10 +813,15 @@ static int max_active(const beam_shape &s) {
 hipError_t launch_gate_up_stream(const beam_shape &s, const void *x, const void *w_gate_up,
                                  const int32_t *offsets, const int32_t *perm, const WorkList &wl,
                                  void *hidden, hipStream_t st) {
-    dim3 grid(s.I / 16, max_active(s));
     (void)offsets;
-    gate_up_stream_kernel<<<grid, 256, 0, st>>>((const bf16_t *)x, (const bf16_t *)w_gate_up, perm,
-                                                wl, (bf16_t *)hidden, s.H, s.K, s.I);
+    if (s.weight_layout == BEAM_WEIGHTS_PACKED)
+        gate_up_stream_packed_kernel<<<dim3(s.I / 32, max_active(s)), 256, 0, st>>>(
+            (const bf16_t *)x, (const bf16_t *)w_gate_up, perm, wl, (bf16_t *)hidden, s.H, s.K,
+            s.I);
+    else
+        gate_up_stream_kernel<<<dim3(s.I / 16, max_active(s)), 256, 0, st>>>(
+            (const bf16_t *)x, (const bf16_t *)w_gate_up, perm, wl, (bf16_t *)hidden, s.H, s.K,
+            s.I);
     return hipGetLastError();
 }
 
@@ -468,10 +829,14 @@ hipError_t launch_down_stream(const beam_shape &s, const void *hidden, const voi
                               const int32_t *offsets, const WorkList &wl, float *y_pairs,
                               hipStream_t st) {
     constexpr int FT = 2;
-    dim3 grid((s.H + 64 * FT - 1) / (64 * FT), max_active(s));
     (void)offsets;
-    down_stream_kernel<FT><<<grid, 256, 0, st>>>((const bf16_t *)hidden, (const bf16_t *)w_down, wl,
-                                                 y_pairs, s.H, s.I);
+    if (s.weight_layout == BEAM_WEIGHTS_PACKED)
+        down_stream_packed_kernel<<<dim3(s.H / 128, max_active(s)), 256, 0, st>>>(
+            (const bf16_t *)hidden, (const bf16_t *)w_down, wl, y_pairs, s.H, s.I);
+    else
+        down_stream_kernel<FT><<<dim3((s.H + 64 * FT - 1) / (64 * FT), max_active(s)), 256, 0,
+                                 st>>>((const bf16_t *)hidden, (const bf16_t *)w_down, wl, y_pairs,
+                                       s.H, s.I);
     return hipGetLastError();
 }
 
@@ -482,20 +847,22 @@ bool tiny_decode_supported(const beam_shape &s, int S) {
     // 28.9 us at T = 1, 27.4 vs 30.6 at T = 3, level at T = 4, slower from there on, because
     // every slot's workgroups pay for a routing pass before most of them find their slot
     // masked.
-    return stream_ffn_supported(s) && s.weight_layout == BEAM_WEIGHTS_PLAIN &&
-           (long)s.T * (s.K + S) <= kTinySlots && s.K + S <= 64;
+    return stream_ffn_supported(s) && (long)s.T * (s.K + S) <= kTinySlots && s.K + S <= 64;
 }
 
 hipError_t launch_tiny_gate_up(const beam_shape &s, const RouteOpts &opt, const void *x,
                                const float *router_logits, const float *mask_logits,
                                const void *w_gate_up, void *hidden, hipStream_t st) {
-    const dim3 grid(s.I / 16, s.T * (s.K + opt.S));
-#define BEAM_TINY(RULE)                                                                         \
-    gate_up_slot_kernel<RULE><<<grid, 256, 0, st>>>(                                            \
-        (const bf16_t *)x, (const bf16_t *)w_gate_up, router_logits, mask_logits, opt.g_shared, \
-        opt.param, (bf16_t *)hidden, s.H, s.N, s.K, opt.S, s.I)
-    if (opt.rule == kRuleCumProb) BEAM_TINY(kRuleCumProb);
-    else BEAM_TINY(kRuleMask);
+    const bool packed = s.weight_layout == BEAM_WEIGHTS_PACKED;
+    const dim3 grid(s.I / (packed ? 32 : 16), s.T * (s.K + opt.S));
+#define BEAM_TINY(KERNEL, RULE)                                                                 \
+    KERNEL<RULE><<<grid, 256, 0, st>>>((const bf16_t *)x, (const bf16_t *)w_gate_up,            \
+                                       router_logits, mask_logits, opt.g_shared, opt.param,     \
+                                       (bf16_t *)hidden, s.H, s.N, s.K, opt.S, s.I)
+    if (packed && opt.rule == kRuleCumProb) BEAM_TINY(gate_up_slot_packed_kernel, kRuleCumProb);
+    else if (packed) BEAM_TINY(gate_up_slot_packed_kernel, kRuleMask);
+    else if (opt.rule == kRuleCumProb) BEAM_TINY(gate_up_slot_kernel, kRuleCumProb);
+    else BEAM_TINY(gate_up_slot_kernel, kRuleMask);
 #undef BEAM_TINY
     return hipGetLastError();
 }
@@ -506,16 +873,22 @@ hipError_t launch_tiny_down_combine(const beam_shape &s, const RouteOpts &opt,
                                     void *out, int32_t *topk_ids_opt, float *topk_w_opt,
                                     int32_t *masked_ids_opt, int32_t *num_pairs_opt,
                                     hipStream_t st) {
-    constexpr int FT = 2;
-    const dim3 grid((s.H + 16 * FT - 1) / (16 * FT), s.T);
-#define BEAM_TINY(RULE)                                                                         \
-    down_combine_token_kernel<FT, RULE><<<grid, 256, 0, st>>>(                                  \
-        (const bf16_t *)hidden, (const bf16_t *)w_down, router_logits, mask_logits,             \
-        opt.g_shared, opt.param, (const bf16_t *)residual, (bf16_t *)out, topk_ids_opt,         \
-        topk_w_opt, masked_ids_opt, num_pairs_opt, s.H, s.N, s.K, opt.S, s.I)
-    if (opt.rule == kRuleCumProb) BEAM_TINY(kRuleCumProb);
-    else BEAM_TINY(kRuleMask);
-#undef BEAM_TINY
+    constexpr int FT = 2;  // plain: 16 * FT = 32 features per workgroup, as one packed block
+    const dim3 grid(s.H / 32, s.T);
+#define BEAM_TINY_ARGS                                                                          \
+    (const bf16_t *)hidden, (const bf16_t *)w_down, router_logits, mask_logits, opt.g_shared,   \
+        opt.param, (const bf16_t *)residual, (bf16_t *)out, topk_ids_opt, topk_w_opt,           \
+        masked_ids_opt, num_pairs_opt, s.H, s.N, s.K, opt.S, s.I
+    const bool packed = s.weight_layout == BEAM_WEIGHTS_PACKED;
+    if (packed && opt.rule == kRuleCumProb)
+        down_combine_token_packed_kernel<kRuleCumProb><<<grid, 256, 0, st>>>(BEAM_TINY_ARGS);
+    else if (packed)
+        down_combine_token_packed_kernel<kRuleMask><<<grid, 256, 0, st>>>(BEAM_TINY_ARGS);
+    else if (opt.rule == kRuleCumProb)
+        down_combine_token_kernel<FT, kRuleCumProb><<<grid, 256, 0, st>>>(BEAM_TINY_ARGS);
+    else
+        down_combine_token_kernel<FT, kRuleMask><<<grid, 256, 0, st>>>(BEAM_TINY_ARGS);
+#undef BEAM_TINY_ARGS
     return hipGetLastError();
 }
 

@@ -48,11 +48,12 @@ def make_tie_free(cfg, sweep: int = 0, with_experts: bool = True, max_rounds: in
     return d
 
 
-def forward(cfg, g, T=None, packed=False):
+def forward(cfg, g, T=None, packed=False, prepacked=False):
     """beam_moe_forward with all optional outputs; returns host arrays.  With
-    packed=True the expert weights are first repacked by beam_pack_weights."""
+    packed=True the expert weights are first repacked by beam_pack_weights; with
+    prepacked=True they already are."""
     T = cfg.T if T is None else T
-    s = shape_of(cfg, T, packed=packed)
+    s = shape_of(cfg, T, packed=packed or prepacked)
     if packed:
         pg, pd = pack_weights(cfg, g["w_gate_up"], g["w_down"])
         g = {**g, "w_gate_up": pg, "w_down": pd}

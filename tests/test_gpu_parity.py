@@ -753,9 +753,9 @@ def test_rule_argument_checks():
 # ---------------------------------------------------------------------------
 # the three-kernel path of the fused entry points for T * slots <= 24
 # ---------------------------------------------------------------------------
-def _staged(cfg, g):
+def _staged(cfg, g, packed=False):
     """The layer through the four staged entry points (the six-kernel path)."""
-    s = hp.shape_of(cfg)
+    s = hp.shape_of(cfg, packed=packed)
     ws, nb = hp.workspace(s)
     T, K, N = cfg.T, cfg.K, cfg.N
     ids = torch.empty((T, K), dtype=torch.int32, device="cuda")
@@ -778,9 +778,11 @@ def _staged(cfg, g):
     return out, mids.cpu().numpy(), int(P.item())
 
 
-@pytest.mark.parametrize("T,keep", [(1, 0.15), (1, 1.0), (2, 0.5), (3, 0.15), (3, 1.0), (3, 0.0),
-                                    (4, 0.5)])
-def test_tiny_batch_path_equals_staged_path_bit_for_bit(T, keep):
+@pytest.mark.parametrize("T,keep,packed", [(1, 0.15, False), (1, 1.0, False), (2, 0.5, False),
+                                           (3, 0.15, False), (3, 1.0, False), (3, 0.0, False),
+                                           (4, 0.5, False), (1, 1.0, True), (3, 0.3, True),
+                                           (4, 0.5, True)])
+def test_tiny_batch_path_equals_staged_path_bit_for_bit(T, keep, packed):
     """Same reductions in the same order: the three-kernel path (T <= 3 here) must
     reproduce the six-kernel path exactly, and both the oracle within the output
     bound.  T = 4 is the first size back on the six-kernel path."""
@@ -788,15 +790,18 @@ def test_tiny_batch_path_equals_staged_path_bit_for_bit(T, keep):
     _log(f"tiny path {cfg}")
     d = hp.make_tie_free(cfg)
     g = hp.upload(cfg, d)
-    res = hp.forward(cfg, g)                              # all optional outputs requested
-    out_staged, mids_staged, P_staged = _staged(cfg, g)
+    if packed:      # one packed copy of the weights serves both paths
+        pg, pd = hp.pack_weights(cfg, g["w_gate_up"], g["w_down"])
+        g = {**g, "w_gate_up": pg, "w_down": pd}
+    res = hp.forward(cfg, g, prepacked=packed)            # all optional outputs requested
+    out_staged, mids_staged, P_staged = _staged(cfg, g, packed=packed)
     assert torch.equal(res["out_raw"], out_staged)
     assert np.array_equal(res["masked_ids"], mids_staged) and res["num_pairs"] == P_staged
     ref = oracle.moe_forward(d["x"], d["w_router"], d["b_router"], d["w_mask"], d["b_mask"],
                              d["w_gate_up"], d["w_down"], cfg.K)
     _check_forward(cfg, d, res, ref)
     # without any optional output (what a serving loop calls)
-    s = hp.shape_of(cfg)
+    s = hp.shape_of(cfg, packed=packed)
     ws, nb = hp.workspace(s)
     out2 = hp.out_tensor(cfg)
     beam.beam_moe_forward(s, g["x"], g["w_router"], g["b_router"], g["w_mask"], g["b_mask"],
