@@ -93,6 +93,9 @@ WorkList work_list(void *base, const beam_shape &s, int max_tiles) {
 // weights once per 16 rows (worst case, every Top-K pair kept).
 static bool use_tiled(const beam_shape &s) {
     if (!tiled_ffn_supported(s)) return false;
+    // Worst-case rows per expert (every pair kept) above which the tiled GEMM takes over.
+    // The host cannot know the keep rate: at 15 % kept the streaming kernels would still
+    // win up to about four times this size, at 100 % they already lose by half here.
     if ((long)s.T * s.K > 32L * s.N) return true;
     // few rows per expert: the streaming kernels, which read either layout (packed needs
     // their shape envelope; outside it the tiled kernel is the only reader of that layout)

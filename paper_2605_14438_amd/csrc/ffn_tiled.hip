@@ -525,7 +525,7 @@ __global__ __launch_bounds__(256, 2) void logits_tile_kernel(
 }
 
 bool logits_tiled_supported(const beam_shape &s) {
-    return s.dtype == BEAM_BF16 && s.T >= 1024 && s.H % 256 == 0 &&
+    return s.dtype == BEAM_BF16 && s.T > 512 && s.H % 256 == 0 &&
            (long)s.T * s.H < (1L << 32);
 }
 
