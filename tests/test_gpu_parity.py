@@ -919,3 +919,78 @@ def test_training_step_mask_router_backward(cfg):
     # reproducible: a second run gives the same bits
     _, _, grad_a2, grad_w2, _ = _train_step_gpu(cfg, d, g, dy, beta)
     assert np.array_equal(grad_a, grad_a2) and np.array_equal(grad_w, grad_w2)
+
+
+# ---------------------------------------------------------------------------
+# the largest batch the envelope admits: T * K just under 2^24 pairs
+# ---------------------------------------------------------------------------
+def test_maximum_pair_count_properties_and_sampled_parity():
+    """T*K = 2^24 - 8 pairs (narrow layer, so that it fits): 32-bit index arithmetic,
+    the multi-chunk grouping at its largest, the tiled path.  Checked by properties
+    that hold at any size plus the oracle on sampled tokens."""
+    cfg = synth.LayerConfig("max_pairs", 13, T=(1 << 21) - 1, H=256, N=16, K=8, I=128,
+                            dtype="bf16", keep=0.3, router_skew="zipf")
+    assert cfg.T * cfg.K < (1 << 24) <= (cfg.T + 1) * cfg.K
+    _log(f"max size {cfg}")
+    d = synth.make_layer(cfg)
+    g = hp.upload(cfg, d)
+    s = hp.shape_of(cfg)
+    ws, nb = hp.workspace(s)
+    T, K, N, H = cfg.T, cfg.K, cfg.N, cfg.H
+    i32 = dict(dtype=torch.int32, device="cuda")
+    ids, mids = torch.empty((T, K), **i32), torch.empty((T, K), **i32)
+    gw = torch.empty((T, K), dtype=torch.float32, device="cuda")
+    counts, offsets = torch.empty((N,), **i32), torch.empty((N + 1,), **i32)
+    perm, inv, P = torch.empty((T * K,), **i32), torch.empty((T * K,), **i32), torch.empty((1,), **i32)
+    st = hp.stream_ptr()
+    beam.beam_route_mask(s, g["x"], g["w_router"], g["b_router"], g["w_mask"], g["b_mask"], ids,
+                         gw, mids, None, None, ws, nb, st)
+    beam.beam_permute(s, mids, counts, offsets, perm, inv, P, ws, nb, st)
+    torch.cuda.synchronize()
+    # grouping invariants on the device (App. A.4), all 16.7 M pairs
+    flat = mids.reshape(-1).long()
+    kept = flat >= 0
+    n_kept = int(kept.sum().item())
+    assert int(P.item()) == n_kept == int(offsets[N].item())
+    assert torch.equal(counts.long(), torch.bincount(flat[kept], minlength=N))
+    assert torch.equal(offsets[1:].long(), torch.cumsum(counts.long(), 0))
+    pk = perm[:n_kept].long()
+    assert (perm[n_kept:] == -1).all()
+    experts_in_order = flat[pk]
+    assert (experts_in_order[1:] >= experts_in_order[:-1]).all()          # grouped by expert
+    same = experts_in_order[1:] == experts_in_order[:-1]
+    assert (pk[1:][same] > pk[:-1][same]).all()                          # stable inside an expert
+    assert torch.equal(inv.long()[pk], torch.arange(n_kept, device="cuda"))   # inverse, bijection
+    assert (inv[~kept] == -1).all()
+    # routing against the oracle on sampled tokens (first, last, random), guard band excluded
+    rng = np.random.default_rng(1)
+    sub = np.unique(np.concatenate([[0, 1, T - 2, T - 1], rng.choice(T, 4000, replace=False)]))
+    xs = d["x"][sub]
+    r = oracle.logits(xs, d["w_router"], d["b_router"])
+    a = oracle.logits(xs, d["w_mask"], d["b_mask"])
+    clear = oracle.decision_margin(r, a, K) >= hp.GUARD
+    assert clear.mean() > 0.9
+    ids_o, g_o, msk_o = oracle.route_mask(r, a, K)
+    sub_t = torch.from_numpy(sub).cuda()
+    assert np.array_equal(ids[sub_t].cpu().numpy()[clear], ids_o[clear])
+    assert np.array_equal(mids[sub_t].cpu().numpy()[clear], msk_o[clear])
+    np.testing.assert_allclose(gw[sub_t].cpu().numpy(), g_o, atol=2e-6, rtol=0)
+    del ids, gw, counts, offsets, perm, inv, flat, kept, pk, experts_in_order, same
+    # the fused layer: pair count and sampled output rows
+    out = hp.out_tensor(cfg)
+    mids2 = torch.empty((T, K), **i32)
+    npairs = torch.empty((1,), **i32)
+    beam.beam_moe_forward(s, g["x"], g["w_router"], g["b_router"], g["w_mask"], g["b_mask"],
+                          g["w_gate_up"], g["w_down"], out, None, None, mids2, npairs, ws, nb, st)
+    torch.cuda.synchronize()
+    assert torch.equal(mids2, mids) and int(npairs.item()) == n_kept
+    pick = sub[clear][:: max(1, int(clear.sum()) // 48)][:48]
+    pick = np.unique(np.concatenate([pick, sub[clear][-2:]]))
+    ref = oracle.moe_forward(d["x"][pick], d["w_router"], d["b_router"], d["w_mask"], d["b_mask"],
+                             d["w_gate_up"], d["w_down"], K)
+    got = out[torch.from_numpy(pick).cuda()].float().cpu().numpy().astype(np.float64)
+    literal, ratio = hp.output_error(got, ref["out"], cfg.dtype)
+    _log(f"  P={n_kept} of {T * K}; {pick.size} sampled rows max|err|/RMS={literal:.4f} "
+         f"worst/bound={ratio:.3f}")
+    assert ratio <= 1.0
+    assert torch.isfinite(out.float()).all()
