@@ -126,6 +126,11 @@ def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp, packed
     return {
         "workload": f"{cfg.name} T={T} keep={cfg.keep}", "T": T, "P": P, "U": U,
         "weights": "packed" if packed else "plain",
+        # 6 stages; the multi-chunk grouping is 4 launches, the tiled logits GEMM repacks the
+        # heads first, a gated shared expert adds one; tiny batches take the three-kernel path
+        "kernels_per_layer": (3 if tiny else 6 + (3 if T * (cfg.K + S) > 512 else 0) + (
+            1 if T > 512 and cfg.dtype == "bf16" and cfg.H % 256 == 0 else 0)) + (
+            1 if gate is not None else 0),
         "us_per_layer": ms * 1e3, "tokens_per_s": T / (ms * 1e-3), "stage_us": stage_us,
         "kernel_us": kernel_us,
         "layer_GBs": layer_bytes / (ms * 1e-3) / 1e9,
@@ -136,6 +141,39 @@ def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp, packed
         "gate_up": {"bytes": gate_up_bytes, "flops": gate_up_flops, "us": kernel_us["gate_up"]},
         "ms_per_step": ms,
     }
+
+
+def measure_ceilings(buf, torch, beam):
+    """What this GPU delivers on the two rooflines (library probe kernels timed with
+    events): a plain streaming read of `buf` and a bare bf16 MFMA loop."""
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    nbytes = buf.numel() * buf.element_size()
+
+    def timed(fn, reps):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    read = [0]
+
+    def stream():
+        read[0] = beam.beam_probe_stream_read(buf, nbytes, sink, st)[1]
+    flops = [0.0]
+
+    def mfma():
+        flops[0] = beam.beam_probe_mfma(20000, sink, st)[1]
+    t_s = timed(stream, 10)
+    t_m = timed(mfma, 3)
+    return {"stream_read_GBs": read[0] / t_s / 1e9, "stream_read_bytes": read[0],
+            "mfma_bf16_TFLOPs": flops[0] / t_m / 1e12,
+            "published": {"hbm_GBs": HBM_PEAK_GBS, "mfma_bf16_TFLOPs": MFMA_BF16_PEAK_TFLOPS}}
 
 
 def measure_training_step(cfg, g, wgu, wd, packed, steps, torch, beam, hp):
@@ -469,7 +507,11 @@ def main():
                "sample": f"first {Ts} tokens of the step, mean of {reps} runs after 1 warm-up, "
                          f"{dt * 1e3:.1f} ms each"}
 
+    ceilings = measure_ceilings(g["w_gate_up"], torch, beam)
     main_roofline = roofline_of(main_pt)
+    for rf in [main_roofline] + [p["roofline"] for p in points]:
+        rf["frac_of_measured_ceiling"] = rf["achieved"] / (
+            ceilings["stream_read_GBs"] if rf["bound"] == "hbm" else ceilings["mfma_bf16_TFLOPs"])
     if (args.workload == "qwen3_decode" and cfg.T == 64 and args.keep is None and not args.packed
             and main_pt["U"] == 63):
         # HBM bytes per gate/up launch of exactly this workload from rocprofv3 --pmc
@@ -497,6 +539,7 @@ def main():
         "rules": rules,
         "decode_stack": stack,
         "training_step": training,
+        "ceilings": ceilings,
     }
     print(json.dumps(rec))
 

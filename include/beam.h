@@ -317,6 +317,22 @@ beam_status beam_moe_forward_timed(const beam_shape *shape, const void *x, const
                                    size_t workspace_bytes, void *hip_stream,
                                    float *stage_ms_host);
 
+/*
+ * Measurement aids, not part of the layer: what this GPU delivers, to read a
+ * kernel's roofline fraction against.  Both only enqueue a kernel; the caller
+ * times it (events on `hip_stream`).
+ *   beam_probe_stream_read  reads `buf` (device, >= 64 MiB, 16-byte aligned) once
+ *       with plain coalesced 16-byte loads, eight in flight per lane; writes the
+ *       number of bytes the kernel really reads (bytes rounded down to whole
+ *       batches) to *bytes_read_host.  sink: >= 4 device bytes, left unchanged.
+ *   beam_probe_mfma  runs iters x 4 back-to-back v_mfma_f32_32x32x16_bf16 per
+ *       wavefront on 2048 workgroups with register operands that change every
+ *       iteration; writes the flop count to *flops_host.
+ */
+beam_status beam_probe_stream_read(const void *buf, size_t bytes, void *sink, void *hip_stream,
+                                   size_t *bytes_read_host);
+beam_status beam_probe_mfma(int32_t iters, void *sink, void *hip_stream, double *flops_host);
+
 /* The same measurement aid for beam_moe_block_forward (the shared-gate kernel,
  * if any, is counted in stage 0). */
 beam_status beam_moe_block_forward_timed(const beam_shape *shape, int32_t num_shared,

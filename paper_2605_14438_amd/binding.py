@@ -30,7 +30,8 @@ EXPORTS = ("beam_abi_version", "beam_status_string", "beam_workspace_bytes", "be
            "beam_permute", "beam_expert_ffn", "beam_combine", "beam_moe_forward",
            "beam_moe_forward_timed", "beam_pack_weights", "beam_block_workspace_bytes",
            "beam_moe_block_forward", "beam_moe_block_forward_timed", "beam_route_rule",
-           "beam_moe_forward_rule", "beam_mask_router_backward")
+           "beam_moe_forward_rule", "beam_mask_router_backward", "beam_probe_stream_read",
+           "beam_probe_mfma")
 BEAM_RULE_MASK = 0
 BEAM_RULE_CUMPROB = 1
 BEAM_NUM_STAGES = 6
@@ -91,6 +92,10 @@ def load() -> ctypes.CDLL:
         lib.beam_mask_router_backward.restype = ctypes.c_int
         lib.beam_mask_router_backward.argtypes = [sp] + [vp] * 9 + [ctypes.c_float] + [vp] * 4 + [
             sz, vp]
+        lib.beam_probe_stream_read.restype = ctypes.c_int
+        lib.beam_probe_stream_read.argtypes = [vp, sz, vp, vp, ctypes.POINTER(sz)]
+        lib.beam_probe_mfma.restype = ctypes.c_int
+        lib.beam_probe_mfma.argtypes = [ctypes.c_int32, vp, vp, ctypes.POINTER(ctypes.c_double)]
         lib.beam_block_workspace_bytes.restype = sz
         lib.beam_block_workspace_bytes.argtypes = [sp, ctypes.c_int32]
         lib.beam_moe_block_forward.restype = ctypes.c_int
@@ -293,3 +298,18 @@ def beam_mask_router_backward(shape, x, topk_ids, topk_weights, mask_logits, y_p
         _p(grad_a), _p(grad_w_mask), _p(loss_reg), _p(workspace), int(workspace_bytes),
         _p(hip_stream))
     return _check("beam_mask_router_backward", st, check)
+
+
+def beam_probe_stream_read(buf, nbytes, sink, hip_stream=None, check: bool = True):
+    """-> (status, bytes the probe kernel reads); measurement aid."""
+    n = ctypes.c_size_t(0)
+    st = load().beam_probe_stream_read(_p(buf), int(nbytes), _p(sink), _p(hip_stream),
+                                       ctypes.byref(n))
+    return _check("beam_probe_stream_read", st, check), int(n.value)
+
+
+def beam_probe_mfma(iters, sink, hip_stream=None, check: bool = True):
+    """-> (status, flops the probe kernel performs); measurement aid."""
+    f = ctypes.c_double(0.0)
+    st = load().beam_probe_mfma(int(iters), _p(sink), _p(hip_stream), ctypes.byref(f))
+    return _check("beam_probe_mfma", st, check), float(f.value)

@@ -38,6 +38,9 @@ hipError_t launch_mask_router_backward(const beam_shape &s, const void *x,
                                        float *partial, float *grad_a, float *grad_w_mask,
                                        float *loss_reg, hipStream_t st);
 
+hipError_t launch_probe_stream_read(const void *buf, size_t bytes, void *sink, hipStream_t st);
+hipError_t launch_probe_mfma(int iters, void *sink, hipStream_t st);
+
 static inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
 WsLayout ws_layout(const beam_shape &s) {
@@ -511,6 +514,24 @@ beam_status beam_mask_router_backward(const beam_shape *shape, const void *x,
                                              expert_offsets, perm, inv_perm, grad_out, reg_coeff,
                                              wl, L.max_tiles, (float *)(ws + L.tile_partial), grad_a,
                                              grad_w_mask, loss_reg, stream));
+    return BEAM_OK;
+}
+
+beam_status beam_probe_stream_read(const void *buf, size_t bytes, void *sink, void *hip_stream,
+                                   size_t *bytes_read_host) {
+    if (!buf || !sink || !bytes_read_host || misaligned(buf) || bytes < (1u << 26))
+        return BEAM_ERR_INVALID_ARG;
+    const size_t per_block = bytes / 16 / 2048 / 2048 * 2048;  // as the launcher cuts it
+    *bytes_read_host = per_block * 16 * 2048;
+    BEAM_TRY_HIP(launch_probe_stream_read(buf, bytes, sink, (hipStream_t)hip_stream));
+    return BEAM_OK;
+}
+
+beam_status beam_probe_mfma(int32_t iters, void *sink, void *hip_stream, double *flops_host) {
+    if (iters < 1 || !sink || !flops_host) return BEAM_ERR_INVALID_ARG;
+    // 2048 workgroups x 4 wavefronts x 4 MFMAs per iteration x 2*32*32*16 flops
+    *flops_host = 2048.0 * 4.0 * 4.0 * (double)iters * 32768.0;
+    BEAM_TRY_HIP(launch_probe_mfma(iters, sink, (hipStream_t)hip_stream));
     return BEAM_OK;
 }
 

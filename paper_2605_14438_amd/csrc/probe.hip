@@ -1,0 +1,77 @@
+// Measurement aids, not part of the layer: what this GPU actually delivers, to
+// put next to the published peaks when a kernel's roofline fraction is read.
+//   stream read : every workgroup reads a contiguous slice with 16-byte loads,
+//                 eight independent loads per lane in flight (the access pattern
+//                 with the fewest obstacles between HBM and a register);
+//   MFMA loop   : v_mfma_f32_32x32x16_bf16 back to back on register operands
+//                 that change every iteration, four independent accumulator
+//                 tiles per wavefront, no memory traffic.
+#include "common.hpp"
+
+namespace beam {
+
+__global__ __launch_bounds__(256) void probe_stream_read_kernel(const uint4 *__restrict__ p,
+                                                                size_t n16_per_block,
+                                                                uint32_t *__restrict__ sink) {
+    const uint4 *b = p + (size_t)blockIdx.x * n16_per_block;
+    uint32_t acc = 0;
+    for (size_t i = threadIdx.x; i + 7 * 256 < n16_per_block; i += 8 * 256) {
+        uint4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = b[i + u * 256];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    if (acc == 0x12345679u) sink[0] = acc;  // keeps the loads alive; practically never taken
+}
+
+__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, uint32_t seed,
+                                                         float *__restrict__ sink) {
+    typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+    // operands: bf16 pairs with small random mantissas (finite, sign-mixed), different per lane
+    uint32_t s = seed ^ (blockIdx.x * 256u + threadIdx.x) * 2654435761u;
+    auto next = [&]() {
+        s = s * 1664525u + 1013904223u;
+        return (s & 0x807f807fu) | 0x3c003c00u;  // +-[0.0078, 0.0156): sums stay finite
+    };
+    u32x4v a = {next(), next(), next(), next()};
+    u32x4v b = {next(), next(), next(), next()};
+    f32x16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                             __builtin_bit_cast(bf16x8, b), acc[i],
+                                                             0, 0, 0);
+        a.x = a.y;  // rotate and refresh: the operands are not loop constants
+        a.y = a.z;
+        a.z = a.w;
+        a.w = next();
+        b.x ^= a.w & 0x007f007fu;
+    }
+    float t = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t += acc[i][r];
+    if (t == 123.456f) sink[0] = t;
+}
+
+hipError_t launch_probe_stream_read(const void *buf, size_t bytes, void *sink, hipStream_t st) {
+    const int grid = 256 * 8;
+    const size_t per_block = bytes / 16 / grid / 2048 * 2048;  // whole 8 x 256 batches
+    if (per_block == 0) return hipErrorInvalidValue;
+    probe_stream_read_kernel<<<grid, 256, 0, st>>>((const uint4 *)buf, per_block, (uint32_t *)sink);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_mfma(int iters, void *sink, hipStream_t st) {
+    probe_mfma_kernel<<<256 * 8, 256, 0, st>>>(iters, 12345u, (float *)sink);
+    return hipGetLastError();
+}
+
+}  // namespace beam

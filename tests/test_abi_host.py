@@ -180,6 +180,17 @@ def test_newer_entry_points_check_arguments_on_the_host(lib):
     assert backward(shape=beam.make_shape(4, 256, 8, 9, 512, beam.BEAM_F32)) == bad   # K > N
 
 
+def test_probe_entry_points_check_arguments_on_the_host(lib):
+    ok = 0x1000
+    bad = binding.BEAM_ERR_INVALID_ARG
+    assert beam.beam_probe_stream_read(None, 1 << 27, ok, check=False)[0] == bad
+    assert beam.beam_probe_stream_read(ok, 1 << 27, None, check=False)[0] == bad
+    assert beam.beam_probe_stream_read(ok + 4, 1 << 27, ok, check=False)[0] == bad    # misaligned
+    assert beam.beam_probe_stream_read(ok, (1 << 26) - 1, ok, check=False)[0] == bad  # too small to time
+    assert beam.beam_probe_mfma(0, ok, check=False)[0] == bad
+    assert beam.beam_probe_mfma(10, None, check=False)[0] == bad
+
+
 def test_product_package_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2605_14438_amd")
     for dirpath, _, files in os.walk(pkg):
