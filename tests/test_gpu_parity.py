@@ -1000,10 +1000,12 @@ def test_probe_kernels_run_and_report_their_work():
     """The measurement aids enqueue one kernel each, leave the sink alone and report the
     byte / flop count a caller divides its event time by."""
     print("probe kernels", flush=True)
-    buf = torch.randint(0, 255, (96 << 20,), dtype=torch.uint8, device="cuda")
+    buf = torch.randint(0, 255, (128 << 20,), dtype=torch.uint8, device="cuda")
     sink = torch.full((4,), 7, dtype=torch.int32, device="cuda")
     _, nbytes = beam.beam_probe_stream_read(buf, buf.numel(), sink)
-    assert 0.99 * buf.numel() <= nbytes <= buf.numel() and nbytes % (2048 * 2048 * 16) == 0
+    assert nbytes == buf.numel()          # a multiple of 2048 workgroups x 2048 x 16 bytes
+    _, part = beam.beam_probe_stream_read(buf, (96 << 20), sink)
+    assert part == 64 << 20               # rounded down to whole batches
     _, flops = beam.beam_probe_mfma(100, sink)
     assert flops == 2048 * 4 * 4 * 100 * 2 * 32 * 32 * 16
     torch.cuda.synchronize()
