@@ -72,8 +72,14 @@ __global__ __launch_bounds__(64) void count_kernel(const int32_t *__restrict__ m
 }
 
 // Work list from the per-expert counts (thread e owns expert e; 256 threads).
+// The row tiles are written by all threads together, tile t by thread t % 256,
+// which finds its expert by bisection over the tile prefix: with a skewed router
+// one expert can own most of the tiles, and its thread would otherwise write
+// them one by one.
 __device__ __forceinline__ void emit_work_list(int e, int N, int count, int offset,
                                                const WorkList &wl, int *scratch) {
+    __shared__ int tile_end[256];   // inclusive prefix of the experts' tile counts
+    __shared__ int row_beg[256];
     int total;
     const int has = (e < N && count > 0) ? 1 : 0;
     const int slot = block_exclusive_scan_256(has, scratch, &total);
@@ -85,9 +91,19 @@ __device__ __forceinline__ void emit_work_list(int e, int N, int count, int offs
     if (threadIdx.x == 0) wl.hdr[0] = total;
     const int nt = e < N ? tiles_of(count) : 0;
     const int tbase = block_exclusive_scan_256(nt, scratch, &total);
-    for (int i = 0; i < nt; ++i) {
-        wl.tile_expert[tbase + i] = e;
-        wl.tile_row0[tbase + i] = offset + i * kTileM;
+    tile_end[e] = tbase + nt;
+    row_beg[e] = offset;
+    __syncthreads();
+    for (int t = threadIdx.x; t < total; t += 256) {
+        int lo = 0, hi = 255;   // first expert whose tiles end after t
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (tile_end[mid] > t) hi = mid;
+            else lo = mid + 1;
+        }
+        const int first = lo == 0 ? 0 : tile_end[lo - 1];
+        wl.tile_expert[t] = lo;
+        wl.tile_row0[t] = row_beg[lo] + (t - first) * kTileM;
     }
     if (threadIdx.x == 0) wl.hdr[1] = total;
 }
