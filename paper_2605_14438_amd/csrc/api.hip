@@ -408,6 +408,7 @@ static beam_status moe_forward_impl(const beam_shape *shape, int S, const beam_r
         for (int i = 5; i <= 6; ++i) BEAM_STAGE_MARK(i);
         return BEAM_OK;
     }
+    bool grouped = false;
     if (logits_tiled_supported(s)) {
         // prefill: both heads as one tiled GEMM into a [T,2N] array; biases join at Top-K
         BEAM_TRY_HIP(launch_logits_tiled(s, x, w_router, w_mask, ws + L.packed_heads, rl, stream));
@@ -417,13 +418,21 @@ static beam_status moe_forward_impl(const beam_shape *shape, int S, const beam_r
     } else {
         BEAM_TRY_HIP(launch_logits(s, x, w_router, router_bias, w_mask, mask_bias, rl, ml, stream));
         BEAM_STAGE_MARK(1);
-        BEAM_TRY_HIP(launch_topk_mask(s, rl, ml, nullptr, nullptr, s.N, opt, ids, gw, mids,
-                                      stream));
+        if (route_permute_supported(s, opt, rl, ml)) {
+            // decode: Top-K, mask and grouping in one launch of one workgroup
+            BEAM_TRY_HIP(launch_route_permute(s, rl, ml, opt, ids, gw, mids, counts, offsets, perm,
+                                              inv, np, wl, stream));
+            grouped = true;
+        } else {
+            BEAM_TRY_HIP(launch_topk_mask(s, rl, ml, nullptr, nullptr, s.N, opt, ids, gw, mids,
+                                          stream));
+        }
     }
     BEAM_STAGE_MARK(2);
-    BEAM_TRY_HIP(launch_permute(se, mids, counts, offsets, perm, inv, np,
-                                (int32_t *)(ws + L.blk_counts), (int32_t *)(ws + L.blk_base),
-                                L.nchunk, wl, stream));
+    if (!grouped)
+        BEAM_TRY_HIP(launch_permute(se, mids, counts, offsets, perm, inv, np,
+                                    (int32_t *)(ws + L.blk_counts),
+                                    (int32_t *)(ws + L.blk_base), L.nchunk, wl, stream));
     BEAM_STAGE_MARK(3);
     BEAM_TRY_HIP(launch_gate_up(se, x, w_gate_up, offsets, perm, np, wl, ws + L.hidden, stream));
     BEAM_STAGE_MARK(4);

@@ -144,6 +144,14 @@ hipError_t launch_permute(const beam_shape &s, const int32_t *masked_ids, int32_
                           int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *num_pairs,
                           int32_t *blk_counts, int32_t *blk_base, int nchunk, const WorkList &wl,
                           hipStream_t st);
+bool route_permute_supported(const beam_shape &s, const RouteOpts &opt, const float *router_logits,
+                             const float *mask_logits);
+hipError_t launch_route_permute(const beam_shape &s, const float *router_logits,
+                                const float *mask_logits, const RouteOpts &opt,
+                                int32_t *topk_ids, float *topk_w, int32_t *masked_ids,
+                                int32_t *counts, int32_t *offsets, int32_t *perm,
+                                int32_t *inv_perm, int32_t *num_pairs, const WorkList &wl,
+                                hipStream_t st);
 hipError_t launch_work_list(const beam_shape &s, const int32_t *offsets, const WorkList &wl,
                             hipStream_t st);
 hipError_t launch_gate_up(const beam_shape &s, const void *x, const void *w_gate_up,

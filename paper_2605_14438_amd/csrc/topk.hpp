@@ -146,7 +146,8 @@ __device__ __forceinline__ void wave_route_token(const float *__restrict__ r,
 // cross-row traffic, and every lane of the row ends up with the row's best key.
 // Same keys, same K rounds, same softmax and shared-expert slots as
 // wave_route_token; needs K + S <= 16.
-// `valid` is row-uniform (false for the rows past the last token).
+// `valid` is row-uniform (false for the rows past the last token).  Returns the
+// masked id that lane j wrote for slot j (-1: dropped, or no slot j).
 __device__ __forceinline__ uint64_t row_max_u64(uint64_t key) {
     max_step<0xB1, 0xf>(key);   // quad_perm [1,0,3,2]
     max_step<0x4E, 0xf>(key);   // quad_perm [2,3,0,1]
@@ -164,7 +165,7 @@ __device__ __forceinline__ float row_sum_f32(float v) {
 }
 
 template <int NPL, int RULE>
-__device__ __forceinline__ void row_route_token(const float *__restrict__ r,
+__device__ __forceinline__ int row_route_token(const float *__restrict__ r,
                                                 const float *__restrict__ a,
                                                 const float *__restrict__ br,
                                                 const float *__restrict__ bm, int N, int K,
@@ -232,15 +233,19 @@ __device__ __forceinline__ void row_route_token(const float *__restrict__ r,
         }
         keep = before <= param;
     }
+    int kept_id = -1;  // what lane j wrote to masked_out; -1 also for the lanes that wrote nothing
     if (valid && j < K) {
+        kept_id = keep ? my_id : -1;
         ids_out[j] = my_id;
         w_out[j] = ex / denom;
-        masked_out[j] = keep ? my_id : -1;
+        masked_out[j] = kept_id;
     } else if (valid && j < K + S) {
-        ids_out[j] = N + j - K;
+        kept_id = N + j - K;
+        ids_out[j] = kept_id;
         w_out[j] = g_shared;
-        masked_out[j] = N + j - K;
+        masked_out[j] = kept_id;
     }
+    return kept_id;
 }
 
 }  // namespace beam

@@ -304,6 +304,9 @@ FWD_CASES = [
     synth.LayerConfig("n256_prefill", 12, T=1200, H=256, N=256, K=16, I=128, dtype="bf16",
                       keep=0.5, router_skew="zipf"),
     SMALL_BF16.with_(keep=0.0), SMALL_BF16.with_(keep=1.0),
+    # up to 32 tokens: Top-K, mask and grouping in one launch (4, 8, 16 candidates per lane)
+    SMALL_BF16.with_(T=32), SMALL_BF16.with_(T=7, keep=0.0), CFG["qwen3_decode"].with_(T=13, I=128),
+    synth.LayerConfig("n256_decode", 10, T=30, H=256, N=256, K=16, I=128, dtype="bf16", keep=0.3),
     PREFILL_SMALL, PREFILL_SMALL.with_(T=1100, keep=1.0), PREFILL_SMALL.with_(T=2200, keep=0.7),
 ]
 
@@ -507,6 +510,8 @@ def _check_block_slots(cfg, res, ids_o, g_o, msk_o, g_shared, S):
 @pytest.mark.parametrize("cfg,use_gate,use_residual,packed", [
     (BLOCK_SMALL, True, True, False), (BLOCK_SMALL, False, False, False),
     (BLOCK_SMALL, True, True, True), (BLOCK_SMALL.with_(T=3), True, True, False),
+    # Top-K and grouping as one launch (up to 32 tokens), with shared-expert slots
+    (BLOCK_SMALL.with_(T=29), True, True, False), (BLOCK_SMALL.with_(T=32), False, True, True),
     (BLOCK_F32, True, True, False), (BLOCK_F32, False, True, False),
     (BLOCK_PREFILL, False, True, False), (BLOCK_PREFILL, False, True, True),
     (BLOCK_PREFILL.with_(shared_gate=True, S=3, T=1029), True, False, True),
@@ -697,7 +702,7 @@ def test_route_rule_cumulative_probability(cfg, phi):
          f"{int((~clear).sum())} tokens inside the guard band")
 
 
-@pytest.mark.parametrize("cfg", [SMALL_BF16, PREFILL_SMALL, CFG["tiny"]],
+@pytest.mark.parametrize("cfg", [SMALL_BF16, SMALL_BF16.with_(T=27), PREFILL_SMALL, CFG["tiny"]],
                          ids=lambda c: f"{c.name}-T{c.T}")
 def test_moe_forward_rule(cfg):
     d = hp.make_tie_free(cfg)
