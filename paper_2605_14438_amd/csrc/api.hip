@@ -438,7 +438,7 @@ static beam_status moe_forward_impl(const beam_shape *shape, int S, const beam_r
     BEAM_STAGE_MARK(4);
     BEAM_TRY_HIP(launch_down(se, ws + L.hidden, w_down, offsets, np, wl, y_pairs, stream));
     BEAM_STAGE_MARK(5);
-    BEAM_TRY_HIP(launch_combine(se, y_pairs, gw, mids, inv, residual, out, stream));
+    BEAM_TRY_HIP(launch_combine(se, y_pairs, gw, mids, inv, residual, out, stream, np));
     BEAM_STAGE_MARK(6);
 #undef BEAM_STAGE_MARK
     return BEAM_OK;

@@ -4,6 +4,8 @@
 // gather over the expert-sorted rows: every output element is written exactly
 // once with coalesced accesses and no atomics, and a token with no kept expert
 // gets an exactly +0 row (App. A.3).
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace beam {
@@ -17,6 +19,16 @@ __device__ __forceinline__ void store4(bf16_t *p, float4 v) {
 }
 
 __device__ __forceinline__ float4 load4(const float *p) { return *(const float4 *)p; }
+typedef float f32x4n __attribute__((ext_vector_type(4)));
+template <bool STREAM>
+__device__ __forceinline__ float4 load_y4(const float *p) {
+    if constexpr (STREAM) {
+        const f32x4n v = __builtin_nontemporal_load((const f32x4n *)p);
+        return make_float4(v.x, v.y, v.z, v.w);
+    } else {
+        return *(const float4 *)p;
+    }
+}
 __device__ __forceinline__ float4 load4(const bf16_t *p) {
     const uint2 q = *(const uint2 *)p;
     return make_float4(__uint_as_float(q.x << 16), __uint_as_float(q.x & 0xffff0000u),
@@ -41,7 +53,8 @@ template <typename T, int CH>
 __global__ __launch_bounds__(256) void combine_wave_kernel(
     const float *__restrict__ y_pairs, const float *__restrict__ topk_w,
     const int32_t *__restrict__ masked_ids, const int32_t *__restrict__ inv_perm,
-    const T *__restrict__ residual, T *__restrict__ out, int Tn, int H, int K) {
+    const T *__restrict__ residual, T *__restrict__ out, int Tn, int H, int K,
+    const int32_t *__restrict__ num_pairs) {
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (t >= Tn) return;  // wave-uniform
@@ -53,44 +66,53 @@ __global__ __launch_bounds__(256) void combine_wave_kernel(
         g = topk_w[f];
     }
     const uint64_t kept = __ballot(row >= 0);
-    for (int c0 = lane * 4; c0 < H; c0 += 256 * CH) {
-        float4 acc[CH];
+    auto sum_slots = [&](auto stream) {
+        constexpr bool STREAM = decltype(stream)::value;
+        for (int c0 = lane * 4; c0 < H; c0 += 256 * CH) {
+            float4 acc[CH];
 #pragma unroll
-        for (int i = 0; i < CH; ++i)
-            acc[i] = residual ? load4(residual + (size_t)t * H + c0 + i * 256)
-                              : make_float4(0.f, 0.f, 0.f, 0.f);
-        uint64_t m = kept;
-        while (m) {
-            const int ka = __builtin_ctzll(m);
-            m &= m - 1;
-            const float *pa = y_pairs + (size_t)__shfl(row, ka) * H + c0;
-            const float ga = __shfl(g, ka);
-            if (m) {
-                const int kb = __builtin_ctzll(m);
+            for (int i = 0; i < CH; ++i)
+                acc[i] = residual ? load4(residual + (size_t)t * H + c0 + i * 256)
+                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+            uint64_t m = kept;
+            while (m) {
+                const int ka = __builtin_ctzll(m);
                 m &= m - 1;
-                const float *pb = y_pairs + (size_t)__shfl(row, kb) * H + c0;
-                const float gb = __shfl(g, kb);
-                float4 ya[CH], yb[CH];
+                const float *pa = y_pairs + (size_t)__shfl(row, ka) * H + c0;
+                const float ga = __shfl(g, ka);
+                if (m) {
+                    const int kb = __builtin_ctzll(m);
+                    m &= m - 1;
+                    const float *pb = y_pairs + (size_t)__shfl(row, kb) * H + c0;
+                    const float gb = __shfl(g, kb);
+                    float4 ya[CH], yb[CH];
 #pragma unroll
-                for (int i = 0; i < CH; ++i) ya[i] = *(const float4 *)(pa + i * 256);
+                    for (int i = 0; i < CH; ++i) ya[i] = load_y4<STREAM>(pa + i * 256);
 #pragma unroll
-                for (int i = 0; i < CH; ++i) yb[i] = *(const float4 *)(pb + i * 256);
+                    for (int i = 0; i < CH; ++i) yb[i] = load_y4<STREAM>(pb + i * 256);
 #pragma unroll
-                for (int i = 0; i < CH; ++i) {
-                    axpy4(ga, ya[i], acc[i]);
-                    axpy4(gb, yb[i], acc[i]);
+                    for (int i = 0; i < CH; ++i) {
+                        axpy4(ga, ya[i], acc[i]);
+                        axpy4(gb, yb[i], acc[i]);
+                    }
+                } else {
+                    float4 ya[CH];
+#pragma unroll
+                    for (int i = 0; i < CH; ++i) ya[i] = load_y4<STREAM>(pa + i * 256);
+#pragma unroll
+                    for (int i = 0; i < CH; ++i) axpy4(ga, ya[i], acc[i]);
                 }
-            } else {
-                float4 ya[CH];
-#pragma unroll
-                for (int i = 0; i < CH; ++i) ya[i] = *(const float4 *)(pa + i * 256);
-#pragma unroll
-                for (int i = 0; i < CH; ++i) axpy4(ga, ya[i], acc[i]);
             }
-        }
 #pragma unroll
-        for (int i = 0; i < CH; ++i) store4(out + (size_t)t * H + c0 + i * 256, acc[i]);
-    }
+            for (int i = 0; i < CH; ++i) store4(out + (size_t)t * H + c0 + i * 256, acc[i]);
+        }
+    };
+    // y_pairs too large to have stayed in cache since the down projection wrote it:
+    // read it past the caches (same values, same order of additions)
+    if (num_pairs && (size_t)*num_pairs * H * sizeof(float) > kStreamBytes)
+        sum_slots(std::true_type{});
+    else
+        sum_slots(std::false_type{});
 }
 
 // Any H % 4 == 0: one workgroup per token, a slot at a time.
@@ -118,13 +140,13 @@ __global__ __launch_bounds__(256) void combine_generic_kernel(
 template <typename T>
 static void launch_typed(const beam_shape &s, const float *y_pairs, const float *topk_w,
                          const int32_t *masked_ids, const int32_t *inv_perm, const T *residual,
-                         T *out, hipStream_t st) {
+                         T *out, hipStream_t st, const int32_t *num_pairs) {
     // decode-sized batches: one wavefront per workgroup, to spread over the CUs
     const int wpb = s.T <= 1024 ? 1 : 4;
     const dim3 wave_grid((s.T + wpb - 1) / wpb);
 #define BEAM_COMBINE_WAVE(CH)                                                                   \
     combine_wave_kernel<T, CH><<<wave_grid, 64 * wpb, 0, st>>>(                                 \
-        y_pairs, topk_w, masked_ids, inv_perm, residual, out, s.T, s.H, s.K)
+        y_pairs, topk_w, masked_ids, inv_perm, residual, out, s.T, s.H, s.K, num_pairs)
     if (s.H % 2048 == 0) BEAM_COMBINE_WAVE(8);
     else if (s.H % 1280 == 0) BEAM_COMBINE_WAVE(5);
     else if (s.H % 1024 == 0) BEAM_COMBINE_WAVE(4);
@@ -139,13 +161,14 @@ static void launch_typed(const beam_shape &s, const float *y_pairs, const float 
 
 hipError_t launch_combine(const beam_shape &s, const float *y_pairs, const float *topk_w,
                           const int32_t *masked_ids, const int32_t *inv_perm,
-                          const void *residual, void *out, hipStream_t st) {
+                          const void *residual, void *out, hipStream_t st,
+                          const int32_t *num_pairs) {
     if (s.dtype == BEAM_BF16)
         launch_typed<bf16_t>(s, y_pairs, topk_w, masked_ids, inv_perm, (const bf16_t *)residual,
-                             (bf16_t *)out, st);
+                             (bf16_t *)out, st, num_pairs);
     else
         launch_typed<float>(s, y_pairs, topk_w, masked_ids, inv_perm, (const float *)residual,
-                            (float *)out, st);
+                            (float *)out, st, num_pairs);
     return hipGetLastError();
 }
 

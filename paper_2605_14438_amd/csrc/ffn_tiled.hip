@@ -100,12 +100,13 @@ struct TileItem {
 // workgroup's MFMAs cover it.
 // COL_GUARD (down roles only): the output is narrower than the last column tile;
 // columns >= H are computed from zero padding and not stored.
+// stream_out (down roles only, uniform): the output goes past the caches.
 template <int BM, int WM, int KS, bool GATE_UP, bool PACKED, bool CHAIN, bool COL_GUARD,
           typename NextItem>
 __device__ __forceinline__ void ffn_tile_run(
     u32x4 *As, const bf16_t *__restrict__ a_src, const bf16_t *__restrict__ w,
     const int32_t *__restrict__ perm, bf16_t *__restrict__ hidden_out, float *__restrict__ y_out,
-    int H, int K, int I, NextItem next_item) {
+    int H, int K, int I, bool stream_out, NextItem next_item) {
     constexpr int PR = 2 * KS;           // 16-byte pieces per LDS row (K-step of 16*KS indices)
     constexpr int RPP = 256 / PR;        // tile rows copied per pass of the 256 threads
     constexpr int AP = BM / RPP;         // A rows per thread
@@ -332,21 +333,29 @@ __device__ __forceinline__ void ffn_tile_run(
             // Activations were the A operand: register r of lane l is row
             // 8*(r >> 2) + 4*(l >> 5) + (r & 3), column l & 31 of the tile, so each
             // store instruction writes two full 128-byte row segments of fp32.
+            auto store_tile = [&](auto stream) {
 #pragma unroll
-            for (int m = 0; m < WTM; ++m) {
+                for (int m = 0; m < WTM; ++m) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int trow = wm * (BM / WM) + m * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
-                    const int grow = done.row0 + trow;
-                    if (grow >= done.row_end) continue;
-                    float *orow = y_out + (size_t)grow * H + n0 + l32;
+                    for (int r = 0; r < 16; ++r) {
+                        const int trow = wm * (BM / WM) + m * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
+                        const int grow = done.row0 + trow;
+                        if (grow >= done.row_end) continue;
+                        float *orow = y_out + (size_t)grow * H + n0 + l32;
 #pragma unroll
-                    for (int n = 0; n < WTN; ++n) {
-                        if (COL_GUARD && n0 + l32 + (wn * WTN + n) * 32 >= H) continue;
-                        orow[(wn * WTN + n) * 32] = acc[m][n][r];
+                        for (int n = 0; n < WTN; ++n) {
+                            if (COL_GUARD && n0 + l32 + (wn * WTN + n) * 32 >= H) continue;
+                            if constexpr (decltype(stream)::value)
+                                __builtin_nontemporal_store(acc[m][n][r],
+                                                            &orow[(wn * WTN + n) * 32]);
+                            else
+                                orow[(wn * WTN + n) * 32] = acc[m][n][r];
+                        }
                     }
                 }
-            }
+            };
+            if (stream_out) store_tile(std::true_type{});
+            else store_tile(std::false_type{});
         }
         if (!has_next) break;
         cur = nxt;
@@ -412,8 +421,10 @@ __global__ __launch_bounds__(256, OCC) void ffn_tile_kernel(
         it.col_tile = col_tile;
         return true;
     };
+    // more rows of y_pairs than the last-level cache can hold until they are read again
+    const bool stream_out = !GATE_UP && (size_t)n_tiles * kTileM * H * sizeof(float) > kStreamBytes;
     ffn_tile_run<kTileM, WM, KS, GATE_UP, PACKED, OCC == 1, false>(
-        As, a_src, w, perm, hidden_out, y_out, H, K, I, next_item);
+        As, a_src, w, perm, hidden_out, y_out, H, K, I, stream_out, next_item);
 }
 
 bool tiled_ffn_supported(const beam_shape &s) {
@@ -521,7 +532,7 @@ __global__ __launch_bounds__(256, 2) void logits_tile_kernel(
     };
     // down-GEMM roles: output width N2, reduction length H, a single expert
     ffn_tile_run<kLogitsM, kWavesM, kLogitsKS, false, true, true, true>(
-        As, x, packed_heads, nullptr, nullptr, logits2, N2, 1, H, next_item);
+        As, x, packed_heads, nullptr, nullptr, logits2, N2, 1, H, false, next_item);
 }
 
 bool logits_tiled_supported(const beam_shape &s) {
