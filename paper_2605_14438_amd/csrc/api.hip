@@ -25,7 +25,7 @@ hipError_t launch_gate_up_tiled(const beam_shape &s, const void *x, const void *
                                 void *hidden, hipStream_t st);
 hipError_t launch_down_tiled(const beam_shape &s, const void *hidden, const void *w_down,
                              const int32_t *offsets, const WorkList &wl, float *y_pairs,
-                             hipStream_t st);
+                             hipStream_t st, int k_split);
 hipError_t launch_pack_weights(const beam_shape &s, const void *w_gate_up, const void *w_down,
                                void *w_gate_up_packed, void *w_down_packed, hipStream_t st);
 
@@ -42,6 +42,25 @@ hipError_t launch_probe_stream_read(const void *buf, size_t bytes, void *sink, h
 hipError_t launch_probe_mfma(int iters, void *sink, hipStream_t st);
 
 static inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+static bool use_tiled(const beam_shape &s);
+
+// Parts the fused layer cuts the down GEMM's reduction into.  The tiled GEMM has
+// (row tiles) x H/256 items for 512 resident workgroups; a few experts with a long
+// reduction (Mixtral-shaped: 8 experts, I = 14336) give fewer items than that, each
+// hundreds of K-steps long, and most of the chip idles.  Decided from the shape alone
+// (item count with every pair kept); the partial sums cost k_split x [T*K,H] fp32 of
+// workspace and are added in part order by the aggregation.  Measured on the
+// Mixtral-shaped layer, down GEMM: T = 256 384 -> 167 us, T = 512 404 -> 173,
+// T = 1024 403 -> 250 (the aggregation gains 4-12 us); at T = 2048 (384 items of work
+// already) four parts give 407 -> 352 us but the aggregation and the gate/up GEMM lose
+// as much, and two parts give nothing, so it stays whole.
+static int down_split_k(const beam_shape &s) {
+    if (!use_tiled(s) || s.I < 4096) return 1;
+    const long items = ((long)s.T * s.K / kTileM + s.N) * (s.H / 256);
+    const int k_split = items <= 512 ? 4 : 1;
+    return (s.I / 64) % k_split == 0 ? k_split : 1;   // whole 64-wide K-steps per part
+}
 
 WsLayout ws_layout(const beam_shape &s) {
     WsLayout L;
@@ -74,7 +93,7 @@ WsLayout ws_layout(const beam_shape &s) {
     L.inv_perm = take(TK * 4);
     L.work = take((16 + 3 * N + 2 * (size_t)L.max_tiles) * 4);
     L.hidden = take(TK * (size_t)s.I * esz);
-    L.y_pairs = take(TK * (size_t)s.H * 4);
+    L.y_pairs = take(TK * (size_t)s.H * 4 * down_split_k(s));
     L.tile_partial = take((size_t)L.max_tiles * s.H * 4);
     L.total = off;
     return L;
@@ -116,8 +135,9 @@ hipError_t launch_gate_up(const beam_shape &s, const void *x, const void *w_gate
 
 hipError_t launch_down(const beam_shape &s, const void *hidden, const void *w_down,
                        const int32_t *offsets, const int32_t *num_pairs, const WorkList &wl,
-                       float *y_pairs, hipStream_t st) {
-    if (use_tiled(s)) return launch_down_tiled(s, hidden, w_down, offsets, wl, y_pairs, st);
+                       float *y_pairs, hipStream_t st, int k_split) {
+    if (use_tiled(s))
+        return launch_down_tiled(s, hidden, w_down, offsets, wl, y_pairs, st, k_split);
     if (stream_ffn_supported(s))
         return launch_down_stream(s, hidden, w_down, offsets, wl, y_pairs, st);
     return launch_down_generic(s, hidden, w_down, offsets, num_pairs, y_pairs, st);
@@ -436,9 +456,11 @@ static beam_status moe_forward_impl(const beam_shape *shape, int S, const beam_r
     BEAM_STAGE_MARK(3);
     BEAM_TRY_HIP(launch_gate_up(se, x, w_gate_up, offsets, perm, np, wl, ws + L.hidden, stream));
     BEAM_STAGE_MARK(4);
-    BEAM_TRY_HIP(launch_down(se, ws + L.hidden, w_down, offsets, np, wl, y_pairs, stream));
+    const int k_split = down_split_k(se);
+    BEAM_TRY_HIP(launch_down(se, ws + L.hidden, w_down, offsets, np, wl, y_pairs, stream,
+                             k_split));
     BEAM_STAGE_MARK(5);
-    BEAM_TRY_HIP(launch_combine(se, y_pairs, gw, mids, inv, residual, out, stream, np));
+    BEAM_TRY_HIP(launch_combine(se, y_pairs, gw, mids, inv, residual, out, stream, np, k_split));
     BEAM_STAGE_MARK(6);
 #undef BEAM_STAGE_MARK
     return BEAM_OK;

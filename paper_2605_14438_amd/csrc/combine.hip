@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256) void combine_wave_kernel(
     const float *__restrict__ y_pairs, const float *__restrict__ topk_w,
     const int32_t *__restrict__ masked_ids, const int32_t *__restrict__ inv_perm,
     const T *__restrict__ residual, T *__restrict__ out, int Tn, int H, int K,
-    const int32_t *__restrict__ num_pairs) {
+    const int32_t *__restrict__ num_pairs, int k_split, size_t slice_stride) {
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (t >= Tn) return;  // wave-uniform
@@ -74,16 +74,18 @@ __global__ __launch_bounds__(256) void combine_wave_kernel(
             for (int i = 0; i < CH; ++i)
                 acc[i] = residual ? load4(residual + (size_t)t * H + c0 + i * 256)
                                   : make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int sl = 0; sl < k_split; ++sl) {   // parts of a split down projection, in order
+            const float *ys = y_pairs + sl * slice_stride;
             uint64_t m = kept;
             while (m) {
                 const int ka = __builtin_ctzll(m);
                 m &= m - 1;
-                const float *pa = y_pairs + (size_t)__shfl(row, ka) * H + c0;
+                const float *pa = ys + (size_t)__shfl(row, ka) * H + c0;
                 const float ga = __shfl(g, ka);
                 if (m) {
                     const int kb = __builtin_ctzll(m);
                     m &= m - 1;
-                    const float *pb = y_pairs + (size_t)__shfl(row, kb) * H + c0;
+                    const float *pb = ys + (size_t)__shfl(row, kb) * H + c0;
                     const float gb = __shfl(g, kb);
                     float4 ya[CH], yb[CH];
 #pragma unroll
@@ -102,6 +104,7 @@ __global__ __launch_bounds__(256) void combine_wave_kernel(
 #pragma unroll
                     for (int i = 0; i < CH; ++i) axpy4(ga, ya[i], acc[i]);
                 }
+            }
             }
 #pragma unroll
             for (int i = 0; i < CH; ++i) store4(out + (size_t)t * H + c0 + i * 256, acc[i]);
@@ -140,13 +143,14 @@ __global__ __launch_bounds__(256) void combine_generic_kernel(
 template <typename T>
 static void launch_typed(const beam_shape &s, const float *y_pairs, const float *topk_w,
                          const int32_t *masked_ids, const int32_t *inv_perm, const T *residual,
-                         T *out, hipStream_t st, const int32_t *num_pairs) {
+                         T *out, hipStream_t st, const int32_t *num_pairs, int k_split) {
     // decode-sized batches: one wavefront per workgroup, to spread over the CUs
     const int wpb = s.T <= 1024 ? 1 : 4;
     const dim3 wave_grid((s.T + wpb - 1) / wpb);
 #define BEAM_COMBINE_WAVE(CH)                                                                   \
     combine_wave_kernel<T, CH><<<wave_grid, 64 * wpb, 0, st>>>(                                 \
-        y_pairs, topk_w, masked_ids, inv_perm, residual, out, s.T, s.H, s.K, num_pairs)
+        y_pairs, topk_w, masked_ids, inv_perm, residual, out, s.T, s.H, s.K, num_pairs,       \
+        k_split, (size_t)s.T * s.K * s.H)
     if (s.H % 2048 == 0) BEAM_COMBINE_WAVE(8);
     else if (s.H % 1280 == 0) BEAM_COMBINE_WAVE(5);
     else if (s.H % 1024 == 0) BEAM_COMBINE_WAVE(4);
@@ -162,13 +166,13 @@ static void launch_typed(const beam_shape &s, const float *y_pairs, const float 
 hipError_t launch_combine(const beam_shape &s, const float *y_pairs, const float *topk_w,
                           const int32_t *masked_ids, const int32_t *inv_perm,
                           const void *residual, void *out, hipStream_t st,
-                          const int32_t *num_pairs) {
+                          const int32_t *num_pairs, int k_split) {
     if (s.dtype == BEAM_BF16)
         launch_typed<bf16_t>(s, y_pairs, topk_w, masked_ids, inv_perm, (const bf16_t *)residual,
-                             (bf16_t *)out, st, num_pairs);
+                             (bf16_t *)out, st, num_pairs, k_split);
     else
         launch_typed<float>(s, y_pairs, topk_w, masked_ids, inv_perm, (const float *)residual,
-                            (float *)out, st, num_pairs);
+                            (float *)out, st, num_pairs, k_split);
     return hipGetLastError();
 }
 

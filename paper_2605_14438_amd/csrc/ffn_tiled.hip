@@ -83,6 +83,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 struct TileItem {
     int e, row0, row_end, col_tile;
+    int slice;  // which part of the reduction (down roles with a split reduction), else 0
 };
 
 // The persistent tile loop of one workgroup.  next_item(seq, it) advances seq to
@@ -101,12 +102,17 @@ struct TileItem {
 // COL_GUARD (down roles only): the output is narrower than the last column tile;
 // columns >= H are computed from zero padding and not stored.
 // stream_out (down roles only, uniform): the output goes past the caches.
+// k_split (down roles only): the reduction is cut into k_split equal parts; an
+// item multiplies part `slice` and writes its partial sums to y_out + slice *
+// slice_stride (elements).  With few, long items (a handful of experts with a
+// long reduction) this is what fills the chip and evens out its last round;
+// the aggregation adds the parts in slice order.
 template <int BM, int WM, int KS, bool GATE_UP, bool PACKED, bool CHAIN, bool COL_GUARD,
           typename NextItem>
 __device__ __forceinline__ void ffn_tile_run(
     u32x4 *As, const bf16_t *__restrict__ a_src, const bf16_t *__restrict__ w,
     const int32_t *__restrict__ perm, bf16_t *__restrict__ hidden_out, float *__restrict__ y_out,
-    int H, int K, int I, bool stream_out, NextItem next_item) {
+    int H, int K, int I, bool stream_out, int k_split, size_t slice_stride, NextItem next_item) {
     constexpr int PR = 2 * KS;           // 16-byte pieces per LDS row (K-step of 16*KS indices)
     constexpr int RPP = 256 / PR;        // tile rows copied per pass of the 256 threads
     constexpr int AP = BM / RPP;         // A rows per thread
@@ -126,7 +132,7 @@ __device__ __forceinline__ void ffn_tile_run(
     const int l32 = lane & 31;
     const int kh = lane >> 5;
     const int kdim = GATE_UP ? H : I;
-    const int nk = kdim / (16 * KS);
+    const int nk = kdim / (16 * KS) / k_split;   // K-steps per item
     // element stride between the weight pieces of consecutive MFMA k-steps,
     // and between consecutive K-steps
     constexpr int kBStep = PACKED ? 512 : 8;
@@ -149,7 +155,7 @@ __device__ __forceinline__ void ffn_tile_run(
             const int tok = perm[grow] / K;                                                     \
             ao[p] = (uint32_t)tok * (uint32_t)H + piece * 8;                                    \
         } else {                                                                                \
-            ao[p] = (uint32_t)grow * (uint32_t)I + piece * 8;                                   \
+            ao[p] = (uint32_t)grow * (uint32_t)I + piece * 8 + (it).slice * nk * (16 * KS);     \
         }                                                                                       \
     }                                                                                           \
     _Pragma("unroll") for (int n = 0; n < WTN; ++n) {                                           \
@@ -167,6 +173,7 @@ __device__ __forceinline__ void ffn_tile_run(
             bp[n] = w + ((size_t)(it).e * H + (it).col_tile * kTileN + nb * 32 + l32) * I +     \
                     kh * (8 * KS);                                                              \
         }                                                                                       \
+        if constexpr (!GATE_UP) bp[n] += (size_t)(it).slice * nk * kBKStep;                     \
     }
 
     f32x16 acc[WTM][WTN];
@@ -341,7 +348,7 @@ __device__ __forceinline__ void ffn_tile_run(
                         const int trow = wm * (BM / WM) + m * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
                         const int grow = done.row0 + trow;
                         if (grow >= done.row_end) continue;
-                        float *orow = y_out + (size_t)grow * H + n0 + l32;
+                        float *orow = y_out + done.slice * slice_stride + (size_t)grow * H + n0 + l32;
 #pragma unroll
                         for (int n = 0; n < WTN; ++n) {
                             if (COL_GUARD && n0 + l32 + (wn * WTN + n) * 32 >= H) continue;
@@ -388,7 +395,8 @@ __global__ __launch_bounds__(256, OCC) void ffn_tile_kernel(
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm,
     const int32_t *__restrict__ wl_hdr, const int32_t *__restrict__ tile_expert,
     const int32_t *__restrict__ tile_row0, bf16_t *__restrict__ hidden_out,
-    float *__restrict__ y_out, int H, int K, int I, int n_col_tiles) {
+    float *__restrict__ y_out, int H, int K, int I, int n_col_tiles, int k_split,
+    size_t slice_stride) {
     __shared__ u32x4 As[2 * kTileM * 2 * KS];
     // Item order: the row tiles of an expert in groups of up to kRowGroup (a group
     // never spans two experts); inside a group the column tile is the slow index
@@ -398,13 +406,17 @@ __global__ __launch_bounds__(256, OCC) void ffn_tile_kernel(
     // with F the list index of its first row tile, so item / n_col_tiles is always
     // a row tile of the item's own group, from which the group is reconstructed.
     const int n_tiles = wl_hdr[1];
-    const int n_work = n_tiles * n_col_tiles;
+    // with a split reduction: all items of part 0, then all of part 1, ...
+    const int n_base = n_tiles * n_col_tiles;
+    const int n_work = n_base * k_split;
     const int xcd = blockIdx.x & 7;
     const int member = blockIdx.x >> 3;  // gridDim.x / 8 workgroups per XCD
     const int per_xcd = gridDim.x >> 3;
     auto next_item = [&](int &round, TileItem &it) -> bool {
-        const int item = (round * 8 + xcd) * per_xcd + member;
-        if (item >= n_work) return false;    // uniform over the workgroup
+        const int item_s = (round * 8 + xcd) * per_xcd + member;
+        if (item_s >= n_work) return false;  // uniform over the workgroup
+        const int slice = item_s / n_base;
+        const int item = item_s - slice * n_base;
         const int q = item / n_col_tiles;
         const int e = tile_expert[q];
         const int beg = offsets[e];
@@ -419,12 +431,14 @@ __global__ __launch_bounds__(256, OCC) void ffn_tile_kernel(
         it.row0 = beg + (g0 + rem - col_tile * size) * kTileM;
         it.row_end = end;
         it.col_tile = col_tile;
+        it.slice = slice;
         return true;
     };
     // more rows of y_pairs than the last-level cache can hold until they are read again
     const bool stream_out = !GATE_UP && (size_t)n_tiles * kTileM * H * sizeof(float) > kStreamBytes;
     ffn_tile_run<kTileM, WM, KS, GATE_UP, PACKED, OCC == 1, false>(
-        As, a_src, w, perm, hidden_out, y_out, H, K, I, stream_out, next_item);
+        As, a_src, w, perm, hidden_out, y_out, H, K, I, stream_out, k_split, slice_stride,
+        next_item);
 }
 
 bool tiled_ffn_supported(const beam_shape &s) {
@@ -436,11 +450,12 @@ bool tiled_ffn_supported(const beam_shape &s) {
 template <bool GATE_UP>
 static void launch_tile(const beam_shape &s, const bf16_t *a, const bf16_t *w,
                         const int32_t *offsets, const int32_t *perm, const WorkList &wl,
-                        bf16_t *hidden, float *y, int nct, hipStream_t st) {
+                        bf16_t *hidden, float *y, int nct, int k_split, hipStream_t st) {
     const bool packed = s.weight_layout == BEAM_WEIGHTS_PACKED;
 #define BEAM_LAUNCH_TILE(KS_, OCC_, PK)                                                        \
     ffn_tile_kernel<kWavesM, KS_, OCC_, GATE_UP, PK><<<256 * OCC_, 256, 0, st>>>(              \
-        a, w, offsets, perm, wl.hdr, wl.tile_expert, wl.tile_row0, hidden, y, s.H, s.K, s.I, nct)
+        a, w, offsets, perm, wl.hdr, wl.tile_expert, wl.tile_row0, hidden, y, s.H, s.K, s.I, nct, \
+        k_split, (size_t)s.T * s.K * s.H)
     // Two schedules of the same tile body.  "Dense": 64-wide K-steps, two
     // workgroups per CU, whose MFMAs cover each other's prologue, epilogue and
     // barriers; the faster one when the reduction is short and the work MFMA
@@ -465,15 +480,17 @@ hipError_t launch_gate_up_tiled(const beam_shape &s, const void *x, const void *
                                 const int32_t *offsets, const int32_t *perm, const WorkList &wl,
                                 void *hidden, hipStream_t st) {
     launch_tile<true>(s, (const bf16_t *)x, (const bf16_t *)w_gate_up, offsets, perm, wl,
-                      (bf16_t *)hidden, nullptr, s.I / (kTileN / 2), st);
+                      (bf16_t *)hidden, nullptr, s.I / (kTileN / 2), 1, st);
     return hipGetLastError();
 }
 
+// k_split > 1: y_pairs holds k_split arrays [T*K,H] of partial sums, one per part of
+// the reduction; I / (16 * kKSteps) must be a multiple of k_split.
 hipError_t launch_down_tiled(const beam_shape &s, const void *hidden, const void *w_down,
                              const int32_t *offsets, const WorkList &wl, float *y_pairs,
-                             hipStream_t st) {
+                             hipStream_t st, int k_split) {
     launch_tile<false>(s, (const bf16_t *)hidden, (const bf16_t *)w_down, offsets, nullptr, wl,
-                       nullptr, y_pairs, s.H / kTileN, st);
+                       nullptr, y_pairs, s.H / kTileN, k_split, st);
     return hipGetLastError();
 }
 
@@ -528,11 +545,12 @@ __global__ __launch_bounds__(256, 2) void logits_tile_kernel(
         it.row0 = tile * kLogitsM;
         it.row_end = Tn;
         it.col_tile = item - tile * nct;
+        it.slice = 0;
         return true;
     };
     // down-GEMM roles: output width N2, reduction length H, a single expert
     ffn_tile_run<kLogitsM, kWavesM, kLogitsKS, false, true, true, true>(
-        As, x, packed_heads, nullptr, nullptr, logits2, N2, 1, H, false, next_item);
+        As, x, packed_heads, nullptr, nullptr, logits2, N2, 1, H, false, 1, 0, next_item);
 }
 
 bool logits_tiled_supported(const beam_shape &s) {

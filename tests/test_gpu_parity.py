@@ -307,6 +307,11 @@ FWD_CASES = [
     # up to 32 tokens: Top-K, mask and grouping in one launch (4, 8, 16 candidates per lane)
     SMALL_BF16.with_(T=32), SMALL_BF16.with_(T=7, keep=0.0), CFG["qwen3_decode"].with_(T=13, I=128),
     synth.LayerConfig("n256_decode", 10, T=30, H=256, N=256, K=16, I=128, dtype="bf16", keep=0.3),
+    # few experts with a long reduction: the down GEMM's reduction is cut into parts whose
+    # partial sums the aggregation adds
+    synth.LayerConfig("long_reduction", 13, T=300, H=256, N=4, K=2, I=4096, dtype="bf16", keep=0.7),
+    synth.LayerConfig("long_reduction", 13, T=2500, H=512, N=4, K=2, I=4096, dtype="bf16",
+                      keep=0.5),
     PREFILL_SMALL, PREFILL_SMALL.with_(T=1100, keep=1.0), PREFILL_SMALL.with_(T=2200, keep=0.7),
 ]
 
@@ -454,7 +459,8 @@ def _prefix_check(name, Tmax, T, packed):
     return kept
 
 
-@pytest.mark.parametrize("T,packed", [(1, False), (16, False), (2048, True), (2048, False)])
+@pytest.mark.parametrize("T,packed", [(1, False), (16, False), (2048, True), (2048, False),
+                                      (600, True), (600, False)])   # split down reduction
 def test_moe_forward_mixtral_full_size(T, packed):
     kept = _prefix_check("mixtral", 2048, T, packed)
     if T == 2048:
