@@ -183,6 +183,10 @@ beam_status beam_combine(const beam_shape *shape, const float *y_pairs, const fl
  * the kept pairs, combine.  Intermediates live in the workspace.  The four
  * *_opt outputs may each be NULL: topk_ids_opt [T,K], topk_weights_opt [T,K],
  * masked_ids_opt [T,K], num_pairs_opt [1] (device).
+ * Same indices as the staged calls; the output may differ from theirs in the
+ * last bits where the fused call orders its fp32 sums differently (few experts
+ * with a long reduction: the down projection is summed in four parts), within
+ * the same tolerance, and is the same on every run.
  */
 beam_status beam_moe_forward(const beam_shape *shape, const void *x, const void *w_router,
                              const float *router_bias, const void *w_mask, const float *mask_bias,

@@ -574,7 +574,12 @@ static beam_status timed_impl(const beam_shape *shape, int32_t num_shared, const
                               float *stage_ms_host) {
     if (!stage_ms_host) return BEAM_ERR_INVALID_ARG;
     hipEvent_t ev[BEAM_NUM_STAGES + 1];
-    for (int i = 0; i <= BEAM_NUM_STAGES; ++i) BEAM_TRY_HIP(hipEventCreate(&ev[i]));
+    for (int i = 0; i <= BEAM_NUM_STAGES; ++i) {
+        if (hipEventCreate(&ev[i]) != hipSuccess) {
+            while (--i >= 0) (void)hipEventDestroy(ev[i]);
+            return BEAM_ERR_HIP;
+        }
+    }
     beam_status st = moe_forward_impl(shape, num_shared, nullptr, x, w_router, router_bias, w_mask,
                                       mask_bias, w_gate_up, w_down, w_shared_gate, residual, out,
                                       nullptr, nullptr, nullptr, nullptr, workspace,
