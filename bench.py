@@ -454,7 +454,8 @@ def main():
             c = pre.with_(T=T, keep=keep)
             dd = synth.make_layer(c, with_experts=False)
             gg = {**hp.upload(c, dd), "w_gate_up": g["w_gate_up"], "w_down": g["w_down"]}
-            points.append(measure_point(c, dd, gg, get_packed_sets(), n, 3, torch, beam, hp,
+            # 20 untimed forwards first: the clock needs tens of milliseconds of load to settle
+            points.append(measure_point(c, dd, gg, get_packed_sets(), n, 20, torch, beam, hp,
                                         packed=True))
         c = pre.with_(T=16384, keep=0.15)
         dd = synth.make_layer(c, with_experts=False)
