@@ -77,7 +77,7 @@ WsLayout ws_layout(const beam_shape &s) {
         return at;
     };
     // one allocation: the prefill logits kernel writes them as a single [T,2N] array
-    L.router_logits = take(2 * T * N * 4);
+    L.router_logits = take(2 * T * N * 4 * logits_split_k(s));   // one [T,2N] array per part
     L.mask_logits = L.router_logits + T * N * 4;
     L.packed_heads = take((2 * N + 255) / 256 * 256 * (size_t)s.H * esz);  // padded to a column tile
     L.topk_ids = take(TK * 4);
@@ -250,11 +250,12 @@ static beam_status route_impl(const beam_shape *shape, const beam_rule *rule, co
         // in the optional copies
         float *l2 = (float *)(ws + L.router_logits);
         BEAM_TRY_HIP(launch_logits_tiled(s, x, w_router, w_mask, ws + L.packed_heads, l2, stream));
+        const int parts = logits_split_k(s);
         BEAM_TRY_HIP(launch_topk_mask(s, l2, l2 + s.N, router_bias, mask_bias, 2 * s.N, opt,
-                                      topk_ids, topk_weights, masked_ids, stream));
+                                      topk_ids, topk_weights, masked_ids, stream, parts));
         if (router_logits_dbg || mask_logits_dbg)
             BEAM_TRY_HIP(launch_split_logits(s, l2, router_bias, mask_bias, router_logits_dbg,
-                                             mask_logits_dbg, stream));
+                                             mask_logits_dbg, stream, parts));
         return BEAM_OK;
     }
     float *rl = router_logits_dbg ? router_logits_dbg : (float *)(ws + L.router_logits);
@@ -434,7 +435,7 @@ static beam_status moe_forward_impl(const beam_shape *shape, int S, const beam_r
         BEAM_TRY_HIP(launch_logits_tiled(s, x, w_router, w_mask, ws + L.packed_heads, rl, stream));
         BEAM_STAGE_MARK(1);
         BEAM_TRY_HIP(launch_topk_mask(s, rl, rl + s.N, router_bias, mask_bias, 2 * s.N, opt, ids,
-                                      gw, mids, stream));
+                                      gw, mids, stream, logits_split_k(s)));
     } else {
         BEAM_TRY_HIP(launch_logits(s, x, w_router, router_bias, w_mask, mask_bias, rl, ml, stream));
         BEAM_STAGE_MARK(1);

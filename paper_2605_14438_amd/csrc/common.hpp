@@ -126,7 +126,7 @@ hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_route
                          int32_t *zero_word = nullptr);
 hipError_t launch_split_logits(const beam_shape &s, const float *logits2, const float *b_router,
                                const float *b_mask, float *router_logits, float *mask_logits,
-                               hipStream_t st);
+                               hipStream_t st, int n_parts = 1);
 bool tiny_decode_supported(const beam_shape &s, int S);
 hipError_t launch_tiny_gate_up(const beam_shape &s, const RouteOpts &opt, const void *x,
                                const float *router_logits, const float *mask_logits,
@@ -142,8 +142,10 @@ hipError_t launch_shared_gate(const beam_shape &s, const void *x, const void *w_
 hipError_t launch_topk_mask(const beam_shape &s, const float *router_logits,
                             const float *mask_logits, const float *b_router, const float *b_mask,
                             int row_stride, const RouteOpts &opt, int32_t *topk_ids,
-                            float *topk_w, int32_t *masked_ids, hipStream_t st);
+                            float *topk_w, int32_t *masked_ids, hipStream_t st, int n_parts = 1);
 bool logits_tiled_supported(const beam_shape &s);
+// parts the tiled logits GEMM cuts its reduction into (its output is that many [T,2N] arrays)
+int logits_split_k(const beam_shape &s);
 hipError_t launch_logits_tiled(const beam_shape &s, const void *x, const void *w_router,
                                const void *w_mask, void *packed_heads, float *logits2,
                                hipStream_t st);

@@ -533,24 +533,28 @@ constexpr int kLogitsKS = 8;
 
 __global__ __launch_bounds__(256, 2) void logits_tile_kernel(
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ packed_heads,
-    float *__restrict__ logits2, int Tn, int H, int N2) {
+    float *__restrict__ logits2, int Tn, int H, int N2, int k_split) {
     __shared__ u32x4 As[2 * kLogitsM * 2 * kLogitsKS];
     const int nct = (N2 + kTileN - 1) / kTileN;
-    const int n_work = ((Tn + kLogitsM - 1) / kLogitsM) * nct;
+    const int n_base = ((Tn + kLogitsM - 1) / kLogitsM) * nct;
+    const int n_work = n_base * k_split;
     auto next_item = [&](int &round, TileItem &it) -> bool {
-        const int item = blockIdx.x + round * gridDim.x;
-        if (item >= n_work) return false;
+        const int item_s = blockIdx.x + round * gridDim.x;
+        if (item_s >= n_work) return false;
+        const int slice = item_s / n_base;
+        const int item = item_s - slice * n_base;
         const int tile = item / nct;
         it.e = 0;
         it.row0 = tile * kLogitsM;
         it.row_end = Tn;
         it.col_tile = item - tile * nct;
-        it.slice = 0;
+        it.slice = slice;
         return true;
     };
     // down-GEMM roles: output width N2, reduction length H, a single expert
     ffn_tile_run<kLogitsM, kWavesM, kLogitsKS, false, true, true, true>(
-        As, x, packed_heads, nullptr, nullptr, logits2, N2, 1, H, false, 1, 0, next_item);
+        As, x, packed_heads, nullptr, nullptr, logits2, N2, 1, H, false, k_split,
+        (size_t)Tn * N2, next_item);
 }
 
 bool logits_tiled_supported(const beam_shape &s) {
@@ -558,15 +562,32 @@ bool logits_tiled_supported(const beam_shape &s) {
            (long)s.T * s.H < (1L << 32);
 }
 
+// With 64-row tiles and at most two column tiles a batch of a few thousand tokens gives
+// fewer items than CUs, and an item is one latency chain per K-step (load the x tile,
+// store it to LDS, barrier, multiply).  Cutting the reduction into parts gives every CU
+// an item: each part writes its own [T,2N] array and every reader of the logits adds the
+// parts in order (LogitParts).  Up to one item per CU: beyond that (measured at 512
+// items) the kernel gains nothing, all workgroups pull the same 1 MB of head weights
+// through L2, and the readers pay for the extra parts.
+int logits_split_k(const beam_shape &s) {
+    if (!logits_tiled_supported(s)) return 1;
+    const long items = ((s.T + kLogitsM - 1) / kLogitsM) * ((2L * s.N + kTileN - 1) / kTileN);
+    int k = 1;
+    while (k < 4 && items * k * 2 <= 256 && (s.H / (16 * kLogitsKS)) % (2 * k) == 0) k *= 2;
+    return k;
+}
+
 hipError_t launch_logits_tiled(const beam_shape &s, const void *x, const void *w_router,
                                const void *w_mask, void *packed_heads, float *logits2,
                                hipStream_t st) {
     pack_heads_kernel<<<256, 256, 0, st>>>((const uint4 *)w_router, (const uint4 *)w_mask,
                                            (uint4 *)packed_heads, s.N, s.H);
-    const int n_work = ((s.T + kLogitsM - 1) / kLogitsM) * ((2 * s.N + kTileN - 1) / kTileN);
+    const int k_split = logits_split_k(s);
+    const int n_work =
+        ((s.T + kLogitsM - 1) / kLogitsM) * ((2 * s.N + kTileN - 1) / kTileN) * k_split;
     const int grid = n_work < 512 ? n_work : 512;
     logits_tile_kernel<<<grid, 256, 0, st>>>((const bf16_t *)x, (const bf16_t *)packed_heads,
-                                             logits2, s.T, s.H, 2 * s.N);
+                                             logits2, s.T, s.H, 2 * s.N, k_split);
     return hipGetLastError();
 }
 

@@ -201,12 +201,12 @@ hipError_t launch_logits(const beam_shape &s, const void *x, const void *w_route
 __global__ __launch_bounds__(256) void split_logits_kernel(
     const float *__restrict__ logits2, const float *__restrict__ b_router,
     const float *__restrict__ b_mask, float *__restrict__ router_logits,
-    float *__restrict__ mask_logits, int Tn, int N) {
+    float *__restrict__ mask_logits, int Tn, int N, LogitParts parts) {
     const size_t total = (size_t)Tn * 2 * N;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
         const int c = (int)(i % (2 * N));
         const size_t t = i / (2 * N);
-        const float v = logits2[i];
+        const float v = sum_parts(logits2 + i, parts);
         if (c < N) {
             if (router_logits) router_logits[t * N + c] = b_router ? v + b_router[c] : v;
         } else {
@@ -217,11 +217,14 @@ __global__ __launch_bounds__(256) void split_logits_kernel(
 
 hipError_t launch_split_logits(const beam_shape &s, const float *logits2, const float *b_router,
                                const float *b_mask, float *router_logits, float *mask_logits,
-                               hipStream_t st) {
+                               hipStream_t st, int n_parts) {
+    LogitParts parts;
+    parts.n = n_parts;
+    parts.stride = (size_t)s.T * 2 * s.N;
     const size_t total = (size_t)s.T * 2 * s.N;
     const int grid = (int)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
     split_logits_kernel<<<grid, 256, 0, st>>>(logits2, b_router, b_mask, router_logits,
-                                              mask_logits, s.T, s.N);
+                                              mask_logits, s.T, s.N, parts);
     return hipGetLastError();
 }
 
@@ -271,14 +274,14 @@ __global__ __launch_bounds__(256) void topk_mask_kernel(
     const float *__restrict__ router_logits, const float *__restrict__ mask_logits,
     const float *__restrict__ b_router, const float *__restrict__ b_mask, int row_stride,
     const float *__restrict__ g_shared, float param, int32_t *__restrict__ topk_ids,
-    float *__restrict__ topk_w, int32_t *__restrict__ masked_ids, int Tn, int N, int K, int S) {
+    float *__restrict__ topk_w, int32_t *__restrict__ masked_ids, int Tn, int N, int K, int S, LogitParts parts) {
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= Tn) return;  // wave-uniform
     const size_t f = (size_t)t * (K + S);
     const float gs = (S > 0 && g_shared) ? g_shared[t] : 1.0f;
     wave_route_token<RULE>(router_logits + (size_t)t * row_stride,
                            mask_logits + (size_t)t * row_stride, b_router, b_mask, N, K, S, gs,
-                           param, topk_ids + f, topk_w + f, masked_ids + f);
+                           param, topk_ids + f, topk_w + f, masked_ids + f, parts);
 }
 
 // Large batches: four tokens per wavefront (one per 16-lane row), 16 per workgroup.
@@ -287,7 +290,7 @@ __global__ __launch_bounds__(256) void topk_mask_rows_kernel(
     const float *__restrict__ router_logits, const float *__restrict__ mask_logits,
     const float *__restrict__ b_router, const float *__restrict__ b_mask, int row_stride,
     const float *__restrict__ g_shared, float param, int32_t *__restrict__ topk_ids,
-    float *__restrict__ topk_w, int32_t *__restrict__ masked_ids, int Tn, int N, int K, int S) {
+    float *__restrict__ topk_w, int32_t *__restrict__ masked_ids, int Tn, int N, int K, int S, LogitParts parts) {
     const int t = blockIdx.x * 16 + (threadIdx.x >> 4);
     const bool valid = t < Tn;
     const int tc = valid ? t : Tn - 1;
@@ -295,7 +298,7 @@ __global__ __launch_bounds__(256) void topk_mask_rows_kernel(
     const float gs = (S > 0 && g_shared) ? g_shared[tc] : 1.0f;
     row_route_token<NPL, RULE>(router_logits + (size_t)tc * row_stride,
                                mask_logits + (size_t)tc * row_stride, b_router, b_mask, N, K, S,
-                               gs, param, valid, topk_ids + f, topk_w + f, masked_ids + f);
+                               gs, param, valid, topk_ids + f, topk_w + f, masked_ids + f, parts);
 }
 
 // Logits live as two [T,N] arrays that already include the biases, or (row_stride
@@ -306,7 +309,7 @@ static hipError_t launch_topk_rule(const beam_shape &s, const float *router_logi
                                    const float *mask_logits, const float *b_router,
                                    const float *b_mask, int row_stride, const RouteOpts &opt,
                                    int32_t *topk_ids, float *topk_w, int32_t *masked_ids,
-                                   hipStream_t st) {
+                                   hipStream_t st, LogitParts parts) {
     // The row variant does four tokens per wavefront at about the cost of one; the
     // wave variant has the shorter latency chain for decode-sized batches.
     const bool aligned = ((uintptr_t)router_logits | (uintptr_t)mask_logits |
@@ -314,7 +317,7 @@ static hipError_t launch_topk_rule(const beam_shape &s, const float *router_logi
     const int S = opt.S;
 #define BEAM_TOPK_ARGS                                                                          \
     router_logits, mask_logits, b_router, b_mask, row_stride, opt.g_shared, opt.param,          \
-        topk_ids, topk_w, masked_ids, s.T, s.N, s.K, S
+        topk_ids, topk_w, masked_ids, s.T, s.N, s.K, S, parts
     if (s.T >= 512 && s.K + S <= 16 && s.N % 4 == 0 && row_stride % 4 == 0 && s.N <= 256 &&
         aligned) {
         dim3 grid((s.T + 15) / 16);
@@ -332,12 +335,16 @@ static hipError_t launch_topk_rule(const beam_shape &s, const float *router_logi
 hipError_t launch_topk_mask(const beam_shape &s, const float *router_logits,
                             const float *mask_logits, const float *b_router, const float *b_mask,
                             int row_stride, const RouteOpts &opt, int32_t *topk_ids,
-                            float *topk_w, int32_t *masked_ids, hipStream_t st) {
+                            float *topk_w, int32_t *masked_ids, hipStream_t st, int n_parts) {
+    LogitParts parts;   // parts of a [T, row_stride] array each
+    parts.n = n_parts;
+    parts.stride = (size_t)s.T * row_stride;
     if (opt.rule == kRuleCumProb)
         return launch_topk_rule<kRuleCumProb>(s, router_logits, mask_logits, b_router, b_mask,
-                                              row_stride, opt, topk_ids, topk_w, masked_ids, st);
+                                              row_stride, opt, topk_ids, topk_w, masked_ids, st,
+                                              parts);
     return launch_topk_rule<kRuleMask>(s, router_logits, mask_logits, b_router, b_mask,
-                                       row_stride, opt, topk_ids, topk_w, masked_ids, st);
+                                       row_stride, opt, topk_ids, topk_w, masked_ids, st, parts);
 }
 
 }  // namespace beam

@@ -77,6 +77,28 @@ __device__ __forceinline__ float key_logit(uint64_t key) {
 constexpr int kRuleMask = 0;
 constexpr int kRuleCumProb = 1;
 
+// The logits may arrive as several arrays of partial sums (a logits GEMM whose
+// reduction was cut into parts): part p of an entry sits p * stride floats after
+// part 0.  The parts are added in order wherever logits are read, so every
+// reader sees the same fp32 value.
+struct LogitParts {
+    int n = 1;
+    size_t stride = 0;
+};
+__device__ __forceinline__ float sum_parts(const float *p, LogitParts parts) {
+    float v = p[0];
+    for (int q = 1; q < parts.n; ++q) v += p[q * parts.stride];
+    return v;
+}
+__device__ __forceinline__ float4 sum_parts4(const float *p, LogitParts parts) {
+    float4 v = *(const float4 *)p;
+    for (int q = 1; q < parts.n; ++q) {
+        const float4 u = *(const float4 *)(p + q * parts.stride);
+        v.x += u.x, v.y += u.y, v.z += u.z, v.w += u.w;
+    }
+    return v;
+}
+
 template <int RULE>
 __device__ __forceinline__ void wave_route_token(const float *__restrict__ r,
                                                  const float *__restrict__ a,
@@ -85,7 +107,8 @@ __device__ __forceinline__ void wave_route_token(const float *__restrict__ r,
                                                  int S, float g_shared, float param,
                                                  int32_t *__restrict__ ids_out,
                                                  float *__restrict__ w_out,
-                                                 int32_t *__restrict__ masked_out) {
+                                                 int32_t *__restrict__ masked_out,
+                                                 LogitParts parts = LogitParts()) {
     const int lane = threadIdx.x & 63;
     uint64_t key[4];
     float logit[4];
@@ -95,8 +118,9 @@ __device__ __forceinline__ void wave_route_token(const float *__restrict__ r,
         key[i] = 0ull;
         logit[i] = -INFINITY;
         if (e < N) {
-            const float rv = br ? r[e] + br[e] : r[e];
-            const float av = bm ? a[e] + bm[e] : a[e];
+            const float r0 = sum_parts(r + e, parts), a0 = sum_parts(a + e, parts);
+            const float rv = br ? r0 + br[e] : r0;
+            const float av = bm ? a0 + bm[e] : a0;
             key[i] = topk_key(rv, e, av >= param);
             logit[i] = rv;
         }
@@ -172,7 +196,8 @@ __device__ __forceinline__ int row_route_token(const float *__restrict__ r,
                                                 int S, float g_shared, float param, bool valid,
                                                 int32_t *__restrict__ ids_out,
                                                 float *__restrict__ w_out,
-                                                int32_t *__restrict__ masked_out) {
+                                                int32_t *__restrict__ masked_out,
+                                               LogitParts parts = LogitParts()) {
     static_assert(NPL % 4 == 0, "candidates are loaded four at a time");
     const int j = threadIdx.x & 15;
     uint64_t key[NPL];
@@ -183,8 +208,8 @@ __device__ __forceinline__ int row_route_token(const float *__restrict__ r,
         float4 rv = make_float4(0.f, 0.f, 0.f, 0.f), av = rv;
         const bool in = valid && e0 < N;  // N % 4 == 0: a group of four is all in or all out
         if (in) {
-            rv = *(const float4 *)(r + e0);
-            av = *(const float4 *)(a + e0);
+            rv = sum_parts4(r + e0, parts);
+            av = sum_parts4(a + e0, parts);
             if (br) {
                 const float4 b = *(const float4 *)(br + e0);
                 rv.x += b.x, rv.y += b.y, rv.z += b.z, rv.w += b.w;
