@@ -126,10 +126,10 @@ def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp, packed
     return {
         "workload": f"{cfg.name} T={T} keep={cfg.keep}", "T": T, "P": P, "U": U,
         "weights": "packed" if packed else "plain",
-        # 6 stages; the multi-chunk grouping is 4 launches, the tiled logits GEMM repacks the
+        # 6 stages; the grouping of more than 8192 pairs is 4 launches, the tiled logits GEMM repacks the
         # heads first, a gated shared expert adds one; up to 32 tokens Top-K and grouping are
         # one launch; tiny batches take the three-kernel path
-        "kernels_per_layer": (3 if tiny else 6 + (3 if T * (cfg.K + S) > 512 else 0) + (
+        "kernels_per_layer": (3 if tiny else 6 + (3 if T * (cfg.K + S) > 8192 else 0) + (
             1 if T > 512 and cfg.dtype == "bf16" and cfg.H % 256 == 0 else 0) - (
             1 if T <= 32 and T * (cfg.K + S) <= 512 and cfg.K + S <= 16 and cfg.N % 4 == 0
             else 0)) + (1 if gate is not None else 0),

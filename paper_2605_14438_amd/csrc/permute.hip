@@ -72,7 +72,8 @@ __global__ __launch_bounds__(64) void count_kernel(const int32_t *__restrict__ m
     for (int e = lane; e < N; e += 64) blk_counts[(size_t)e * gridDim.x + blockIdx.x] = hist[e];
 }
 
-// Work list from the per-expert counts (thread e owns expert e; 256 threads).
+// Work list from the per-expert counts (thread e < 256 owns expert e; threads past
+// 256, if any, pass e >= N and count 0 and help with the barriers and the tile list).
 // The row tiles are written by all threads together, tile t by thread t % 256,
 // which finds its expert by bisection over the tile prefix: with a skewed router
 // one expert can own most of the tiles, and its thread would otherwise write
@@ -92,10 +93,12 @@ __device__ __forceinline__ void emit_work_list(int e, int N, int count, int offs
     if (threadIdx.x == 0) wl.hdr[0] = total;
     const int nt = e < N ? tiles_of(count) : 0;
     const int tbase = block_exclusive_scan_256(nt, scratch, &total);
-    tile_end[e] = tbase + nt;
-    row_beg[e] = offset;
+    if (threadIdx.x < 256) {
+        tile_end[e] = tbase + nt;
+        row_beg[e] = offset;
+    }
     __syncthreads();
-    for (int t = threadIdx.x; t < total; t += 256) {
+    for (int t = threadIdx.x; t < total; t += blockDim.x) {
         int lo = 0, hi = 255;   // first expert whose tiles end after t
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
@@ -415,6 +418,96 @@ hipError_t launch_route_permute(const beam_shape &s, const float *router_logits,
     return hipGetLastError();
 }
 
+// A few thousand pairs (prefill chunks of up to about 2000 tokens): the whole counting
+// sort in one launch of one workgroup of 16 wavefronts instead of four launches, which
+// at this size are four times a launch's fixed cost.  Wavefront w owns a contiguous run
+// of 64-pair groups; it counts its pairs per expert into its own LDS row, thread e then
+// turns the rows into start positions (prefix over the wavefronts, prefix over the
+// experts, work list), and every wavefront walks its run again in order, placing each
+// kept pair at its expert's running position: stable, no atomics, same result as the
+// four-launch path.
+constexpr int kOneWgWaves = 16;
+constexpr int kOneWgGroups = 8;   // 64-pair groups per wavefront, held in registers
+constexpr int kOneWgMaxPairs = 64 * kOneWgWaves * kOneWgGroups;
+
+__global__ __launch_bounds__(64 * kOneWgWaves) void permute_one_workgroup_kernel(
+    const int32_t *__restrict__ masked_ids, int32_t *__restrict__ counts,
+    int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm,
+    int32_t *__restrict__ num_pairs, int TK, int N, WorkList wl) {
+    __shared__ int pos[kOneWgWaves][256];   // per wavefront and expert: count, then next position
+    __shared__ int scratch[256];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int groups = (TK + 63) >> 6;
+    const int per_wave = (groups + kOneWgWaves - 1) / kOneWgWaves;   // <= kOneWgGroups
+    const int f0 = wave * per_wave * 64 + lane;
+    // this wavefront's ids, all loads in flight at once; -1 past its run or past the input
+    int ids[kOneWgGroups];
+#pragma unroll
+    for (int q = 0; q < kOneWgGroups; ++q) {
+        const int f = f0 + q * 64;
+        int id = (q < per_wave && f < TK) ? masked_ids[f] : -1;
+        ids[q] = (id >= 0 && id < N) ? id : -1;
+    }
+    for (int i = tid; i < kOneWgWaves * 256; i += 64 * kOneWgWaves) (&pos[0][0])[i] = 0;
+    __syncthreads();
+    uint64_t peers[kOneWgGroups];
+#pragma unroll
+    for (int q = 0; q < kOneWgGroups; ++q) {
+        peers[q] = 0;
+        if (q >= per_wave) continue;   // uniform: small inputs use the first groups only
+        const bool valid = ids[q] >= 0;
+        peers[q] = match_id(ids[q], valid);
+        if (valid && (peers[q] & ((1ull << lane) - 1ull)) == 0)
+            pos[wave][ids[q]] += __popcll(peers[q]);
+    }
+    __syncthreads();
+    int cnt = 0;
+    if (tid < 256) {   // thread e: exclusive prefix of expert e's counts over the wavefronts
+#pragma unroll
+        for (int w = 0; w < kOneWgWaves; ++w) {
+            const int c = pos[w][tid];
+            pos[w][tid] = cnt;
+            cnt += c;
+        }
+    }
+    int total;
+    const int excl = block_exclusive_scan_256(cnt, scratch, &total);
+    if (tid < 256) {
+#pragma unroll
+        for (int w = 0; w < kOneWgWaves; ++w) pos[w][tid] += excl;
+        if (tid < N) {
+            counts[tid] = cnt;
+            offsets[tid] = excl;
+        }
+    }
+    if (tid == 0) {
+        offsets[N] = total;
+        *num_pairs = total;
+    }
+    emit_work_list(tid, N, cnt, excl, wl, scratch);
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kOneWgGroups; ++q) {
+        if (q >= per_wave) continue;
+        const int f = f0 + q * 64;
+        const bool valid = ids[q] >= 0;
+        const int rank = __popcll(peers[q] & ((1ull << lane) - 1ull));
+        const int base = valid ? pos[wave][ids[q]] : 0;
+        if (valid && rank == 0) pos[wave][ids[q]] = base + __popcll(peers[q]);
+        if (f < TK) {
+            if (valid) {
+                perm[base + rank] = f;
+                inv_perm[f] = base + rank;
+            } else {
+                inv_perm[f] = -1;
+            }
+            if (f >= total) perm[f] = -1;  // rows [P, T*K) carry no pair
+        }
+    }
+}
+
 hipError_t launch_permute(const beam_shape &s, const int32_t *masked_ids, int32_t *counts,
                           int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *num_pairs,
                           int32_t *blk_counts, int32_t *blk_base, int nchunk, const WorkList &wl,
@@ -423,6 +516,11 @@ hipError_t launch_permute(const beam_shape &s, const int32_t *masked_ids, int32_
     if (nchunk == 1) {
         permute_single_chunk_kernel<<<1, 256, 0, st>>>(masked_ids, counts, offsets, perm, inv_perm,
                                                        num_pairs, TK, s.N, wl);
+        return hipGetLastError();
+    }
+    if (TK <= kOneWgMaxPairs) {
+        permute_one_workgroup_kernel<<<1, 64 * kOneWgWaves, 0, st>>>(
+            masked_ids, counts, offsets, perm, inv_perm, num_pairs, TK, s.N, wl);
         return hipGetLastError();
     }
     count_kernel<<<nchunk, 64, 0, st>>>(masked_ids, blk_counts, TK, s.N);
