@@ -30,23 +30,32 @@ __device__ __forceinline__ uint64_t match_id(int id, bool valid) {
 
 // Exclusive prefix sum over 256 entries held one per thread by the first 256
 // threads of a workgroup (every thread of the workgroup must call it; threads
-// >= 256 only take part in the barriers); returns the exclusive value, *total
-// gets the sum.
-__device__ __forceinline__ int block_exclusive_scan_256(int v, int *scratch /*[256]*/, int *total) {
+// >= 256 pass 0 and only take part in the barriers); returns the exclusive
+// value, *total gets the sum.  Wavefront shuffles plus four wavefront totals in
+// scratch: two barriers.
+__device__ __forceinline__ int block_exclusive_scan_256(int v, int *scratch /*[>= 4]*/, int *total) {
     const int tid = threadIdx.x;
-    const bool in = tid < 256;
-    if (in) scratch[tid] = v;
-    __syncthreads();
-    for (int off = 1; off < 256; off <<= 1) {
-        const int add = (in && tid >= off) ? scratch[tid - off] : 0;
-        __syncthreads();
-        if (in) scratch[tid] += add;
-        __syncthreads();
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    int incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(incl, off);
+        if (lane >= off) incl += t;
     }
-    const int incl = in ? scratch[tid] : 0;
-    *total = scratch[255];
+    if (tid < 256 && lane == 63) scratch[wave] = incl;
     __syncthreads();
-    return incl - v;
+    int run = incl - v;
+    int sum = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const int s = scratch[w];
+        run += w < wave ? s : 0;
+        sum += s;
+    }
+    *total = sum;
+    __syncthreads();   // scratch may be written again
+    return tid < 256 ? run : 0;
 }
 
 // One wavefront counts the kept pairs of one chunk per expert.
