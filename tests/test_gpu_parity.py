@@ -138,9 +138,9 @@ def _run_permute(m_host, N, K):
     (65, 8, 128, 0.5), (8, 1, 8, 0.6), (63, 2, 8, 0.5), (257, 2, 8, 0.5), (1000, 8, 128, 0.15),
     (4096, 8, 128, 0.25), (16384, 8, 128, 1.0), (16384, 8, 128, 0.15), (300, 4, 60, 0.0),
     (777, 6, 256, 0.7),
-    # around the largest pair count of the single-workgroup sort (8192), ragged last group
+    # around the largest pair count of the single-workgroup sort (8192) and twice that, ragged last group
     (1024, 8, 128, 0.3), (1025, 8, 128, 0.3), (629, 13, 200, 0.5), (2730, 3, 7, 1.0),
-    (2048, 8, 128, 0.3), (5461, 3, 7, 1.0),
+    (2048, 8, 128, 0.3), (2049, 8, 128, 0.3), (5461, 3, 7, 1.0), (1261, 13, 200, 0.5),
 ])
 def test_permute(T, K, N, keep):
     _log(f"permute T={T} K={K} N={N} keep={keep}")
