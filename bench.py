@@ -449,8 +449,8 @@ def main():
             gg = {**hp.upload(c, dd), "w_gate_up": g["w_gate_up"], "w_down": g["w_down"]}
             points.append(measure_point(c, dd, gg, sets, psteps, 10, torch, beam, hp))
         pre = synth.CONFIGS["qwen3_prefill"]
-        for T, keep, n in ((4096, 0.15, 30), (16384, 0.15, 20), (16384, 0.25, 20), (16384, 0.5, 15),
-                           (16384, 1.0, 10)):
+        for T, keep, n in ((1024, 0.15, 30), (4096, 0.15, 30), (16384, 0.15, 20), (16384, 0.25, 20),
+                           (16384, 0.5, 15), (16384, 1.0, 10)):
             c = pre.with_(T=T, keep=keep)
             dd = synth.make_layer(c, with_experts=False)
             gg = {**hp.upload(c, dd), "w_gate_up": g["w_gate_up"], "w_down": g["w_down"]}
