@@ -16,7 +16,7 @@
  *   x [T,H]; w_router, w_mask [N,H]; w_gate_up [N,2I,H] (rows 0..I-1 gate,
  *   rows I..2I-1 up); w_down [N,H,I].
  *
- * Readings of the paper taken here (each also listed in the design notes):
+ * Readings of the paper taken here:
  *   - Top-K order: logit descending, equal logits -> lower expert index first;
  *     slot k holds the (k+1)-th ranked expert (Sec. 3.2 Step 1 leaves it open).
  *   - Routing weights: softmax over the K surviving logits (Eq. 4: softmax of
