@@ -326,7 +326,7 @@ beam_status beam_moe_forward_timed(const beam_shape *shape, const void *x, const
  * kernel's roofline fraction against.  Both only enqueue a kernel; the caller
  * times it (events on `hip_stream`).
  *   beam_probe_stream_read  reads `buf` (device, >= 64 MiB, 16-byte aligned) once
- *       with plain coalesced 16-byte loads, eight in flight per lane; writes the
+ *       with coalesced non-temporal 16-byte loads, eight in flight per lane; writes the
  *       number of bytes the kernel really reads (bytes rounded down to whole
  *       batches) to *bytes_read_host.  sink: >= 4 device bytes, left unchanged.
  *   beam_probe_mfma  runs iters x 4 back-to-back v_mfma_f32_32x32x16_bf16 per

@@ -19,6 +19,19 @@
 
 namespace beam {
 
+// Packed expert weights are read once per pass, a whole 1 KiB fragment per load
+// instruction, and never again soon: loading them with the non-temporal hint keeps
+// them from being installed in the caches on their way through, which on this GPU
+// raises a plain streaming read from 6.1 to 7.0 TB/s (decode layer from packed
+// weights 123.7 -> 114.4 us).  Not for row-major weights: there one instruction
+// takes half of each 128-byte line and the next one the other half, which the hint
+// turns into two trips to memory (123.3 -> 130.6 us).  The activation rows, which
+// every workgroup of an expert shares, keep the default policy.
+typedef uint32_t u32x4w __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x4w load_weights16v(const bf16_t *p) {
+    return __builtin_nontemporal_load((const u32x4w *)p);
+}
+
 // Rows [row_beg, row_end) of the hidden activation for the 16 gate and 16 up
 // features j0.. of expert e:  hidden[row, j] = bf16(SiLU(x_t . W_gate[j]) * (x_t . W_up[j])),
 // t = token_of(row).  The workgroup's 4 wavefronts split the reduction over H.
@@ -465,7 +478,9 @@ constexpr int kGateUpPackedChunk = 4;
 
 // hidden rows [row_beg, row_end) x the 32 features of block q of expert e; the 4
 // wavefronts split the reduction over H.  red: LDS, 3 * 32 * 64 floats.
-template <int CH, typename TokenOf>
+// STREAM: weights with the non-temporal hint (not for the single-token kernels, where
+// it measured 2 us slower per layer: a handful of workgroups, nothing to displace).
+template <int CH, bool STREAM, typename TokenOf>
 __device__ __forceinline__ void gate_up_rows_packed(const bf16_t *__restrict__ x,
                                                     const bf16_t *__restrict__ w_gate_up, int e,
                                                     int row_beg, int row_end, TokenOf token_of,
@@ -494,8 +509,13 @@ __device__ __forceinline__ void gate_up_rows_packed(const bf16_t *__restrict__ x
         auto load = [&](int b, int k) {
 #pragma unroll
             for (int j = 0; j < CH; ++j) {
-                wg[b][j] = *(const u32x4s *)(gp + (size_t)(k + j) * 512);
-                wu[b][j] = *(const u32x4s *)(up + (size_t)(k + j) * 512);
+                if constexpr (STREAM) {
+                    wg[b][j] = load_weights16v(gp + (size_t)(k + j) * 512);
+                    wu[b][j] = load_weights16v(up + (size_t)(k + j) * 512);
+                } else {
+                    wg[b][j] = *(const u32x4s *)(gp + (size_t)(k + j) * 512);
+                    wu[b][j] = *(const u32x4s *)(up + (size_t)(k + j) * 512);
+                }
             }
 #pragma unroll
             for (int j = 0; j < CH; ++j) xv[b][j] = *(const u32x4s *)(xp + (k + j) * 16);
@@ -577,7 +597,7 @@ __global__ __launch_bounds__(256, 2) void gate_up_stream_packed_kernel(
     const int row_end = wl.active_end[u];
     if (u >= n_active) return;
     __shared__ float red[3 * 32 * 64];
-    gate_up_rows_packed<kGateUpPackedChunk>(x, w_gate_up, e, row_beg, row_end,
+    gate_up_rows_packed<kGateUpPackedChunk, true>(x, w_gate_up, e, row_beg, row_end,
                                             [&](int row) { return perm[row] / K; }, hidden, H, I,
                                             blockIdx.x, red);
 }
@@ -605,7 +625,7 @@ __device__ __forceinline__ void down_rows_packed(const bf16_t *__restrict__ hidd
         auto load = [&](int b, int k) {
 #pragma unroll
             for (int j = 0; j < CH; ++j) {
-                w[b][j] = *(const u32x4s *)(wp + (size_t)(k + j) * 512);
+                w[b][j] = load_weights16v(wp + (size_t)(k + j) * 512);
                 hv[b][j] = *(const u32x4s *)(hp + (k + j) * 16);
             }
         };
@@ -682,7 +702,7 @@ __global__ __launch_bounds__(256, 2) void gate_up_slot_packed_kernel(
     __syncthreads();
     const int e = masked_s[f - t * slots];
     if (e < 0) return;  // uniform over the workgroup
-    gate_up_rows_packed<kGateUpPackedChunk>(x, w_gate_up, e, f, f + 1, [&](int) { return t; },
+    gate_up_rows_packed<kGateUpPackedChunk, false>(x, w_gate_up, e, f, f + 1, [&](int) { return t; },
                                             hidden, H, I, blockIdx.x, red);
 }
 
