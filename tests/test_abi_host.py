@@ -61,6 +61,20 @@ def test_workspace_bytes(lib):
     assert beam.beam_workspace_bytes(beam.make_shape(4, 256, 512, 2, 512, beam.BEAM_F32)) == 0
 
 
+def test_workspace_covers_the_split_reductions(lib):
+    """Shapes whose fused layer cuts a reduction into parts need one array per part:
+    the down projection of few experts with a long reduction (four [T*K,H] arrays) and
+    the prefill logits GEMM with fewer items than CUs (up to four [T,2N] arrays)."""
+    T, H, N, K, I = 512, 4096, 8, 2, 14336                    # Mixtral-shaped, packed
+    s = beam.make_shape(T, H, N, K, I, beam.BEAM_BF16, binding.BEAM_WEIGHTS_PACKED)
+    assert beam.beam_workspace_bytes(s) >= 4 * T * K * H * 4 + T * K * I * 2
+    # four times the tokens: more than 512 down-GEMM items possible, the reduction stays whole
+    s4 = beam.make_shape(4 * T, H, N, K, I, beam.BEAM_BF16, binding.BEAM_WEIGHTS_PACKED)
+    assert beam.beam_workspace_bytes(s4) < 2 * (4 * T) * K * (H * 4 + I * 2)
+    q = beam.make_shape(1024, 2048, 128, 8, 768, beam.BEAM_BF16)   # 16 logits items -> 4 parts
+    assert beam.beam_workspace_bytes(q) >= 4 * 1024 * 256 * 4 + 1024 * 8 * (2048 * 4 + 768 * 2)
+
+
 @pytest.mark.parametrize("shape,code", [
     ((-1, 256, 8, 2, 512, 0), binding.BEAM_ERR_INVALID_ARG),
     ((4, 256, 8, 0, 512, 0), binding.BEAM_ERR_INVALID_ARG),
