@@ -15,6 +15,11 @@
 namespace beam {
 
 __device__ __forceinline__ float4 ld4(const float *p) { return *(const float4 *)p; }
+typedef float f32x4t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 ld4_stream(const float *p) {
+    const f32x4t v = __builtin_nontemporal_load((const f32x4t *)p);
+    return make_float4(v.x, v.y, v.z, v.w);
+}
 __device__ __forceinline__ float4 ld4(const bf16_t *p) {
     const uint2 q = *(const uint2 *)p;
     return make_float4(__uint_as_float(q.x << 16), __uint_as_float(q.x & 0xffff0000u),
@@ -42,7 +47,7 @@ __global__ __launch_bounds__(256) void mask_grad_pairs_kernel(
             const float *y = y_pairs + (size_t)row * H;
             for (int h = lane * 4; h < H; h += 256) {
                 const float4 a = ld4(dy + h);
-                const float4 b = ld4(y + h);
+                const float4 b = ld4_stream(y + h);   // read once, larger than the caches
                 dot = fmaf(a.x, b.x, dot);
                 dot = fmaf(a.y, b.y, dot);
                 dot = fmaf(a.z, b.z, dot);
