@@ -251,7 +251,8 @@ beam_status beam_moe_forward_rule(const beam_shape *shape, const beam_rule *rule
  *   w_shared_gate  [H] dtype or NULL.  The paper gives no formula for g_sh: NULL
  *                  means g_sh = 1, otherwise g_sh[t] = sigma(x_t . w_shared_gate).
  *                  Must be NULL when S = 0.
- *   residual       [T,H] dtype or NULL (no residual term); must not overlap out.
+ *   residual       [T,H] dtype or NULL (no residual term); its bytes must not overlap
+ *                  those of out (BEAM_ERR_INVALID_ARG otherwise).
  *                  The sum starts from h in fp32 and is rounded once.
  *   *_opt          as in beam_moe_forward but with K+S slots per token:
  *                  [T,K+S]; slots K .. K+S-1 are the shared blocks (ids N .. N+S-1,
@@ -262,6 +263,17 @@ beam_status beam_moe_forward_rule(const beam_shape *shape, const beam_rule *rule
  * (0 = invalid or unsupported; N+S <= 256 and K+S <= 64).
  */
 size_t beam_block_workspace_bytes(const beam_shape *shape, int32_t num_shared);
+/*
+ * Host-only query, for callers and tests that audit the workspace: where the fused
+ * entry points keep the fp32 router and mask logits of Sec. 3.2 Step 1 (Eq. 5) inside
+ * a workspace of beam_block_workspace_bytes(shape, num_shared) bytes.  Writes the
+ * region's byte offset and size and the number of [T,2N] arrays of partial sums it has
+ * room for (a prefill-sized logits product may cut its reduction into that many parts).
+ * Nothing is enqueued.  Errors as beam_block_workspace_bytes (status instead of 0).
+ */
+beam_status beam_workspace_logits_region(const beam_shape *shape, int32_t num_shared,
+                                         size_t *offset_host, size_t *bytes_host,
+                                         int32_t *parts_host);
 beam_status beam_moe_block_forward(const beam_shape *shape, int32_t num_shared, const void *x,
                                    const void *w_router, const float *router_bias,
                                    const void *w_mask, const float *mask_bias,

@@ -31,7 +31,7 @@ EXPORTS = ("beam_abi_version", "beam_status_string", "beam_workspace_bytes", "be
            "beam_moe_forward_timed", "beam_pack_weights", "beam_block_workspace_bytes",
            "beam_moe_block_forward", "beam_moe_block_forward_timed", "beam_route_rule",
            "beam_moe_forward_rule", "beam_mask_router_backward", "beam_probe_stream_read",
-           "beam_probe_mfma")
+           "beam_probe_mfma", "beam_workspace_logits_region")
 BEAM_RULE_MASK = 0
 BEAM_RULE_CUMPROB = 1
 BEAM_NUM_STAGES = 6
@@ -98,6 +98,10 @@ def load() -> ctypes.CDLL:
         lib.beam_probe_mfma.argtypes = [ctypes.c_int32, vp, vp, ctypes.POINTER(ctypes.c_double)]
         lib.beam_block_workspace_bytes.restype = sz
         lib.beam_block_workspace_bytes.argtypes = [sp, ctypes.c_int32]
+        lib.beam_workspace_logits_region.restype = ctypes.c_int
+        lib.beam_workspace_logits_region.argtypes = [sp, ctypes.c_int32, ctypes.POINTER(sz),
+                                                     ctypes.POINTER(sz),
+                                                     ctypes.POINTER(ctypes.c_int32)]
         lib.beam_moe_block_forward.restype = ctypes.c_int
         lib.beam_moe_block_forward.argtypes = [sp, ctypes.c_int32] + [vp] * 15 + [sz, vp]
         lib.beam_moe_block_forward_timed.restype = ctypes.c_int
@@ -210,6 +214,15 @@ def beam_moe_forward(shape, x, w_router, router_bias, w_mask, mask_bias, w_gate_
 def beam_block_workspace_bytes(shape, num_shared: int) -> int:
     s = _shape(shape)
     return int(load().beam_block_workspace_bytes(ctypes.byref(s), int(num_shared)))
+
+
+def beam_workspace_logits_region(shape, num_shared: int, check: bool = True):
+    """Returns (status, byte offset, bytes, parts) of the logits region of the workspace."""
+    s = _shape(shape)
+    off, nb, parts = ctypes.c_size_t(0), ctypes.c_size_t(0), ctypes.c_int32(0)
+    st = load().beam_workspace_logits_region(ctypes.byref(s), int(num_shared), ctypes.byref(off),
+                                             ctypes.byref(nb), ctypes.byref(parts))
+    return _check("beam_workspace_logits_region", st, check), off.value, nb.value, parts.value
 
 
 def beam_moe_block_forward(shape, num_shared, x, w_router, router_bias, w_mask, mask_bias,

@@ -62,7 +62,9 @@ static int down_split_k(const beam_shape &s) {
     return (s.I / 64) % k_split == 0 ? k_split : 1;   // whole 64-wide K-steps per part
 }
 
-WsLayout ws_layout(const beam_shape &s) {
+// `s` counts every expert and slot the grouped kernels see; the last S of them are the
+// shared experts appended by the block entry point, which the router never scores.
+WsLayout ws_layout(const beam_shape &s, int S) {
     WsLayout L;
     const size_t T = (size_t)s.T, N = (size_t)s.N, K = (size_t)s.K;
     const size_t TK = T * K;
@@ -76,9 +78,18 @@ WsLayout ws_layout(const beam_shape &s) {
         off = align_up(off + bytes);
         return at;
     };
-    // one allocation: the prefill logits kernel writes them as a single [T,2N] array
-    L.router_logits = take(2 * T * N * 4 * logits_split_k(s));   // one [T,2N] array per part
-    L.mask_logits = L.router_logits + T * N * 4;
+    // one allocation: the prefill logits kernel writes them as a single [T,2N] array, one
+    // per part of its reduction.  The logits GEMM and Top-K run on the routed experts only
+    // and cut the reduction by THEIR column count (2 * (N - S) can fit one column tile where
+    // 2 * N needs two, which doubles the parts), so the parts are counted for that shape.
+    beam_shape routed = s;
+    routed.N = s.N - S;
+    routed.K = s.K - S;
+    const int parts_routed = logits_split_k(routed), parts_all = logits_split_k(s);
+    L.logit_parts = parts_routed > parts_all ? parts_routed : parts_all;
+    L.router_logits = take(2 * T * N * 4 * (size_t)L.logit_parts);
+    L.router_logits_bytes = off - L.router_logits;
+    L.mask_logits = L.router_logits + T * (N - S) * 4;
     L.packed_heads = take((2 * N + 255) / 256 * 256 * (size_t)s.H * esz);  // padded to a column tile
     L.topk_ids = take(TK * 4);
     L.topk_w = take(TK * 4);
@@ -387,7 +398,13 @@ static beam_status moe_forward_impl(const beam_shape *shape, int S, const beam_r
         misaligned(w_shared_gate))
         return BEAM_ERR_INVALID_ARG;
     if (w_shared_gate && S == 0) return BEAM_ERR_INVALID_ARG;
-    const WsLayout L = ws_layout(se);
+    if (residual) {
+        // both are __restrict__ in the kernels: the byte ranges must not overlap
+        const size_t nbytes = (size_t)s.T * s.H * (s.dtype == BEAM_BF16 ? 2 : 4);
+        const uintptr_t r0 = (uintptr_t)residual, o0 = (uintptr_t)out;
+        if (r0 < o0 + nbytes && o0 < r0 + nbytes) return BEAM_ERR_INVALID_ARG;
+    }
+    const WsLayout L = ws_layout(se, S);
     st = check_ws(se, workspace, workspace_bytes, L);
     if (st != BEAM_OK) return st;
     if (s.T == 0) return BEAM_OK;
@@ -500,7 +517,23 @@ size_t beam_block_workspace_bytes(const beam_shape *shape, int32_t num_shared) {
     se.K += num_shared;
     if (se.N > 256 || se.K > 64 || (long)se.T * se.K >= (1L << 24)) return 0;
     if (se.weight_layout == BEAM_WEIGHTS_PACKED && !tiled_ffn_supported(se)) return 0;
-    return ws_layout(se).total;
+    return ws_layout(se, num_shared).total;
+}
+
+beam_status beam_workspace_logits_region(const beam_shape *shape, int32_t num_shared,
+                                         size_t *offset_host, size_t *bytes_host,
+                                         int32_t *parts_host) {
+    if (!offset_host || !bytes_host || !parts_host) return BEAM_ERR_INVALID_ARG;
+    if (beam_block_workspace_bytes(shape, num_shared) == 0)
+        return check_shape(shape) != BEAM_OK ? check_shape(shape) : BEAM_ERR_UNSUPPORTED;
+    beam_shape se = *shape;
+    se.N += num_shared;
+    se.K += num_shared;
+    const WsLayout L = ws_layout(se, num_shared);
+    *offset_host = L.router_logits;
+    *bytes_host = L.router_logits_bytes;
+    *parts_host = L.logit_parts;
+    return BEAM_OK;
 }
 
 beam_status beam_moe_block_forward(const beam_shape *shape, int32_t num_shared, const void *x,

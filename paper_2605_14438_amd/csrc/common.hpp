@@ -85,10 +85,12 @@ struct WsLayout {
     size_t y_pairs;        // [T*K, H] f32
     size_t tile_partial;   // [max_tiles, H] f32 : per-tile sums of the mask-router backward
     size_t total;
+    size_t router_logits_bytes;  // size of the logits region (router + mask, every part)
+    int logit_parts;             // [T,2N] arrays the region has room for
     int nchunk;
     int max_tiles;
 };
-WsLayout ws_layout(const beam_shape &s);
+WsLayout ws_layout(const beam_shape &s, int S = 0);
 
 // Work list written on the device after the prefix sums:
 //   hdr[0] = number of experts with at least one kept pair (U)
@@ -107,6 +109,14 @@ struct WorkList {
     int32_t *tile_row0;
 };
 WorkList work_list(void *base, const beam_shape &s, int max_tiles);
+
+// Between the launches of a multi-kernel sequence: return at the first launch that
+// failed (a later successful launch may clear what hipGetLastError reports).
+#define BEAM_CHECK_LAUNCH()                                   \
+    do {                                                      \
+        const hipError_t launch_err_ = hipGetLastError();     \
+        if (launch_err_ != hipSuccess) return launch_err_;    \
+    } while (0)
 
 // ---- launchers (each returns hipGetLastError() after enqueueing) ----------
 // What the Top-K stage appends and decides beyond Eq. 4: S shared-expert slots

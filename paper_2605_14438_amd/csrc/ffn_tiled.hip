@@ -582,6 +582,7 @@ hipError_t launch_logits_tiled(const beam_shape &s, const void *x, const void *w
                                hipStream_t st) {
     pack_heads_kernel<<<256, 256, 0, st>>>((const uint4 *)w_router, (const uint4 *)w_mask,
                                            (uint4 *)packed_heads, s.N, s.H);
+    BEAM_CHECK_LAUNCH();
     const int k_split = logits_split_k(s);
     const int n_work =
         ((s.T + kLogitsM - 1) / kLogitsM) * ((2 * s.N + kTileN - 1) / kTileN) * k_split;
@@ -627,6 +628,7 @@ hipError_t launch_pack_weights(const beam_shape &s, const void *w_gate_up, const
     pack_weights_kernel<true><<<4096, 256, 0, st>>>((const uint4 *)w_gate_up,
                                                     (uint4 *)w_gate_up_packed, s.N, 2 * s.I, s.H,
                                                     s.I);
+    BEAM_CHECK_LAUNCH();
     pack_weights_kernel<false><<<4096, 256, 0, st>>>((const uint4 *)w_down, (uint4 *)w_down_packed,
                                                      s.N, s.H, s.I, s.I);
     return hipGetLastError();

@@ -533,8 +533,11 @@ hipError_t launch_permute(const beam_shape &s, const int32_t *masked_ids, int32_
         return hipGetLastError();
     }
     count_kernel<<<nchunk, 64, 0, st>>>(masked_ids, blk_counts, TK, s.N);
+    BEAM_CHECK_LAUNCH();
     chunk_prefix_kernel<<<s.N, 256, 0, st>>>(blk_counts, blk_base, counts, nchunk);
+    BEAM_CHECK_LAUNCH();
     scan_kernel<<<1, 256, 0, st>>>(counts, offsets, num_pairs, s.N, wl);
+    BEAM_CHECK_LAUNCH();
     scatter_kernel<<<nchunk, 64, 0, st>>>(masked_ids, offsets, blk_base, perm, inv_perm, TK, s.N);
     return hipGetLastError();
 }

@@ -157,15 +157,18 @@ hipError_t launch_mask_router_backward(const beam_shape &s, const void *x,
         mask_grad_pairs_kernel<bf16_t><<<s.T, 256, 0, st>>>(
             topk_ids, topk_w, mask_logits, y_pairs, inv_perm, (const bf16_t *)grad_out, rk, grad_a,
             loss_reg, s.H, s.N, s.K);
+        BEAM_CHECK_LAUNCH();
         mask_grad_w_partial_kernel<bf16_t><<<gp, 64, 0, st>>>((const bf16_t *)x, grad_a, perm,
                                                                offsets, wl, partial, s.H, s.K);
     } else {
         mask_grad_pairs_kernel<float><<<s.T, 256, 0, st>>>(
             topk_ids, topk_w, mask_logits, y_pairs, inv_perm, (const float *)grad_out, rk, grad_a,
             loss_reg, s.H, s.N, s.K);
+        BEAM_CHECK_LAUNCH();
         mask_grad_w_partial_kernel<float><<<gp, 64, 0, st>>>((const float *)x, grad_a, perm,
                                                               offsets, wl, partial, s.H, s.K);
     }
+    BEAM_CHECK_LAUNCH();
     mask_grad_w_reduce_kernel<<<gr, 64, 0, st>>>(partial, offsets, grad_w_mask, s.H, s.N);
     return hipGetLastError();
 }

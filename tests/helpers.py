@@ -1,8 +1,8 @@
 """Shared plumbing of the GPU parity tests: upload of synthetic layers, the
 guard-band redraw that makes index comparisons well posed, and the output
 tolerance.  Uses the oracle (test infrastructure) and the binding; expected
-values come from the oracle only (the one formula evaluated here is the error
-model of hidden_rounding_allowance, which widens a bound and checks nothing)."""
+values come from the oracle only, the hidden activation inside the error model
+of hidden_rounding_allowance included."""
 from __future__ import annotations
 
 import numpy as np
@@ -113,14 +113,16 @@ def block_forward(cfg, d, g=None, T=None, packed=False, use_gate=True, use_resid
             "masked_ids": mids.cpu().numpy(), "num_pairs": int(npairs.item())}
 
 
-def output_error(got, ref, dtype: str, allowance=None):
+def output_error(got, ref, dtype: str, allowance=None, rms=None):
     """Return (literal metric, worst ratio to the element-wise bound).
+    rms: the output RMS to use instead of that of `ref` (sampled checks pass the RMS of
+    the randomly drawn rows, so that rows picked for their size do not loosen the bound).
 
     literal metric: max|got-ref| / RMS(ref over all T*H elements).
     bound, bf16:  |got-ref| <= 2e-2*RMS + 2^-8*|ref|  (the stated budget plus the
                   half-ulp no bf16 output can avoid);  fp32: 1e-4*RMS.
     allowance: optional per-element addition to the bound (see hidden_rounding_allowance)."""
-    rms = float(np.sqrt(np.mean(ref ** 2)))
+    rms = float(np.sqrt(np.mean(ref ** 2))) if rms is None else float(rms)
     err = np.abs(got - ref)
     if rms == 0.0:
         return float(err.max()), (0.0 if err.max() == 0 else np.inf)
@@ -134,6 +136,27 @@ def output_error(got, ref, dtype: str, allowance=None):
     return literal, float((err / bound).max())
 
 
+def oracle_hidden(x, w_gate_up, masked_ids):
+    """h = SiLU(x W_gate) * (x W_up) of every kept slot, [T*K, I] f64, taken from the oracle:
+    oracle.pair_outputs with a down projection that copies a block of min(I, H) hidden
+    features to the output (ones on the diagonal), one block of features at a time."""
+    N, I2, H = w_gate_up.shape
+    I = I2 // 2
+    T, K = masked_ids.shape
+    h = np.zeros((T * K, I))
+    blk = min(I, H)
+    eye = np.zeros((N, H, blk), np.float32)
+    eye[:, np.arange(blk), np.arange(blk)] = 1.0
+    for j0 in range(0, I, blk):
+        j1 = min(j0 + blk, I)
+        sel = np.zeros((N, 2 * blk, H), np.float32)
+        sel[:, :j1 - j0] = w_gate_up[:, j0:j1]
+        sel[:, blk:blk + j1 - j0] = w_gate_up[:, I + j0:I + j1]
+        y, _ = oracle.pair_outputs(x, sel, eye, masked_ids)
+        h[:, j0:j1] = y[:, :j1 - j0]
+    return h
+
+
 def hidden_rounding_allowance(cfg, d, masked_ids, topk_weights, w_gate_up=None, w_down=None):
     """What rounding h = SiLU(gate)*up to bf16 between the two projections may add to an
     output element, from the arithmetic: every h_i moves by at most 2^-9 |h_i|, uniformly
@@ -141,21 +164,75 @@ def hidden_rounding_allowance(cfg, d, masked_ids, topk_weights, w_gate_up=None, 
     six sigma of that, weighted by g_k and added over the kept slots.  At the benchmark's
     shapes this is a small part of the stated 2e-2 RMS and the tests there do without it;
     for narrow layers and low keep rates (small RMS) it can exceed it.  [T,H], zero for fp32.
-    masked_ids / topk_weights may carry appended shared-expert slots when the expert arrays
-    with the appended blocks are passed."""
+    h comes from the oracle (oracle_hidden).  masked_ids / topk_weights may carry appended
+    shared-expert slots when the expert arrays with the appended blocks are passed."""
     out = np.zeros((cfg.T, cfg.H))
     if cfg.dtype != "bf16":
         return out
     w_gate_up = d["w_gate_up"] if w_gate_up is None else w_gate_up
     w_down = d["w_down"] if w_down is None else w_down
-    x = d["x"].astype(np.float64)
     sigma = 2.0 ** -9 / np.sqrt(3.0)
-    I = cfg.I
+    h = oracle_hidden(d["x"], w_gate_up, masked_ids).reshape(cfg.T, masked_ids.shape[1], -1)
     for e in np.unique(masked_ids[masked_ids >= 0]):
         tt, kk = np.nonzero(masked_ids == e)
-        w = w_gate_up[e].astype(np.float64)
-        gate = x[tt] @ w[:I].T
-        h = gate / (1.0 + np.exp(-gate)) * (x[tt] @ w[I:].T)
-        spread = np.sqrt((h ** 2) @ (w_down[e].astype(np.float64) ** 2).T)          # [rows, H]
+        spread = np.sqrt((h[tt, kk] ** 2) @ (w_down[e].astype(np.float64) ** 2).T)   # [rows, H]
         np.add.at(out, tt, 6.0 * sigma * topk_weights[tt, kk, None].astype(np.float64) * spread)
     return out
+
+
+def allowance_applies(cfg) -> bool:
+    """Where the bf16 rounding of h can pass the stated 2e-2 of the output RMS: a narrow
+    layer (few terms per output element to average the rounding over) or a low keep rate
+    (an RMS that is mostly zero rows)."""
+    return cfg.dtype == "bf16" and (cfg.H <= 128 or cfg.keep <= 0.15)
+
+
+def staged_error_parts(cfg, g, ref_out, packed=False, tokens=None, rms=None):
+    """The layer through the staged entry points, with the output error split into its two
+    parts.  Returns (pre, rnd, out) where
+      pre = max |y - ref| / RMS(ref): y is the fp64 sum, over the kept slots, of the GPU's
+            own routing weight times its own fp32 expert output row (what the aggregation
+            adds up before it rounds): the part the stated 2e-2 budget is for;
+      rnd = max |out - y| / (2^-9 |y| + 1e-6 max|y|): the output rounding against a bf16
+            half-ulp plus the fp32 accumulation of at most K terms (fp32: the latter
+            alone); at most 1;
+      out = the staged path's output tensor.
+    tokens: optional index array; ref_out then holds those rows only.  rms: as output_error."""
+    s = shape_of(cfg, packed=packed)
+    ws, nb = workspace(s)
+    T, K, N, H = cfg.T, cfg.K, cfg.N, cfg.H
+    i32 = dict(dtype=torch.int32, device="cuda")
+    ids, mids = torch.empty((T, K), **i32), torch.empty((T, K), **i32)
+    gw = torch.empty((T, K), dtype=torch.float32, device="cuda")
+    counts, offsets = torch.empty((N,), **i32), torch.empty((N + 1,), **i32)
+    perm, inv, P = torch.empty((T * K,), **i32), torch.empty((T * K,), **i32), torch.empty((1,), **i32)
+    y = torch.empty((T * K, H), dtype=torch.float32, device="cuda")
+    out = out_tensor(cfg)
+    st = stream_ptr()
+    beam.beam_route_mask(s, g["x"], g["w_router"], g["b_router"], g["w_mask"], g["b_mask"], ids,
+                         gw, mids, None, None, ws, nb, st)
+    beam.beam_permute(s, mids, counts, offsets, perm, inv, P, ws, nb, st)
+    beam.beam_expert_ffn(s, g["x"], g["w_gate_up"], g["w_down"], offsets, perm, P, y, ws, nb, st)
+    beam.beam_combine(s, y, gw, mids, inv, out, st)
+    torch.cuda.synchronize()
+    tok = np.arange(T) if tokens is None else np.asarray(tokens)
+    tok_d = torch.from_numpy(tok).cuda()
+    rows = inv.view(T, K)[tok_d]                              # [n, K], -1 where dropped
+    kept = (mids[tok_d] >= 0) & (rows >= 0)
+    pre = np.zeros((tok.size, H))
+    gw_h = gw[tok_d].cpu().numpy().astype(np.float64)
+    for k in range(K):
+        sel = kept[:, k]
+        if not bool(sel.any()):
+            continue
+        yk = y[rows[:, k][sel].long()].cpu().numpy().astype(np.float64)
+        sel_h = sel.cpu().numpy()
+        pre[sel_h] += gw_h[sel_h, k, None] * yk
+    got = out[tok_d].float().cpu().numpy().astype(np.float64)
+    rms = float(np.sqrt(np.mean(ref_out ** 2))) if rms is None else float(rms)
+    part_pre = float(np.abs(pre - ref_out).max() / rms) if rms > 0 else float(np.abs(pre).max())
+    half_ulp = 2.0 ** -9 if cfg.dtype == "bf16" else 0.0
+    bound = half_ulp * np.abs(pre) + 1e-6 * np.abs(pre).max()
+    part_rnd = float((np.abs(got - pre) / bound).max()) if bound.max() > 0 else \
+        float(np.abs(got - pre).max())
+    return part_pre, part_rnd, out

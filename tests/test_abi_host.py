@@ -75,6 +75,63 @@ def test_workspace_covers_the_split_reductions(lib):
     assert beam.beam_workspace_bytes(q) >= 4 * 1024 * 256 * 4 + 1024 * 8 * (2048 * 4 + 768 * 2)
 
 
+def _logits_parts(T, H, N):
+    """Parts the prefill logits product cuts its reduction into, as documented for the
+    kernel: 64-row tiles x 256-column tiles are its items; the parts double (up to 4)
+    while twice the items still fit 256 compute units and the 128-wide reduction steps
+    divide evenly."""
+    if T <= 512 or H % 256:
+        return 1
+    items = -(-T // 64) * -(-2 * N // 256)
+    k = 1
+    while k < 4 and items * k * 2 <= 256 and (H // 128) % (2 * k) == 0:
+        k *= 2
+    return k
+
+
+def test_logits_region_holds_the_parts_of_the_routed_shape(lib):
+    """The block entry point sizes the workspace for N + S experts, but the logits product
+    and Top-K run on the N routed experts and cut the reduction by THEIR column count:
+    the region must hold that many [T, 2N] arrays, for every (N, S, T)."""
+    worst = 0
+    for H in (2048, 512):
+        for N in (8, 60, 64, 120, 126, 127, 128, 200):
+            for S in (0, 1, 2, 4, 10):
+                if N + S > 256:
+                    continue
+                for T in (513, 1024, 2048, 2049, 4096, 4097, 6000, 8192, 8193, 16384):
+                    s = beam.make_shape(T, H, N, 4, 256, beam.BEAM_BF16)
+                    st, off, nbytes, parts = beam.beam_workspace_logits_region(s, S)
+                    assert st == binding.BEAM_OK and off % 256 == 0
+                    need = _logits_parts(T, H, N)
+                    worst = max(worst, need)
+                    assert parts >= need and parts >= _logits_parts(T, H, N + S)
+                    assert nbytes >= need * T * 2 * N * 4, (H, N, S, T)
+                    assert off + nbytes <= beam.beam_block_workspace_bytes(s, S)
+    assert worst == 4
+    # the case that used to overflow: 4 parts of [4096, 256] fp32 where N + S gave room for 2
+    s = beam.make_shape(4096, 2048, 128, 8, 768, beam.BEAM_BF16)
+    _, _, nbytes, parts = beam.beam_workspace_logits_region(s, 1)
+    assert parts == 4 and nbytes >= 4 * 4096 * 256 * 4
+    assert beam.beam_workspace_logits_region(s, 200, check=False)[0] == binding.BEAM_ERR_UNSUPPORTED
+    bad = beam.make_shape(4, 256, 8, 9, 512, beam.BEAM_F32)
+    assert beam.beam_workspace_logits_region(bad, 0, check=False)[0] == binding.BEAM_ERR_INVALID_ARG
+
+
+def test_residual_must_not_overlap_the_output(lib):
+    s = beam.make_shape(4, 256, 8, 2, 512, beam.BEAM_F32)
+    ok, big = 0x100000, 1 << 40
+    nbytes = 4 * 256 * 4
+
+    def block(res, out):
+        return beam.beam_moe_block_forward(s, 0, ok, ok, None, ok, None, ok, ok, None, res, out,
+                                           None, None, None, None, ok, big, check=False)
+    out = 0x200000
+    assert block(out, out) == binding.BEAM_ERR_INVALID_ARG
+    assert block(out + nbytes - 16, out) == binding.BEAM_ERR_INVALID_ARG
+    assert block(out - nbytes + 16, out) == binding.BEAM_ERR_INVALID_ARG
+
+
 @pytest.mark.parametrize("shape,code", [
     ((-1, 256, 8, 2, 512, 0), binding.BEAM_ERR_INVALID_ARG),
     ((4, 256, 8, 0, 512, 0), binding.BEAM_ERR_INVALID_ARG),

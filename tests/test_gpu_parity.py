@@ -361,13 +361,18 @@ def test_moe_forward_drawn_shapes(i):
     d = hp.make_tie_free(cfg)
     ref = oracle.moe_forward(d["x"], d["w_router"], d["b_router"], d["w_mask"], d["b_mask"],
                              d["w_gate_up"], d["w_down"], cfg.K)
-    # narrow layers at low keep rates: the bf16 rounding of h is no longer small against
-    # 2e-2 of an RMS that is mostly zero rows; the bound gets the term the arithmetic gives
-    extra = hp.hidden_rounding_allowance(cfg, d, ref["masked_ids"], ref["topk_weights"])
-    _check_forward(cfg, d, hp.forward(cfg, hp.upload(cfg, d)), ref, allowance=extra)
-    if _packable(cfg):
-        _check_forward(cfg, d, hp.forward(cfg, hp.upload(cfg, d), packed=True), ref,
-                       allowance=extra)
+    # narrow layers and low keep rates: the bf16 rounding of h is no longer small against
+    # 2e-2 of an RMS that is mostly zero rows; there, and only there, the bound gets the
+    # term the arithmetic gives.  Everywhere else the plain bound must hold.
+    extra = None
+    if hp.allowance_applies(cfg):
+        extra = hp.hidden_rounding_allowance(cfg, d, ref["masked_ids"], ref["topk_weights"])
+    for packed in ([False, True] if _packable(cfg) else [False]):
+        res = hp.forward(cfg, hp.upload(cfg, d), packed=packed)
+        _, plain_ratio = hp.output_error(res["out"], ref["out"], cfg.dtype)
+        _log(f"  drawn{i} packed={packed}: worst/bound without the allowance {plain_ratio:.3f}"
+             f" (allowance {'applies' if extra is not None else 'does not apply'})")
+        _check_forward(cfg, d, res, ref, allowance=extra)
 
 
 def test_moe_forward_all_ones_mask_is_topk_moe():
@@ -384,20 +389,40 @@ def test_moe_forward_all_ones_mask_is_topk_moe():
     _check_forward(cfg, d, res, ref)
 
 
+def _check_error_parts(cfg, g, res, ref_out, packed, tokens=None, rms=None):
+    """The fused output equals the staged one bit for bit, and the staged path shows the two
+    parts of its error separately: what precedes the output rounding stays inside the
+    stated 2e-2 of the RMS, and the rounding itself is a bf16 half-ulp."""
+    pre, rnd, out_staged = hp.staged_error_parts(cfg, g, ref_out, packed=packed, tokens=tokens,
+                                                 rms=rms)
+    assert torch.equal(res["out_raw"], out_staged)
+    _log(f"    error parts: before the output rounding {pre:.4f} of the RMS, "
+         f"output rounding {rnd:.3f} of a half-ulp")
+    assert pre <= (2e-2 if cfg.dtype == "bf16" else 1e-4)
+    assert rnd <= 1.0
+    return pre, rnd
+
+
+@pytest.mark.parametrize("packed", [False, True], ids=["plain", "packed"])
 @pytest.mark.parametrize("T", [1, 8, 32, 64])
-def test_moe_forward_qwen3_decode_full_size(T):
+def test_moe_forward_qwen3_decode_full_size(T, packed):
+    """The benchmark's own path (packed weights) and the row-major one, at full width."""
     cfg = CFG["qwen3_decode"].with_(T=T)
-    _log(f"moe_forward full size {cfg}")
+    _log(f"moe_forward full size {cfg} packed={packed}")
     d = hp.make_tie_free(cfg)
     ref = oracle.moe_forward(d["x"], d["w_router"], d["b_router"], d["w_mask"], d["b_mask"],
                              d["w_gate_up"], d["w_down"], cfg.K)
-    res = hp.forward(cfg, hp.upload(cfg, d))
+    g = hp.upload(cfg, d)
+    if packed:
+        g["w_gate_up"], g["w_down"] = hp.pack_weights(cfg, g["w_gate_up"], g["w_down"])
+    res = hp.forward(cfg, g, prepacked=packed)
     _check_forward(cfg, d, res, ref)
+    _check_error_parts(cfg, g, res, ref["out"], packed)
     if T == 64:
         per_token = (ref["masked_ids"] >= 0).sum(axis=1)
         assert per_token.min() == 0 and per_token.max() >= 3
         # run it again into the same buffers: identical bits
-        res2 = hp.forward(cfg, hp.upload(cfg, d))
+        res2 = hp.forward(cfg, g, prepacked=packed)
         assert torch.equal(res["out_raw"], res2["out_raw"])
 
 
@@ -418,14 +443,17 @@ def _sampled_forward_check(cfg, packed, n_sample=48):
     zero = np.flatnonzero(kept == 0)
     pick.update(zero[:8].tolist())                                       # none kept
     pick.update([0, cfg.T - 1])
-    pick.update(rng.choice(cfg.T, size=n_sample, replace=False).tolist())
+    drawn = rng.choice(cfg.T, size=n_sample, replace=False)
+    pick.update(drawn.tolist())
     sub = np.array(sorted(pick))
     ref = oracle.moe_forward(d["x"][sub], d["w_router"], d["b_router"], d["w_mask"], d["b_mask"],
                              d["w_gate_up"], d["w_down"], cfg.K)
     assert np.array_equal(ref["masked_ids"], msk_o[sub])
     got = res["out"][sub]
-    # the RMS of the tolerance is that of the whole output, estimated on the sample
-    literal, ratio = hp.output_error(got, ref["out"], cfg.dtype)
+    # the RMS of the tolerance is that of the whole output, estimated on the randomly drawn
+    # rows alone: the rows picked for keeping the most experts would inflate it
+    rms = float(np.sqrt(np.mean(ref["out"][np.isin(sub, drawn)] ** 2)))
+    literal, ratio = hp.output_error(got, ref["out"], cfg.dtype, rms=rms)
     _log(f"  {cfg.name} T={cfg.T} keep={cfg.keep} packed={packed}: P={res['num_pairs']} "
          f"sample {sub.size} tokens max|err|/RMS={literal:.4f} worst/bound={ratio:.3f}")
     assert ratio <= 1.0
@@ -439,8 +467,11 @@ def _sampled_forward_check(cfg, packed, n_sample=48):
         assert (raw.view(torch.int16) == 0).all()
 
 
-@pytest.mark.parametrize("T,keep,packed", [(4096, 0.15, True), (4096, 1.0, False),
-                                           (16384, 0.15, True), (16384, 0.5, True)])
+@pytest.mark.parametrize("T,keep,packed", [(4096, 0.15, True), (4096, 0.25, True),
+                                           (4096, 0.5, True), (4096, 1.0, False),
+                                           (4096, 1.0, True),
+                                           (16384, 0.15, True), (16384, 0.25, True),
+                                           (16384, 0.5, True), (16384, 1.0, True)])
 def test_moe_forward_qwen3_prefill_full_size_sampled(T, keep, packed):
     cfg = CFG["qwen3_prefill"].with_(T=T, keep=keep)
     _log(f"moe_forward full size sampled {cfg} packed={packed}")
@@ -482,15 +513,26 @@ def _prefix_check(name, Tmax, T, packed):
         rng = np.random.default_rng(T)
         pick = set(np.argsort(-kept, kind="stable")[:6].tolist())
         pick.update(np.flatnonzero(kept == 0)[:6].tolist())
-        pick.update(rng.choice(T, size=24, replace=False).tolist())
+        drawn = rng.choice(T, size=24, replace=False)
+        pick.update(drawn.tolist())
         sub = np.array(sorted(pick))
     ref = oracle.moe_forward(dd["x"][sub], d["w_router"], d["b_router"], d["w_mask"], d["b_mask"],
                              d["w_gate_up"], d["w_down"], cfg.K)
-    literal, ratio = hp.output_error(res["out"][sub], ref["out"], cfg.dtype)
+    rms = None if T <= 64 else float(np.sqrt(np.mean(ref["out"][np.isin(sub, drawn)] ** 2)))
+    literal, ratio = hp.output_error(res["out"][sub], ref["out"], cfg.dtype, rms=rms)
     _log(f"  {name} T={T}: P={res['num_pairs']} kept/token min {kept.min()} max {kept.max()} "
          f"mean {kept.mean():.2f}; {sub.size} tokens max|err|/RMS={literal:.4f} "
          f"worst/bound={ratio:.3f}")
     assert ratio <= 1.0
+    if name == "large":
+        # this workload's literal metric passes 2e-2 (heavy-tailed rows against an RMS that
+        # is mostly tokens keeping one or no expert): show that the excess is the output
+        # rounding alone
+        gs = gg
+        if packed:
+            pg, pd = hp.pack_weights(cfg, gg["w_gate_up"], gg["w_down"])
+            gs = {**gg, "w_gate_up": pg, "w_down": pd}
+        _check_error_parts(cfg, gs, res, ref["out"], packed, tokens=sub, rms=rms)
     zero = np.flatnonzero(kept == 0)
     if zero.size:
         raw = res["out_raw"][torch.from_numpy(zero).cuda()]
@@ -599,10 +641,15 @@ def test_moe_block_forward_drawn_shapes(i):
     res = hp.block_forward(cfg, d, packed=packed, use_gate=use_gate, use_residual=use_residual)
     _check_block_slots(cfg, res, ref["topk_ids"], ref["topk_weights"], ref["masked_ids"],
                        ref["g_shared"], cfg.S)
-    gu, dn = synth.append_shared_blocks(cfg, d) if cfg.S > 0 else (d["w_gate_up"], d["w_down"])
-    extra = hp.hidden_rounding_allowance(cfg, d, res["masked_ids"], res["topk_weights"], gu, dn)
+    extra = np.zeros_like(ref["out"])
+    if hp.allowance_applies(cfg):        # narrow layer or low keep rate, nowhere else
+        gu, dn = synth.append_shared_blocks(cfg, d) if cfg.S > 0 else (d["w_gate_up"], d["w_down"])
+        extra = hp.hidden_rounding_allowance(cfg, d, res["masked_ids"], res["topk_weights"], gu, dn)
+    _, plain_ratio = hp.output_error(res["out"], ref["out"], cfg.dtype)
     literal, ratio = hp.output_error(res["out"], ref["out"], cfg.dtype, extra)
-    _log(f"  max|err|/RMS={literal:.4f} worst/bound={ratio:.3f}")
+    _log(f"  max|err|/RMS={literal:.4f} worst/bound={ratio:.3f} "
+         f"(without the allowance {plain_ratio:.3f}; it "
+         f"{'applies' if hp.allowance_applies(cfg) else 'does not apply'})")
     assert ratio <= 1.0
     if use_residual and cfg.dtype == "bf16":
         # the residual (~N(0,1)) must not hide the experts' part: the same bound with the RMS
@@ -666,12 +713,25 @@ def test_moe_block_forward_argument_checks():
     torch.cuda.synchronize()
 
 
+# 128 routed experts and one gated shared block: the routed heads fill one 256-column tile
+# of the logits product exactly while the extended expert count needs two, so the two
+# shapes cut the logits reduction into different numbers of parts (workspace carve-up)
+QWEN3_SHARED = synth.LayerConfig("qwen3_shared", 14, T=4096, H=2048, N=128, K=8, I=768,
+                                 dtype="bf16", keep=0.15, router_skew="zipf", S=1,
+                                 shared_gate=True)
+
+
 @pytest.mark.parametrize("name,T,packed", [("qwen15_moe", 64, False), ("qwen15_moe", 1, False),
                                            ("dsv2_lite", 64, False), ("dsv2_lite", 4096, True),
-                                           ("qwen15_moe", 2048, True)])
+                                           ("qwen15_moe", 2048, True),
+                                           (QWEN3_SHARED, 4096, True), (QWEN3_SHARED, 6000, True),
+                                           (QWEN3_SHARED, 2100, False)],
+                         ids=lambda v: getattr(v, "name", str(v)))
 def test_moe_block_forward_full_size(name, T, packed):
-    """The two shared-expert models of the paper's evaluation at full layer size."""
-    cfg = CFG[name].with_(T=T)
+    """The two shared-expert models of the paper's evaluation at full layer size, and the
+    Qwen3-shaped layer with a shared block added."""
+    cfg = (CFG[name] if isinstance(name, str) else name).with_(T=T)
+    name = cfg.name
     _log(f"moe_block_forward full size {cfg} packed={packed}")
     d = hp.make_tie_free(cfg)
     ids_o, g_o, msk_o = oracle.route_mask(d["router_logits"], d["mask_logits"], cfg.K)
