@@ -193,9 +193,9 @@ def staged_error_parts(cfg, g, ref_out, packed=False, tokens=None, rms=None):
       pre = max |y - ref| / RMS(ref): y is the fp64 sum, over the kept slots, of the GPU's
             own routing weight times its own fp32 expert output row (what the aggregation
             adds up before it rounds): the part the stated 2e-2 budget is for;
-      rnd = max |out - y| / (2^-9 |y| + 1e-6 max|y|): the output rounding against a bf16
-            half-ulp plus the fp32 accumulation of at most K terms (fp32: the latter
-            alone); at most 1;
+      rnd = max |out - y| / (2^-8 |y| + 1e-6 max|y|): the output rounding against a bf16
+            half-ulp (8 significant bits: at most 2^-8 of the value) plus the fp32
+            accumulation of at most K terms (fp32: the latter alone); at most 1;
       out = the staged path's output tensor.
     tokens: optional index array; ref_out then holds those rows only.  rms: as output_error."""
     s = shape_of(cfg, packed=packed)
@@ -231,7 +231,7 @@ def staged_error_parts(cfg, g, ref_out, packed=False, tokens=None, rms=None):
     got = out[tok_d].float().cpu().numpy().astype(np.float64)
     rms = float(np.sqrt(np.mean(ref_out ** 2))) if rms is None else float(rms)
     part_pre = float(np.abs(pre - ref_out).max() / rms) if rms > 0 else float(np.abs(pre).max())
-    half_ulp = 2.0 ** -9 if cfg.dtype == "bf16" else 0.0
+    half_ulp = 2.0 ** -8 if cfg.dtype == "bf16" else 0.0
     bound = half_ulp * np.abs(pre) + 1e-6 * np.abs(pre).max()
     part_rnd = float((np.abs(got - pre) / bound).max()) if bound.max() > 0 else \
         float(np.abs(got - pre).max())
