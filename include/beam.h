@@ -196,6 +196,30 @@ beam_status beam_moe_forward(const beam_shape *shape, const void *x, const void 
                              size_t workspace_bytes, void *hip_stream);
 
 /*
+ * beam_moe_forward for callers that cannot allocate device memory or hand in a
+ * workspace: code running under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments (without the optional outputs and the
+ * workspace), same kernels, same bits in `out`.  The intermediates live in a device
+ * array of BEAM_NOALLOC_WORKSPACE_BYTES that belongs to the library's code object: every
+ * GPU the library runs on holds that much memory from the first call on it until the
+ * process ends.  The call allocates and frees nothing and does not synchronise; the
+ * first call on a device looks up the array's device address (do it once outside a
+ * graph capture).
+ *   - A shape whose beam_workspace_bytes() exceeds BEAM_NOALLOC_WORKSPACE_BYTES returns
+ *     BEAM_ERR_WORKSPACE before anything is enqueued (Qwen3-shaped layer, H 2048,
+ *     I 768, top-8: up to 395 tokens; H 4096, I 1536, top-8: up to 186).
+ *   - All calls on one GPU share the one array and it keeps the last call's contents:
+ *     calls that overlap in time on one GPU (two streams, two threads) race.  Calls on
+ *     one stream are ordered and safe.  Nothing in the array needs clearing between
+ *     calls.
+ */
+#define BEAM_NOALLOC_WORKSPACE_BYTES (32u << 20)
+beam_status beam_moe_forward_noalloc(const beam_shape *shape, const void *x, const void *w_router,
+                                     const float *router_bias, const void *w_mask,
+                                     const float *mask_bias, const void *w_gate_up,
+                                     const void *w_down, void *out, void *hip_stream);
+
+/*
  * Other activation rules on the same Top-K slots (the paper's ablation on the
  * binarisation threshold, Sec. 4.4, and the cumulative-probability baseline of
  * Sec. 4.1).  A rule only decides which of the K ranked slots are kept, i.e. what

@@ -31,7 +31,9 @@ EXPORTS = ("beam_abi_version", "beam_status_string", "beam_workspace_bytes", "be
            "beam_moe_forward_timed", "beam_pack_weights", "beam_block_workspace_bytes",
            "beam_moe_block_forward", "beam_moe_block_forward_timed", "beam_route_rule",
            "beam_moe_forward_rule", "beam_mask_router_backward", "beam_probe_stream_read",
-           "beam_probe_mfma", "beam_workspace_logits_region")
+           "beam_probe_mfma", "beam_workspace_logits_region",
+           "beam_moe_forward_noalloc")
+BEAM_NOALLOC_WORKSPACE_BYTES = 32 << 20
 BEAM_RULE_MASK = 0
 BEAM_RULE_CUMPROB = 1
 BEAM_NUM_STAGES = 6
@@ -84,6 +86,8 @@ def load() -> ctypes.CDLL:
         lib.beam_combine.argtypes = [sp] + [vp] * 6
         lib.beam_moe_forward.restype = ctypes.c_int
         lib.beam_moe_forward.argtypes = [sp] + [vp] * 13 + [sz, vp]
+        lib.beam_moe_forward_noalloc.restype = ctypes.c_int
+        lib.beam_moe_forward_noalloc.argtypes = [sp] + [vp] * 9
         rp = ctypes.POINTER(beam_rule)
         lib.beam_route_rule.restype = ctypes.c_int
         lib.beam_route_rule.argtypes = [sp, rp] + [vp] * 11 + [sz, vp]
@@ -209,6 +213,15 @@ def beam_moe_forward(shape, x, w_router, router_bias, w_mask, mask_bias, w_gate_
                                  _p(num_pairs_opt), _p(workspace), int(workspace_bytes),
                                  _p(hip_stream))
     return _check("beam_moe_forward", st, check)
+
+
+def beam_moe_forward_noalloc(shape, x, w_router, router_bias, w_mask, mask_bias, w_gate_up, w_down,
+                             out, hip_stream=None, check: bool = True) -> int:
+    s = _shape(shape)
+    st = load().beam_moe_forward_noalloc(ctypes.byref(s), _p(x), _p(w_router), _p(router_bias),
+                                         _p(w_mask), _p(mask_bias), _p(w_gate_up), _p(w_down),
+                                         _p(out), _p(hip_stream))
+    return _check("beam_moe_forward_noalloc", st, check)
 
 
 def beam_block_workspace_bytes(shape, num_shared: int) -> int:

@@ -2,6 +2,8 @@
 // workspace carve-up, and the order in which the stage kernels are enqueued.
 // Nothing here allocates, copies to the host or synchronises (the stage-timed
 // measurement entry point excepted).
+#include <atomic>
+
 #include "common.hpp"
 
 namespace beam {
@@ -494,6 +496,50 @@ beam_status beam_moe_forward(const beam_shape *shape, const void *x, const void 
                             w_gate_up, w_down, nullptr, nullptr, out, topk_ids_opt,
                             topk_weights_opt, masked_ids_opt, num_pairs_opt, workspace,
                             workspace_bytes, hip_stream, nullptr);
+}
+
+// ---------------------------------------------------------------------------
+// beam_moe_forward for callers that cannot allocate: the intermediates live in a
+// device array that is part of this library's code object instead of a caller's
+// workspace.  In host code the array's name is only a stand-in for the symbol;
+// its device address is looked up once per device (hipGetSymbolAddress, with that
+// device current) and only that address is ever handed to the kernels.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[BEAM_NOALLOC_WORKSPACE_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void *> g_scratch_addr[kMaxDevices];
+
+// Device address of `scratch` on the current device, or NULL on a HIP error.
+static void *scratch_on_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void *p = g_scratch_addr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    void *found = nullptr;
+    if (hipGetSymbolAddress(&found, HIP_SYMBOL(scratch)) != hipSuccess || !found) return nullptr;
+    // every thread that races here gets the same address from the runtime
+    g_scratch_addr[dev].store(found, std::memory_order_release);
+    return found;
+}
+
+beam_status beam_moe_forward_noalloc(const beam_shape *shape, const void *x, const void *w_router,
+                                     const float *router_bias, const void *w_mask,
+                                     const float *mask_bias, const void *w_gate_up,
+                                     const void *w_down, void *out, void *hip_stream) {
+    beam_status st = check_shape(shape);
+    if (st != BEAM_OK) return st;
+    // the size check comes before anything touches the device
+    if (ws_layout(*shape).total > (size_t)BEAM_NOALLOC_WORKSPACE_BYTES) return BEAM_ERR_WORKSPACE;
+    if (!x || !w_router || !w_mask || !w_gate_up || !w_down || !out) return BEAM_ERR_INVALID_ARG;
+    if (shape->T == 0) return BEAM_OK;
+    void *ws = scratch_on_current_device();
+    if (!ws) return BEAM_ERR_HIP;
+    // Nothing in the workspace has to start at zero: every kernel of the layer writes what a
+    // later one reads (the one counter of the small-batch path is reset by the logits kernel).
+    return moe_forward_impl(shape, 0, nullptr, x, w_router, router_bias, w_mask, mask_bias,
+                            w_gate_up, w_down, nullptr, nullptr, out, nullptr, nullptr, nullptr,
+                            nullptr, ws, (size_t)BEAM_NOALLOC_WORKSPACE_BYTES, hip_stream, nullptr);
 }
 
 beam_status beam_moe_forward_rule(const beam_shape *shape, const beam_rule *rule, const void *x,
