@@ -131,10 +131,14 @@ def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp, packed
         # 6 stages; the grouping of more than 8192 pairs is 4 launches, the tiled logits GEMM repacks the
         # heads first, a gated shared expert adds one; up to 32 tokens Top-K and grouping are
         # one launch; tiny batches take the three-kernel path
+        # ... and between decode and prefill size both families of expert GEMM kernels are
+        # enqueued (the one the device does not choose leaves at once): two more
         "kernels_per_layer": (3 if tiny else 6 + (3 if T * (cfg.K + S) > 8192 else 0) + (
             1 if T > 512 and cfg.dtype == "bf16" and cfg.H % 256 == 0 else 0) - (
             1 if T <= 32 and T * (cfg.K + S) <= 512 and cfg.K + S <= 16 and cfg.N % 4 == 0
-            else 0)) + (1 if gate is not None else 0),
+            else 0)) + (1 if gate is not None else 0) + (
+            2 if (cfg.dtype == "bf16" and cfg.H % 512 == 0 and cfg.I % 128 == 0 and cfg.I < 4096
+                  and max(512, 8 * (N + S)) < T * (cfg.K + S) <= 256 * (N + S)) else 0),
         "us_per_layer": ms * 1e3, "tokens_per_s": T / (ms * 1e-3), "stage_us": stage_us,
         "kernel_us": kernel_us,
         "layer_GBs": layer_bytes / (ms * 1e-3) / 1e9,
@@ -376,6 +380,52 @@ def upload_layer(cfg, d, hp, synth):
     return g
 
 
+def device_weight_sets(cfg, nsets, torch, seed):
+    """Expert weights drawn on the device (N(0, 0.02^2), bf16, seeded) for workload points
+    whose multi-GB weights would take minutes to draw on the host.  Timing only: the
+    routing inputs (x, heads, biases) still come from synth, so keep rate and skew are the
+    workload's; read as packed weights a random array is the same distribution."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    n = cfg.N + cfg.S
+    sets = []
+    for _ in range(nsets):
+        gu = (torch.randn(n, 2 * cfg.I, cfg.H, generator=gen, device="cuda") * 0.02).to(torch.bfloat16)
+        dn = (torch.randn(n, cfg.H, cfg.I, generator=gen, device="cuda") * 0.02).to(torch.bfloat16)
+        sets.append((gu, dn))
+    return sets
+
+
+def _sha16(paths):
+    import hashlib
+    h = hashlib.sha256()
+    for p in paths:
+        with open(os.path.join(ROOT, p), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` on `workload` from the tracked counter summary
+    (profiles/traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by what the
+    same counters read for a device copy of known size).  Counters cannot be read inside
+    this process, so the figure is carried from that run, and only while the kernel's
+    source files still hash to what they were when it was taken; otherwise None."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(path):
+        return None
+    for rec in json.load(open(path))["records"]:
+        if rec["workload"] == workload and rec["kernel"] == kernel:
+            try:
+                same = _sha16(rec["source_files"]) == rec["source_sha16"]
+            except OSError:
+                same = False
+            if same:
+                return {"bytes": rec["fetch_bytes"] + rec["write_bytes"],
+                        "source": f"profiles/traffic.json@{rec['commit']}"}
+    return None
+
+
 def roofline_of(pt):
     """Roofline record of the dominant kernel (gate/up) of a point: HBM bound
     when its byte time exceeds its flop time at the peaks, else MFMA bound."""
@@ -383,13 +433,19 @@ def roofline_of(pt):
     sec = gu["us"] * 1e-6
     t_b = gu["bytes"] / (HBM_PEAK_GBS * 1e9)
     t_f = gu["flops"] / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    tr = measured_traffic(pt["workload"] + " " + pt["weights"], "gate_up")
+    extra = {"traffic": tr["bytes"] if tr else None,
+             "duration_us": gu["us"], "duration_kind": "HIP events around the stage, bubble-corrected"}
+    if tr:
+        extra["traffic_source"] = tr["source"]
+        extra["traffic_over_algorithmic"] = tr["bytes"] / gu["bytes"]
     if t_b >= t_f:
         a = gu["bytes"] / sec / 1e9
         return {"bound": "hbm", "kernel": "gate_up", "achieved": a, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": a / HBM_PEAK_GBS, "traffic": None}
+                "unit": "GB/s", "frac": a / HBM_PEAK_GBS, **extra}
     a = gu["flops"] / sec / 1e12
     return {"bound": "mfma", "kernel": "gate_up", "achieved": a, "peak": MFMA_BF16_PEAK_TFLOPS,
-            "unit": "TFLOP/s", "frac": a / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+            "unit": "TFLOP/s", "frac": a / MFMA_BF16_PEAK_TFLOPS, **extra}
 
 
 def main():
@@ -459,7 +515,8 @@ def main():
             points.append(measure_point(c, dd, gg, main_sets, psteps, 10, torch, beam, hp,
                                         packed=args.packed))
         pre = synth.CONFIGS["qwen3_prefill"]
-        for T, keep, n in ((1024, 0.15, 30), (4096, 0.15, 30), (16384, 0.15, 20), (16384, 0.25, 20),
+        for T, keep, n in ((1024, 0.15, 30), (4096, 0.15, 30), (4096, 0.25, 30), (4096, 0.5, 20),
+                           (4096, 1.0, 20), (16384, 0.15, 20), (16384, 0.25, 20),
                            (16384, 0.5, 15), (16384, 1.0, 10)):
             c = pre.with_(T=T, keep=keep)
             dd = synth.make_layer(c, with_experts=False)
@@ -487,6 +544,23 @@ def main():
             points.append(measure_point(c, dd, gg, bsets, psteps, 10, torch, beam, hp,
                                         packed=args.packed))
             del dd, gg, bsets
+        # Mixtral-shaped and large fine-grained layers: expert weights drawn on the device
+        packed_sets = None               # free the repacked Qwen3 copies
+        torch.cuda.empty_cache()
+        for name, Ts in (("mixtral", (1, 16, 2048)), ("large", (64, 8192))):
+            base = synth.CONFIGS[name]
+            wsets = device_weight_sets(base, 2, torch, synth.seed_for(base, 98))
+            for T in Ts:
+                c = base.with_(T=T)
+                dd = synth.make_layer(c, with_experts=False)
+                gg = hp.upload(c, dd)
+                pt = measure_point(c, dd, gg, wsets, 20 if T <= 64 else 10, 10, torch, beam, hp,
+                                   packed=args.packed)
+                pt["weights"] += ", drawn on the device"
+                points.append(pt)
+                del dd, gg
+            del wsets
+            torch.cuda.empty_cache()
     rules = []
     if not args.no_points and args.workload == "qwen3_decode":
         rules = measure_rules(cfg, g, main_sets, max(20, args.steps // 4), torch, beam, hp,
@@ -531,13 +605,6 @@ def main():
     for rf in [main_roofline] + [p["roofline"] for p in points]:
         rf["frac_of_measured_ceiling"] = rf["achieved"] / (
             ceilings["stream_read_GBs"] if rf["bound"] == "hbm" else ceilings["mfma_bf16_TFLOPs"])
-    if (args.workload == "qwen3_decode" and cfg.T == 64 and args.keep is None and args.packed
-            and main_pt["U"] == 63):
-        # HBM bytes per gate/up launch of exactly this workload from rocprofv3 --pmc
-        # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors calibrated on a 1 GiB device copy):
-        # profiles/qwen3_decode_T64_keep15_kernels.md.  Counters cannot be read in-process.
-        main_roofline["traffic"] = 398.1e6 + 0.12e6
-        main_roofline["traffic_over_algorithmic"] = (398.1e6 + 0.12e6) / main_pt["gate_up"]["bytes"]
     rec = {
         "metric": "masked_moe_layer_tokens_per_s", "value": main_pt["tokens_per_s"],
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -3,6 +3,7 @@
 // Nothing here allocates, copies to the host or synchronises (the stage-timed
 // measurement entry point excepted).
 #include <atomic>
+#include <cstdlib>
 
 #include "common.hpp"
 
@@ -16,18 +17,19 @@ hipError_t launch_gate_up_generic(const beam_shape &s, const void *x, const void
 hipError_t launch_down_generic(const beam_shape &s, const void *hidden, const void *w_down,
                                const int32_t *offsets, const int32_t *num_pairs, float *y_pairs,
                                hipStream_t st);
+// want: kRegimeAny, or the regime (work list hdr[2]) under which the kernel is to run at all
 hipError_t launch_gate_up_stream(const beam_shape &s, const void *x, const void *w_gate_up,
                                  const int32_t *offsets, const int32_t *perm, const WorkList &wl,
-                                 void *hidden, hipStream_t st);
+                                 void *hidden, hipStream_t st, int want);
 hipError_t launch_down_stream(const beam_shape &s, const void *hidden, const void *w_down,
                               const int32_t *offsets, const WorkList &wl, float *y_pairs,
-                              hipStream_t st);
+                              hipStream_t st, int want);
 hipError_t launch_gate_up_tiled(const beam_shape &s, const void *x, const void *w_gate_up,
                                 const int32_t *offsets, const int32_t *perm, const WorkList &wl,
-                                void *hidden, hipStream_t st);
+                                void *hidden, hipStream_t st, int want);
 hipError_t launch_down_tiled(const beam_shape &s, const void *hidden, const void *w_down,
                              const int32_t *offsets, const WorkList &wl, float *y_pairs,
-                             hipStream_t st, int k_split);
+                             hipStream_t st, int k_split, int want);
 hipError_t launch_pack_weights(const beam_shape &s, const void *w_gate_up, const void *w_down,
                                void *w_gate_up_packed, void *w_down_packed, hipStream_t st);
 
@@ -57,11 +59,9 @@ static bool use_tiled(const beam_shape &s);
 // T = 1024 403 -> 250 (the aggregation gains 4-12 us); at T = 2048 (384 items of work
 // already) four parts give 407 -> 352 us but the aggregation and the gate/up GEMM lose
 // as much, and two parts give nothing, so it stays whole.
+static int down_split_k_if_tiled(const beam_shape &s);
 static int down_split_k(const beam_shape &s) {
-    if (!use_tiled(s) || s.I < 4096) return 1;
-    const long items = ((long)s.T * s.K / kTileM + s.N) * (s.H / 256);
-    const int k_split = items <= 512 ? 4 : 1;
-    return (s.I / 64) % k_split == 0 ? k_split : 1;   // whole 64-wide K-steps per part
+    return use_tiled(s) ? down_split_k_if_tiled(s) : 1;
 }
 
 // `s` counts every expert and slot the grouped kernels see; the last S of them are the
@@ -124,36 +124,82 @@ WorkList work_list(void *base, const beam_shape &s, int max_tiles) {
     return wl;
 }
 
-// Row count per expert above which the tiled GEMM beats re-streaming the
-// weights once per 16 rows (worst case, every Top-K pair kept).
-static bool use_tiled(const beam_shape &s) {
-    if (!tiled_ffn_supported(s)) return false;
-    // Worst-case rows per expert (every pair kept) above which the tiled GEMM takes over.
-    // The host cannot know the keep rate: at 15 % kept the streaming kernels would still
-    // win up to about four times this size, at 100 % they already lose by half here.
-    if ((long)s.T * s.K > 32L * s.N) return true;
-    // few rows per expert: the streaming kernels, which read either layout (packed needs
-    // their shape envelope; outside it the tiled kernel is the only reader of that layout)
-    return s.weight_layout == BEAM_WEIGHTS_PACKED && !stream_ffn_supported(s);
+// What the shape alone says about the expert GEMMs.  Decode-sized batches (a handful of
+// rows per expert whatever the keep rate) stream; beyond 256 rows per expert in the worst
+// case the tiled GEMM it is; in between the right family depends on the keep rate and the
+// routing skew, which only the device knows after grouping (work list hdr[2]): both
+// families are enqueued and the one not chosen leaves at once (measured: a batch of 512
+// tokens with every pair kept and a skewed router 419 us streamed against 226 us tiled, 15 %
+// kept 130 against 143; 1024 tokens, uniform router, 15 % kept 248 against 270).
+// A split down reduction (few experts, long reduction) is a host decision the aggregation
+// shares, so those shapes stay with the host's rule.
+static int down_split_k_if_tiled(const beam_shape &s) {
+    if (!tiled_ffn_supported(s) || s.I < 4096) return 1;
+    const long items = ((long)s.T * s.K / kTileM + s.N) * (s.H / 256);
+    const int k_split = items <= 512 ? 4 : 1;
+    return (s.I / 64) % k_split == 0 ? k_split : 1;   // whole 64-wide K-steps per part
 }
+
+Regime ffn_regime(const beam_shape &s) {
+    const bool tiled_ok = tiled_ffn_supported(s), stream_ok = stream_ffn_supported(s);
+    if (!tiled_ok && !stream_ok) return Regime::Generic;
+    const long TK = (long)s.T * s.K;
+    if (!stream_ok)   // packed weights outside the streaming envelope have no other reader
+        return (s.weight_layout == BEAM_WEIGHTS_PACKED || TK > 32L * s.N) ? Regime::Tiled
+                                                                          : Regime::Generic;
+    if (!tiled_ok) return Regime::Stream;
+    if (getenv("BEAM_TUNE_REGIME")) {
+        const int r = atoi(getenv("BEAM_TUNE_REGIME"));
+        if (r == 1) return Regime::Tiled;
+        if (r == 2) return Regime::Stream;
+        if (r == 3) return (long)s.T * s.K > 32L * s.N ? Regime::Tiled : Regime::Stream;
+    }
+    if (TK <= kChunk || TK <= 8L * s.N) return Regime::Stream;   // a few rows per expert at most
+    if (TK > 256L * s.N) return Regime::Tiled;
+    if (down_split_k_if_tiled(s) > 1) return TK > 32L * s.N ? Regime::Tiled : Regime::Stream;
+    return Regime::Auto;
+}
+
+static bool use_tiled(const beam_shape &s) { return ffn_regime(s) == Regime::Tiled; }
 
 hipError_t launch_gate_up(const beam_shape &s, const void *x, const void *w_gate_up,
                           const int32_t *offsets, const int32_t *perm, const int32_t *num_pairs,
                           const WorkList &wl, void *hidden, hipStream_t st) {
-    if (use_tiled(s)) return launch_gate_up_tiled(s, x, w_gate_up, offsets, perm, wl, hidden, st);
-    if (stream_ffn_supported(s))
-        return launch_gate_up_stream(s, x, w_gate_up, offsets, perm, wl, hidden, st);
-    return launch_gate_up_generic(s, x, w_gate_up, offsets, perm, num_pairs, hidden, st);
+    switch (ffn_regime(s)) {
+        case Regime::Tiled:
+            return launch_gate_up_tiled(s, x, w_gate_up, offsets, perm, wl, hidden, st, kRegimeAny);
+        case Regime::Stream:
+            return launch_gate_up_stream(s, x, w_gate_up, offsets, perm, wl, hidden, st, kRegimeAny);
+        case Regime::Auto: {
+            const hipError_t e = launch_gate_up_stream(s, x, w_gate_up, offsets, perm, wl, hidden,
+                                                       st, kRegimeStream);
+            if (e != hipSuccess) return e;
+            return launch_gate_up_tiled(s, x, w_gate_up, offsets, perm, wl, hidden, st,
+                                        kRegimeTiled);
+        }
+        default:
+            return launch_gate_up_generic(s, x, w_gate_up, offsets, perm, num_pairs, hidden, st);
+    }
 }
 
 hipError_t launch_down(const beam_shape &s, const void *hidden, const void *w_down,
                        const int32_t *offsets, const int32_t *num_pairs, const WorkList &wl,
                        float *y_pairs, hipStream_t st, int k_split) {
-    if (use_tiled(s))
-        return launch_down_tiled(s, hidden, w_down, offsets, wl, y_pairs, st, k_split);
-    if (stream_ffn_supported(s))
-        return launch_down_stream(s, hidden, w_down, offsets, wl, y_pairs, st);
-    return launch_down_generic(s, hidden, w_down, offsets, num_pairs, y_pairs, st);
+    switch (ffn_regime(s)) {
+        case Regime::Tiled:
+            return launch_down_tiled(s, hidden, w_down, offsets, wl, y_pairs, st, k_split,
+                                     kRegimeAny);
+        case Regime::Stream:
+            return launch_down_stream(s, hidden, w_down, offsets, wl, y_pairs, st, kRegimeAny);
+        case Regime::Auto: {
+            const hipError_t e =
+                launch_down_stream(s, hidden, w_down, offsets, wl, y_pairs, st, kRegimeStream);
+            if (e != hipSuccess) return e;
+            return launch_down_tiled(s, hidden, w_down, offsets, wl, y_pairs, st, 1, kRegimeTiled);
+        }
+        default:
+            return launch_down_generic(s, hidden, w_down, offsets, num_pairs, y_pairs, st);
+    }
 }
 
 static beam_status check_shape(const beam_shape *s) {
@@ -319,7 +365,7 @@ beam_status beam_permute(const beam_shape *shape, const int32_t *masked_ids, int
     BEAM_TRY_HIP(launch_permute(s, masked_ids, expert_counts, expert_offsets, perm, inv_perm,
                                 num_pairs, (int32_t *)(ws + L.blk_counts),
                                 (int32_t *)(ws + L.blk_base), L.nchunk, wl,
-                                (hipStream_t)hip_stream));
+                                (hipStream_t)hip_stream, !use_tiled(s)));
     return BEAM_OK;
 }
 
@@ -341,7 +387,7 @@ beam_status beam_expert_ffn(const beam_shape *shape, const void *x, const void *
     char *ws = (char *)workspace;
     hipStream_t stream = (hipStream_t)hip_stream;
     const WorkList wl = work_list(ws + L.work, s, L.max_tiles);
-    BEAM_TRY_HIP(launch_work_list(s, expert_offsets, wl, stream));
+    BEAM_TRY_HIP(launch_work_list(s, expert_offsets, wl, stream, !use_tiled(s)));
     BEAM_TRY_HIP(launch_gate_up(s, x, w_gate_up, expert_offsets, perm, num_pairs, wl,
                                 ws + L.hidden, stream));
     BEAM_TRY_HIP(launch_down(s, ws + L.hidden, w_down, expert_offsets, num_pairs, wl, y_pairs,
@@ -472,7 +518,8 @@ static beam_status moe_forward_impl(const beam_shape *shape, int S, const beam_r
     if (!grouped)
         BEAM_TRY_HIP(launch_permute(se, mids, counts, offsets, perm, inv, np,
                                     (int32_t *)(ws + L.blk_counts),
-                                    (int32_t *)(ws + L.blk_base), L.nchunk, wl, stream));
+                                    (int32_t *)(ws + L.blk_base), L.nchunk, wl, stream,
+                                    !use_tiled(se)));
     BEAM_STAGE_MARK(3);
     BEAM_TRY_HIP(launch_gate_up(se, x, w_gate_up, offsets, perm, np, wl, ws + L.hidden, stream));
     BEAM_STAGE_MARK(4);

@@ -95,11 +95,20 @@ WsLayout ws_layout(const beam_shape &s, int S = 0);
 // Work list written on the device after the prefix sums:
 //   hdr[0] = number of experts with at least one kept pair (U)
 //   hdr[1] = number of row tiles
-//   active[u]      expert id of the u-th non-empty expert (ascending)
+//   hdr[2] = which expert GEMM kernels suit the realised counts (kRegimeStream / kRegimeTiled);
+//            where the host cannot tell from the shape it launches both families and each
+//            kernel leaves at once unless it is the one chosen here
+//   active[u]      expert id of the u-th non-empty expert (most rows first where the list
+//                  is built from counts; descending id in the single-chunk grouping)
 //   active_beg[u], active_end[u]  its grouped rows [beg, end)
 //   tile_expert[i] expert of row tile i,  tile_row0[i] its first grouped row
 // A workgroup that serves active expert u fetches all four words in one round
 // trip instead of chasing hdr -> active -> offsets.
+constexpr int kRegimeStream = 0;
+constexpr int kRegimeTiled = 1;
+constexpr int kRegimeAny = -1;     // kernel argument: run whatever hdr[2] says
+// rows of one expert that the streaming kernels cover in one pass over its weights
+constexpr int kStreamRows = 32;
 struct WorkList {
     int32_t *hdr;
     int32_t *active;
@@ -162,7 +171,7 @@ hipError_t launch_logits_tiled(const beam_shape &s, const void *x, const void *w
 hipError_t launch_permute(const beam_shape &s, const int32_t *masked_ids, int32_t *counts,
                           int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *num_pairs,
                           int32_t *blk_counts, int32_t *blk_base, int nchunk, const WorkList &wl,
-                          hipStream_t st);
+                          hipStream_t st, bool longest_first = false);
 bool route_permute_supported(const beam_shape &s, const RouteOpts &opt, const float *router_logits,
                              const float *mask_logits);
 hipError_t launch_route_permute(const beam_shape &s, const float *router_logits,
@@ -171,8 +180,13 @@ hipError_t launch_route_permute(const beam_shape &s, const float *router_logits,
                                 int32_t *counts, int32_t *offsets, int32_t *perm,
                                 int32_t *inv_perm, int32_t *num_pairs, const WorkList &wl,
                                 hipStream_t st);
+// longest_first: order the active-expert list by row count, most rows first (for the
+// streaming kernels, which walk it)
 hipError_t launch_work_list(const beam_shape &s, const int32_t *offsets, const WorkList &wl,
-                            hipStream_t st);
+                            hipStream_t st, bool longest_first = false);
+// What the host can tell about the expert GEMMs from the shape alone.
+enum class Regime { Stream, Tiled, Auto, Generic };
+Regime ffn_regime(const beam_shape &s);
 hipError_t launch_gate_up(const beam_shape &s, const void *x, const void *w_gate_up,
                           const int32_t *offsets, const int32_t *perm, const int32_t *num_pairs,
                           const WorkList &wl, void *hidden, hipStream_t st);

@@ -157,10 +157,11 @@ __device__ __forceinline__ void gate_up_rows(const bf16_t *__restrict__ x,
 __global__ __launch_bounds__(256) void gate_up_stream_kernel(
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ w_gate_up,
     const int32_t *__restrict__ perm, WorkList wl, bf16_t *__restrict__ hidden, int H, int K,
-    int I) {
+    int I, int want) {
     const int u = blockIdx.y;
-    // one round trip: the four words are independent loads
-    const int n_active = wl.hdr[0];
+    // one round trip: the words are independent loads.  Not the regime chosen on the
+    // device: no active expert for this kernel, every workgroup leaves.
+    const int n_active = (want != kRegimeAny && wl.hdr[2] != want) ? 0 : wl.hdr[0];
     const int e = wl.active[u];
     const int row_beg = wl.active_beg[u];
     const int row_end = wl.active_end[u];
@@ -432,9 +433,9 @@ __device__ __forceinline__ void down_rows(const bf16_t *__restrict__ hidden,
 template <int FT>
 __global__ __launch_bounds__(256) void down_stream_kernel(
     const bf16_t *__restrict__ hidden, const bf16_t *__restrict__ w_down, WorkList wl,
-    float *__restrict__ y_pairs, int H, int I) {
+    float *__restrict__ y_pairs, int H, int I, int want) {
     const int u = blockIdx.y;
-    const int n_active = wl.hdr[0];
+    const int n_active = (want != kRegimeAny && wl.hdr[2] != want) ? 0 : wl.hdr[0];
     const int e = wl.active[u];
     const int row_beg = wl.active_beg[u];
     const int row_end = wl.active_end[u];
@@ -589,9 +590,9 @@ __device__ __forceinline__ void gate_up_rows_packed(const bf16_t *__restrict__ x
 __global__ __launch_bounds__(256, 2) void gate_up_stream_packed_kernel(
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ w_gate_up,
     const int32_t *__restrict__ perm, WorkList wl, bf16_t *__restrict__ hidden, int H, int K,
-    int I) {
+    int I, int want) {
     const int u = blockIdx.y;
-    const int n_active = wl.hdr[0];
+    const int n_active = (want != kRegimeAny && wl.hdr[2] != want) ? 0 : wl.hdr[0];
     const int e = wl.active[u];
     const int row_beg = wl.active_beg[u];
     const int row_end = wl.active_end[u];
@@ -669,9 +670,9 @@ __device__ __forceinline__ void down_rows_packed(const bf16_t *__restrict__ hidd
 // grid (H/128, max active experts): each wavefront one block of 32 output features
 __global__ __launch_bounds__(256) void down_stream_packed_kernel(
     const bf16_t *__restrict__ hidden, const bf16_t *__restrict__ w_down, WorkList wl,
-    float *__restrict__ y_pairs, int H, int I) {
+    float *__restrict__ y_pairs, int H, int I, int want) {
     const int u = blockIdx.y;
-    const int n_active = wl.hdr[0];
+    const int n_active = (want != kRegimeAny && wl.hdr[2] != want) ? 0 : wl.hdr[0];
     const int e = wl.active[u];
     const int row_beg = wl.active_beg[u];
     const int row_end = wl.active_end[u];
@@ -832,31 +833,31 @@ static int max_active(const beam_shape &s) {
 
 hipError_t launch_gate_up_stream(const beam_shape &s, const void *x, const void *w_gate_up,
                                  const int32_t *offsets, const int32_t *perm, const WorkList &wl,
-                                 void *hidden, hipStream_t st) {
+                                 void *hidden, hipStream_t st, int want) {
     (void)offsets;
     if (s.weight_layout == BEAM_WEIGHTS_PACKED)
         gate_up_stream_packed_kernel<<<dim3(s.I / 32, max_active(s)), 256, 0, st>>>(
             (const bf16_t *)x, (const bf16_t *)w_gate_up, perm, wl, (bf16_t *)hidden, s.H, s.K,
-            s.I);
+            s.I, want);
     else
         gate_up_stream_kernel<<<dim3(s.I / 16, max_active(s)), 256, 0, st>>>(
             (const bf16_t *)x, (const bf16_t *)w_gate_up, perm, wl, (bf16_t *)hidden, s.H, s.K,
-            s.I);
+            s.I, want);
     return hipGetLastError();
 }
 
 hipError_t launch_down_stream(const beam_shape &s, const void *hidden, const void *w_down,
                               const int32_t *offsets, const WorkList &wl, float *y_pairs,
-                              hipStream_t st) {
+                              hipStream_t st, int want) {
     constexpr int FT = 2;
     (void)offsets;
     if (s.weight_layout == BEAM_WEIGHTS_PACKED)
         down_stream_packed_kernel<<<dim3(s.H / 128, max_active(s)), 256, 0, st>>>(
-            (const bf16_t *)hidden, (const bf16_t *)w_down, wl, y_pairs, s.H, s.I);
+            (const bf16_t *)hidden, (const bf16_t *)w_down, wl, y_pairs, s.H, s.I, want);
     else
         down_stream_kernel<FT><<<dim3((s.H + 64 * FT - 1) / (64 * FT), max_active(s)), 256, 0,
                                  st>>>((const bf16_t *)hidden, (const bf16_t *)w_down, wl, y_pairs,
-                                       s.H, s.I);
+                                       s.H, s.I, want);
     return hipGetLastError();
 }
 

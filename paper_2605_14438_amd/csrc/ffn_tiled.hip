@@ -396,7 +396,7 @@ __global__ __launch_bounds__(256, OCC) void ffn_tile_kernel(
     const int32_t *__restrict__ wl_hdr, const int32_t *__restrict__ tile_expert,
     const int32_t *__restrict__ tile_row0, bf16_t *__restrict__ hidden_out,
     float *__restrict__ y_out, int H, int K, int I, int n_col_tiles, int k_split,
-    size_t slice_stride) {
+    size_t slice_stride, int want) {
     __shared__ u32x4 As[2 * kTileM * 2 * KS];
     // Item order: the row tiles of an expert in groups of up to kRowGroup (a group
     // never spans two experts); inside a group the column tile is the slow index
@@ -405,7 +405,8 @@ __global__ __launch_bounds__(256, OCC) void ffn_tile_kernel(
     // The items of a group are the range [F * n_col_tiles, (F + size) * n_col_tiles)
     // with F the list index of its first row tile, so item / n_col_tiles is always
     // a row tile of the item's own group, from which the group is reconstructed.
-    const int n_tiles = wl_hdr[1];
+    // not the regime chosen on the device: no tiles for this kernel, every workgroup leaves
+    const int n_tiles = (want != kRegimeAny && wl_hdr[2] != want) ? 0 : wl_hdr[1];
     // with a split reduction: all items of part 0, then all of part 1, ...
     const int n_base = n_tiles * n_col_tiles;
     const int n_work = n_base * k_split;
@@ -450,12 +451,12 @@ bool tiled_ffn_supported(const beam_shape &s) {
 template <bool GATE_UP>
 static void launch_tile(const beam_shape &s, const bf16_t *a, const bf16_t *w,
                         const int32_t *offsets, const int32_t *perm, const WorkList &wl,
-                        bf16_t *hidden, float *y, int nct, int k_split, hipStream_t st) {
+                        bf16_t *hidden, float *y, int nct, int k_split, hipStream_t st, int want) {
     const bool packed = s.weight_layout == BEAM_WEIGHTS_PACKED;
 #define BEAM_LAUNCH_TILE(KS_, OCC_, PK)                                                        \
     ffn_tile_kernel<kWavesM, KS_, OCC_, GATE_UP, PK><<<256 * OCC_, 256, 0, st>>>(              \
         a, w, offsets, perm, wl.hdr, wl.tile_expert, wl.tile_row0, hidden, y, s.H, s.K, s.I, nct, \
-        k_split, (size_t)s.T * s.K * s.H)
+        k_split, (size_t)s.T * s.K * s.H, want)
     // Two schedules of the same tile body.  "Dense": 64-wide K-steps, two
     // workgroups per CU, whose MFMAs cover each other's prologue, epilogue and
     // barriers; the faster one when the reduction is short and the work MFMA
@@ -478,9 +479,9 @@ static void launch_tile(const beam_shape &s, const bf16_t *a, const bf16_t *w,
 
 hipError_t launch_gate_up_tiled(const beam_shape &s, const void *x, const void *w_gate_up,
                                 const int32_t *offsets, const int32_t *perm, const WorkList &wl,
-                                void *hidden, hipStream_t st) {
+                                void *hidden, hipStream_t st, int want) {
     launch_tile<true>(s, (const bf16_t *)x, (const bf16_t *)w_gate_up, offsets, perm, wl,
-                      (bf16_t *)hidden, nullptr, s.I / (kTileN / 2), 1, st);
+                      (bf16_t *)hidden, nullptr, s.I / (kTileN / 2), 1, st, want);
     return hipGetLastError();
 }
 
@@ -488,9 +489,9 @@ hipError_t launch_gate_up_tiled(const beam_shape &s, const void *x, const void *
 // the reduction; I / (16 * kKSteps) must be a multiple of k_split.
 hipError_t launch_down_tiled(const beam_shape &s, const void *hidden, const void *w_down,
                              const int32_t *offsets, const WorkList &wl, float *y_pairs,
-                             hipStream_t st, int k_split) {
+                             hipStream_t st, int k_split, int want) {
     launch_tile<false>(s, (const bf16_t *)hidden, (const bf16_t *)w_down, offsets, nullptr, wl,
-                       nullptr, y_pairs, s.H / kTileN, k_split, st);
+                       nullptr, y_pairs, s.H / kTileN, k_split, st, want);
     return hipGetLastError();
 }
 

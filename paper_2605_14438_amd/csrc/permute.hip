@@ -10,6 +10,8 @@
 // Placement uses only prefix sums and wavefront ballots, never atomics on the
 // destination, so the result is the same on every run.  When the whole input
 // is one chunk (decode batches) the three steps run as one launch.
+#include <cstdlib>
+
 #include "common.hpp"
 #include "topk.hpp"
 
@@ -88,18 +90,41 @@ __global__ __launch_bounds__(64) void count_kernel(const int32_t *__restrict__ m
 // one expert can own most of the tiles, and its thread would otherwise write
 // them one by one.
 __device__ __forceinline__ void emit_work_list(int e, int N, int count, int offset,
-                                               const WorkList &wl, int *scratch) {
+                                               const WorkList &wl, int *scratch,
+                                               bool longest_first) {
     __shared__ int tile_end[256];   // inclusive prefix of the experts' tile counts
     __shared__ int row_beg[256];
-    int total;
+    // Order of the active-expert list, which the streaming kernels walk one workgroup set
+    // per entry.  longest_first (asked for when those kernels may run): experts that need
+    // several passes over their weights come first (more than four passes, then more than
+    // one, then the rest; expert order inside a class), so that the long-running workgroup
+    // sets (a shared expert's above all) start first instead of forming the tail.  One scan
+    // of the three class flags packed ten bits apiece gives every expert its position.
     const int has = (e < N && count > 0) ? 1 : 0;
-    const int slot = block_exclusive_scan_256(has, scratch, &total);
+    int cls = 2;
+    if (longest_first) cls = count > 4 * kStreamRows ? 0 : (count > kStreamRows ? 1 : 2);
+    int packed_total;
+    const int packed_before = block_exclusive_scan_256(has << (10 * cls), scratch, &packed_total);
+    const int t0 = packed_total & 1023, t1 = (packed_total >> 10) & 1023;
+    const int n_active = t0 + t1 + (packed_total >> 20);
     if (has) {
+        const int within = (packed_before >> (10 * cls)) & 1023;
+        const int slot = within + (cls > 0 ? t0 : 0) + (cls > 1 ? t1 : 0);
         wl.active[slot] = e;
         wl.active_beg[slot] = offset;
         wl.active_end[slot] = offset + count;
     }
-    if (threadIdx.x == 0) wl.hdr[0] = total;
+    if (threadIdx.x == 0) wl.hdr[0] = n_active;
+    // Regime of the expert GEMMs, from the realised counts: the streaming kernels read an
+    // expert's weights once per pass of kStreamRows rows, the tiled GEMM about once; measured
+    // on the Qwen3-shaped layer (T = 128 .. 4096, keep 15 % .. 100 %, uniform and skewed
+    // routing) the streaming kernels win while the passes stay within 1.3 per active expert.
+    int passes;
+    (void)block_exclusive_scan_256(e < N ? (count + kStreamRows - 1) / kStreamRows : 0, scratch,
+                                   &passes);
+    if (threadIdx.x == 0)
+        wl.hdr[2] = (10 * passes > 13 * n_active) ? kRegimeTiled : kRegimeStream;
+    int total;
     const int nt = e < N ? tiles_of(count) : 0;
     const int tbase = block_exclusive_scan_256(nt, scratch, &total);
     if (threadIdx.x < 256) {
@@ -163,7 +188,7 @@ __global__ __launch_bounds__(256) void chunk_prefix_kernel(const int32_t *__rest
 __global__ __launch_bounds__(256) void scan_kernel(int32_t *__restrict__ counts,
                                                    int32_t *__restrict__ offsets,
                                                    int32_t *__restrict__ num_pairs, int N,
-                                                   WorkList wl) {
+                                                   WorkList wl, int longest_first) {
     __shared__ int scratch[256];
     const int e = threadIdx.x;
     const int run = e < N ? counts[e] : 0;
@@ -174,12 +199,12 @@ __global__ __launch_bounds__(256) void scan_kernel(int32_t *__restrict__ counts,
         offsets[N] = total;
         *num_pairs = total;
     }
-    emit_work_list(e, N, run, excl, wl, scratch);
+    emit_work_list(e, N, run, excl, wl, scratch, longest_first != 0);
 }
 
 // Work list alone, for callers that hand in expert_offsets directly.
 __global__ __launch_bounds__(256) void work_list_kernel(const int32_t *__restrict__ offsets, int N,
-                                                        WorkList wl) {
+                                                        WorkList wl, int longest_first) {
     __shared__ int scratch[256];
     const int e = threadIdx.x;
     int off = 0, cnt = 0;
@@ -188,7 +213,7 @@ __global__ __launch_bounds__(256) void work_list_kernel(const int32_t *__restric
         cnt = offsets[e + 1] - off;
         if (cnt < 0) cnt = 0;
     }
-    emit_work_list(e, N, cnt, off, wl, scratch);
+    emit_work_list(e, N, cnt, off, wl, scratch, longest_first != 0);
 }
 
 __global__ __launch_bounds__(64) void scatter_kernel(const int32_t *__restrict__ masked_ids,
@@ -325,11 +350,14 @@ __device__ __forceinline__ void permute_chunk_body(const int32_t *ids, ChunkShar
             *num_pairs = total;
             wl.hdr[0] = t_has;
             wl.hdr[1] = t_tiles;
+            wl.hdr[2] = kRegimeStream;   // a handful of pairs: never the tiled GEMM's case
         }
         if (has) {
-            wl.active[s_has - 1] = tid;
-            wl.active_beg[s_has - 1] = excl;
-            wl.active_end[s_has - 1] = excl + cnt;
+            // descending expert id: the shared experts (the last ids, every token's rows)
+            // come first in the list the streaming kernels walk
+            wl.active[t_has - s_has] = tid;
+            wl.active_beg[t_has - s_has] = excl;
+            wl.active_end[t_has - s_has] = excl + cnt;
         }
         for (int i = 0; i < nt; ++i) {
             wl.tile_expert[s_tiles - nt + i] = tid;
@@ -442,7 +470,7 @@ constexpr int kOneWgMaxPairs = 64 * kOneWgWaves * kOneWgGroups;
 __global__ __launch_bounds__(64 * kOneWgWaves) void permute_one_workgroup_kernel(
     const int32_t *__restrict__ masked_ids, int32_t *__restrict__ counts,
     int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm,
-    int32_t *__restrict__ num_pairs, int TK, int N, WorkList wl) {
+    int32_t *__restrict__ num_pairs, int TK, int N, WorkList wl, int longest_first) {
     __shared__ int pos[kOneWgWaves][256];   // per wavefront and expert: count, then next position
     __shared__ int scratch[256];
     const int tid = threadIdx.x;
@@ -495,7 +523,7 @@ __global__ __launch_bounds__(64 * kOneWgWaves) void permute_one_workgroup_kernel
         offsets[N] = total;
         *num_pairs = total;
     }
-    emit_work_list(tid, N, cnt, excl, wl, scratch);
+    emit_work_list(tid, N, cnt, excl, wl, scratch, longest_first != 0);
     __syncthreads();
 #pragma unroll
     for (int q = 0; q < kOneWgGroups; ++q) {
@@ -520,8 +548,9 @@ __global__ __launch_bounds__(64 * kOneWgWaves) void permute_one_workgroup_kernel
 hipError_t launch_permute(const beam_shape &s, const int32_t *masked_ids, int32_t *counts,
                           int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *num_pairs,
                           int32_t *blk_counts, int32_t *blk_base, int nchunk, const WorkList &wl,
-                          hipStream_t st) {
+                          hipStream_t st, bool longest_first) {
     const int TK = s.T * s.K;
+    const int lf = longest_first && !(getenv("BEAM_TUNE_LPT") && atoi(getenv("BEAM_TUNE_LPT")) == 0);
     if (nchunk == 1) {
         permute_single_chunk_kernel<<<1, 256, 0, st>>>(masked_ids, counts, offsets, perm, inv_perm,
                                                        num_pairs, TK, s.N, wl);
@@ -529,22 +558,23 @@ hipError_t launch_permute(const beam_shape &s, const int32_t *masked_ids, int32_
     }
     if (TK <= kOneWgMaxPairs) {
         permute_one_workgroup_kernel<<<1, 64 * kOneWgWaves, 0, st>>>(
-            masked_ids, counts, offsets, perm, inv_perm, num_pairs, TK, s.N, wl);
+            masked_ids, counts, offsets, perm, inv_perm, num_pairs, TK, s.N, wl, lf);
         return hipGetLastError();
     }
     count_kernel<<<nchunk, 64, 0, st>>>(masked_ids, blk_counts, TK, s.N);
     BEAM_CHECK_LAUNCH();
     chunk_prefix_kernel<<<s.N, 256, 0, st>>>(blk_counts, blk_base, counts, nchunk);
     BEAM_CHECK_LAUNCH();
-    scan_kernel<<<1, 256, 0, st>>>(counts, offsets, num_pairs, s.N, wl);
+    scan_kernel<<<1, 256, 0, st>>>(counts, offsets, num_pairs, s.N, wl, lf);
     BEAM_CHECK_LAUNCH();
     scatter_kernel<<<nchunk, 64, 0, st>>>(masked_ids, offsets, blk_base, perm, inv_perm, TK, s.N);
     return hipGetLastError();
 }
 
 hipError_t launch_work_list(const beam_shape &s, const int32_t *offsets, const WorkList &wl,
-                            hipStream_t st) {
-    work_list_kernel<<<1, 256, 0, st>>>(offsets, s.N, wl);
+                            hipStream_t st, bool longest_first) {
+    const int lf = longest_first && !(getenv("BEAM_TUNE_LPT") && atoi(getenv("BEAM_TUNE_LPT")) == 0);
+    work_list_kernel<<<1, 256, 0, st>>>(offsets, s.N, wl, lf);
     return hipGetLastError();
 }
 

@@ -316,6 +316,12 @@ FWD_CASES = [
     synth.LayerConfig("long_reduction", 13, T=2500, H=512, N=4, K=2, I=4096, dtype="bf16",
                       keep=0.5),
     PREFILL_SMALL, PREFILL_SMALL.with_(T=1100, keep=1.0), PREFILL_SMALL.with_(T=2200, keep=0.7),
+    # batches between decode and prefill size, where the kernel family of the expert GEMMs is
+    # chosen on the device from the realised counts: a skewed router with every pair kept
+    # (several passes per expert: the tiled GEMM) and a uniform one at a low keep rate (one
+    # pass per expert: the streaming kernels)
+    CFG["qwen3_prefill"].with_(T=300, keep=1.0, I=128), CFG["qwen3_decode"].with_(T=300, keep=0.3, I=128),
+    PREFILL_SMALL.with_(T=1000, keep=1.0), PREFILL_SMALL.with_(T=600, keep=0.1, router_skew="none"),
 ]
 
 
