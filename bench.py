@@ -552,11 +552,15 @@ def main():
             wsets = device_weight_sets(base, 2, torch, synth.seed_for(base, 98))
             for T in Ts:
                 c = base.with_(T=T)
-                dd = synth.make_layer(c, with_experts=False)
-                gg = hp.upload(c, dd)
-                pt = measure_point(c, dd, gg, wsets, 20 if T <= 64 else 10, 10, torch, beam, hp,
-                                   packed=args.packed)
+                for sweep in range(8):     # a single token may keep nothing: next draw then
+                    dd = synth.make_layer(c, sweep=sweep, with_experts=False)
+                    gg = hp.upload(c, dd)
+                    pt = measure_point(c, dd, gg, wsets, 20 if T <= 64 else 10, 10, torch, beam,
+                                       hp, packed=args.packed)
+                    if pt["P"] > 0:
+                        break
                 pt["weights"] += ", drawn on the device"
+                pt["input_draw"] = sweep
                 points.append(pt)
                 del dd, gg
             del wsets

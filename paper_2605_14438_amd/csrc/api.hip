@@ -3,7 +3,6 @@
 // Nothing here allocates, copies to the host or synchronises (the stage-timed
 // measurement entry point excepted).
 #include <atomic>
-#include <cstdlib>
 
 #include "common.hpp"
 
@@ -148,12 +147,6 @@ Regime ffn_regime(const beam_shape &s) {
         return (s.weight_layout == BEAM_WEIGHTS_PACKED || TK > 32L * s.N) ? Regime::Tiled
                                                                           : Regime::Generic;
     if (!tiled_ok) return Regime::Stream;
-    if (getenv("BEAM_TUNE_REGIME")) {
-        const int r = atoi(getenv("BEAM_TUNE_REGIME"));
-        if (r == 1) return Regime::Tiled;
-        if (r == 2) return Regime::Stream;
-        if (r == 3) return (long)s.T * s.K > 32L * s.N ? Regime::Tiled : Regime::Stream;
-    }
     if (TK <= kChunk || TK <= 8L * s.N) return Regime::Stream;   // a few rows per expert at most
     if (TK > 256L * s.N) return Regime::Tiled;
     if (down_split_k_if_tiled(s) > 1) return TK > 32L * s.N ? Regime::Tiled : Regime::Stream;

@@ -10,7 +10,6 @@
 // Placement uses only prefix sums and wavefront ballots, never atomics on the
 // destination, so the result is the same on every run.  When the whole input
 // is one chunk (decode batches) the three steps run as one launch.
-#include <cstdlib>
 
 #include "common.hpp"
 #include "topk.hpp"
@@ -118,12 +117,15 @@ __device__ __forceinline__ void emit_work_list(int e, int N, int count, int offs
     // Regime of the expert GEMMs, from the realised counts: the streaming kernels read an
     // expert's weights once per pass of kStreamRows rows, the tiled GEMM about once; measured
     // on the Qwen3-shaped layer (T = 128 .. 4096, keep 15 % .. 100 %, uniform and skewed
-    // routing) the streaming kernels win while the passes stay within 1.3 per active expert.
+    // routing) the streaming kernels win while the passes stay within 1.3 per active expert
+    // and no expert has more than four passes (its workgroups would run them back to back
+    // while the rest of the chip idles: a shared expert from 129 tokens on).
     int passes;
     (void)block_exclusive_scan_256(e < N ? (count + kStreamRows - 1) / kStreamRows : 0, scratch,
                                    &passes);
     if (threadIdx.x == 0)
-        wl.hdr[2] = (10 * passes > 13 * n_active) ? kRegimeTiled : kRegimeStream;
+        wl.hdr[2] = (10 * passes > 13 * n_active || (longest_first && t0 > 0)) ? kRegimeTiled
+                                                                               : kRegimeStream;
     int total;
     const int nt = e < N ? tiles_of(count) : 0;
     const int tbase = block_exclusive_scan_256(nt, scratch, &total);
@@ -550,7 +552,7 @@ hipError_t launch_permute(const beam_shape &s, const int32_t *masked_ids, int32_
                           int32_t *blk_counts, int32_t *blk_base, int nchunk, const WorkList &wl,
                           hipStream_t st, bool longest_first) {
     const int TK = s.T * s.K;
-    const int lf = longest_first && !(getenv("BEAM_TUNE_LPT") && atoi(getenv("BEAM_TUNE_LPT")) == 0);
+    const int lf = longest_first ? 1 : 0;
     if (nchunk == 1) {
         permute_single_chunk_kernel<<<1, 256, 0, st>>>(masked_ids, counts, offsets, perm, inv_perm,
                                                        num_pairs, TK, s.N, wl);
@@ -573,7 +575,7 @@ hipError_t launch_permute(const beam_shape &s, const int32_t *masked_ids, int32_
 
 hipError_t launch_work_list(const beam_shape &s, const int32_t *offsets, const WorkList &wl,
                             hipStream_t st, bool longest_first) {
-    const int lf = longest_first && !(getenv("BEAM_TUNE_LPT") && atoi(getenv("BEAM_TUNE_LPT")) == 0);
+    const int lf = longest_first ? 1 : 0;
     work_list_kernel<<<1, 256, 0, st>>>(offsets, s.N, wl, lf);
     return hipGetLastError();
 }
