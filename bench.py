@@ -124,10 +124,15 @@ def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp, packed
     layer_flops = P * 6 * H * I + 4 * T * H * N
     gate_up_bytes = U * 2 * H * I * esz + T * H * esz
     gate_up_flops = P * 4 * H * I
+    # down: the touched experts' H x I weights, the hidden rows in, the fp32 pair rows out
+    down_bytes = U * H * I * esz + P * I * esz + P * H * 4
+    down_flops = P * 2 * H * I
     t_roof_us = max(layer_bytes / (HBM_PEAK_GBS * 1e3), layer_flops / (MFMA_BF16_PEAK_TFLOPS * 1e6))
     return {
         "workload": f"{cfg.name} T={T} keep={cfg.keep}", "T": T, "P": P, "U": U,
         "weights": "packed" if packed else "plain",
+        "stage_algorithmic": {"gate_up": {"bytes": gate_up_bytes, "flops": gate_up_flops},
+                              "down": {"bytes": down_bytes, "flops": down_flops}},
         # 6 stages; the grouping of more than 8192 pairs is 4 launches, the tiled logits GEMM repacks the
         # heads first, a gated shared expert adds one; up to 32 tokens Top-K and grouping are
         # one launch; tiny batches take the three-kernel path
@@ -620,9 +625,11 @@ def main():
                    "kept_pairs": main_pt["P"],
                    "experts_touched": main_pt["U"], "weight_sets_rotated": len(sets),
                    "weights": main_pt["weights"],
+                   "point": main_pt["workload"] + " " + main_pt["weights"],
                    "input_setup_s": round(t_gen, 1)},
         "layer": {k: main_pt[k] for k in ("layer_GBs", "layer_TFLOPs", "frac_hbm", "frac_mfma",
-                                          "frac_of_roofline", "stage_us", "kernel_us")},
+                                          "frac_of_roofline", "stage_us", "kernel_us",
+                                          "stage_algorithmic")},
         "roofline": main_roofline,
         "cpu_baseline": cpu,
         "points": points,
