@@ -14,9 +14,13 @@ weights so that no step finds its weights in the 256 MB last-level cache.
 Prints ONE JSON line.  `roofline` describes the dominant kernel (gate/up
 GEMM): algorithmic bytes per launch / its mean duration measured with HIP
 events on the launch stream (`stage_us`: event to event; `kernel_us`: the same
-minus the bubble the event pairs add, see measure_point).  `cpu_baseline` is the plain CPU oracle timed on
-the host cores.  `points` holds further workload points (decode batch sizes,
-prefill) measured the same way.
+minus the bubble the event pairs add, see measure_point); `roofline.traffic` is the
+HBM bytes per launch that rocprofv3's FETCH_SIZE / WRITE_SIZE counters read for that kernel on
+that workload, carried from profiles/traffic.json while the kernel's sources are unchanged
+(measured_traffic).  `cpu_baseline` is the plain CPU oracle timed on the host cores.
+`points` holds the other workload points (decode batch sizes, the prefill grid, whole blocks
+with shared experts, the Mixtral-shaped and the large layer) measured the same way, each
+with its own `roofline`.
 """
 import argparse
 import json

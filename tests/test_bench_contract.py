@@ -38,7 +38,36 @@ def test_single_gpu_run_prints_one_json_line_with_the_agreed_keys():
     assert roof["bound"] in ("hbm", "mfma") and roof["unit"] in ("GB/s", "TFLOP/s")
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-9
     assert 0.3 < roof["frac"] < 1.0                  # an HBM-bound kernel cannot beat the peak
+    # measured HBM bytes per launch, carried from the tracked counter summary while the
+    # kernel sources are what they were then; a streaming kernel reads its weights once
+    assert roof["traffic"] is None or 0.95 < roof["traffic_over_algorithmic"] < 1.2
     cpu = rec["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]
     assert rec["value"] > 10 * cpu["value"]
     assert abs(rec["value"] - 64 / (rec["ms_per_step"] * 1e-3)) < 1e-6 * rec["value"]
+
+
+def test_traffic_table_is_used_only_while_the_kernel_sources_are_unchanged(monkeypatch):
+    """roofline.traffic comes from profiles/traffic.json (counter runs summarised by
+    paper_2605_14438_amd.profile_summary); a record is dropped as soon as the kernel's source
+    files no longer hash to what they were when it was taken."""
+    sys.path.insert(0, ROOT)
+    import bench
+    table = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))
+    recs = table["records"]
+    assert recs, "the traffic table is empty"
+    for r in recs:
+        assert r["kernel"] in ("gate_up", "down")
+        assert r["fetch_bytes"] > 0 and r["write_bytes"] >= 0 and r["forwards"] > 0
+        assert r["profile"].startswith("profiles/") and os.path.exists(os.path.join(ROOT, r["profile"]))
+        for f in r["source_files"]:
+            assert os.path.exists(os.path.join(ROOT, f)), f
+        got = bench.measured_traffic(r["workload"], r["kernel"])
+        if bench._sha16(r["source_files"]) == r["source_sha16"]:
+            assert got["bytes"] == r["fetch_bytes"] + r["write_bytes"]
+        else:
+            assert got is None
+    r = recs[0]
+    monkeypatch.setattr(bench, "_sha16", lambda paths: "0" * 16)
+    assert bench.measured_traffic(r["workload"], r["kernel"]) is None
+    assert bench.measured_traffic("no such workload", "gate_up") is None
