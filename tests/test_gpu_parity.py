@@ -322,6 +322,7 @@ FWD_CASES = [
     # pass per expert: the streaming kernels)
     CFG["qwen3_prefill"].with_(T=300, keep=1.0, I=128), CFG["qwen3_decode"].with_(T=300, keep=0.3, I=128),
     PREFILL_SMALL.with_(T=1000, keep=1.0), PREFILL_SMALL.with_(T=600, keep=0.1, router_skew="none"),
+    PREFILL_SMALL.with_(T=600, keep=0.0),     # no pair at all in that zone: neither family has work
 ]
 
 
@@ -608,6 +609,11 @@ def _check_block_slots(cfg, res, ids_o, g_o, msk_o, g_shared, S):
     (BLOCK_F32, True, True, False), (BLOCK_F32, False, True, False),
     (BLOCK_PREFILL, False, True, False), (BLOCK_PREFILL, False, True, True),
     (BLOCK_PREFILL.with_(shared_gate=True, S=3, T=1029), True, False, True),
+    # between decode and prefill size the device chooses the kernel family: shared blocks
+    # with more than four streaming passes (300 rows) select the tiled GEMM whatever the
+    # routed experts hold; with 120 rows they do not
+    (BLOCK_SMALL.with_(T=300), True, True, True), (BLOCK_SMALL.with_(T=300, keep=0.1), True, True, False),
+    (BLOCK_SMALL.with_(T=120, keep=0.2), True, True, True),
 ], ids=lambda v: getattr(v, "name", str(v)))
 def test_moe_block_forward_small(cfg, use_gate, use_residual, packed):
     _log(f"moe_block_forward {cfg} gate={use_gate} residual={use_residual} packed={packed}")
