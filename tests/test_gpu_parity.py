@@ -548,14 +548,15 @@ def _prefix_check(name, Tmax, T, packed):
 
 
 @pytest.mark.parametrize("T,packed", [(1, False), (16, False), (2048, True), (2048, False),
-                                      (600, True), (600, False)])   # split down reduction
+                                      (600, True), (600, False),    # split down reduction
+                                      (1, True), (16, True)])       # the benchmark's decode points
 def test_moe_forward_mixtral_full_size(T, packed):
     kept = _prefix_check("mixtral", 2048, T, packed)
     if T == 2048:
         assert 0.5 < kept.mean() / 2 < 0.7          # ~60% of the Top-2 pairs kept
 
 
-@pytest.mark.parametrize("T,packed", [(64, False), (8192, True)])
+@pytest.mark.parametrize("T,packed", [(64, False), (8192, True), (64, True)])
 def test_moe_forward_large_full_size(T, packed):
     kept = _prefix_check("large", 8192, T, packed)
     if T == 8192:
@@ -736,6 +737,10 @@ QWEN3_SHARED = synth.LayerConfig("qwen3_shared", 14, T=4096, H=2048, N=128, K=8,
 @pytest.mark.parametrize("name,T,packed", [("qwen15_moe", 64, False), ("qwen15_moe", 1, False),
                                            ("dsv2_lite", 64, False), ("dsv2_lite", 4096, True),
                                            ("qwen15_moe", 2048, True),
+                                           # the benchmark's block points, and batches where the
+                                           # shared blocks' row count decides the kernel family
+                                           ("qwen15_moe", 64, True), ("dsv2_lite", 64, True),
+                                           ("qwen15_moe", 128, True), ("dsv2_lite", 256, True),
                                            (QWEN3_SHARED, 4096, True), (QWEN3_SHARED, 6000, True),
                                            (QWEN3_SHARED, 2100, False)],
                          ids=lambda v: getattr(v, "name", str(v)))
