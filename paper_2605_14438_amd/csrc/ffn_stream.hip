@@ -259,13 +259,26 @@ __global__ __launch_bounds__(256) void down_combine_token_kernel(
         c = c < H ? c : H - 1;
         wrow[f] = w_down + (size_t)c * I + g * 8;
     }
+    // One or two kept slots and a long reduction: the wavefronts that would idle take
+    // parts of the reduction (four parts of one slot, two of each of two), added in order
+    // below; a short reduction stays whole and bit-identical to the staged path.
+    const int nkept = __popcll(kept);
+    int parts = 1;
+    if (I >= 4096 && nkept >= 1 && nkept <= 2 && I % ((4 / nkept) * 128) == 0) parts = 4 / nkept;
+    const int len = I / parts;
     int ord = 0;
     for (uint64_t m = kept; m; m &= m - 1, ++ord) {
-        if ((ord & 3) != wave) continue;  // wave-uniform
+        int part = 0;
+        if (parts == 1) {
+            if ((ord & 3) != wave) continue;  // wave-uniform
+        } else {
+            if (wave % nkept != ord) continue;
+            part = wave / nkept;
+        }
         const int k = __builtin_ctzll(m);
         const int e = masked_s[wave][k];
-        const bf16_t *hp = hidden + ((size_t)t * slots + k) * I + g * 8;
-        const size_t eoff = (size_t)e * H * I;
+        const bf16_t *hp = hidden + ((size_t)t * slots + k) * I + g * 8 + part * len;
+        const size_t eoff = (size_t)e * H * I + (size_t)part * len;
         f32x4 acc[FT];
 #pragma unroll
         for (int f = 0; f < FT; ++f) acc[f] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -291,7 +304,7 @@ __global__ __launch_bounds__(256) void down_combine_token_kernel(
         };
         load(0, 0);
         int kk = 0;
-        for (; kk + 256 < I; kk += 256) {
+        for (; kk + 256 < len; kk += 256) {
             load(1, kk + 128);
             __builtin_amdgcn_sched_barrier(0);
             mma(0);
@@ -301,7 +314,7 @@ __global__ __launch_bounds__(256) void down_combine_token_kernel(
             mma(1);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (kk + 128 < I) {
+        if (kk + 128 < len) {
             load(1, kk + 128);
             __builtin_amdgcn_sched_barrier(0);
             mma(0);
@@ -315,7 +328,7 @@ __global__ __launch_bounds__(256) void down_combine_token_kernel(
 #pragma unroll
             for (int f = 0; f < FT; ++f)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) y_s[ord][f][g][r] = acc[f][r];
+                for (int r = 0; r < 4; ++r) y_s[ord * parts + part][f][g][r] = acc[f][r];
         }
     }
     __syncthreads();
@@ -336,7 +349,11 @@ __global__ __launch_bounds__(256) void down_combine_token_kernel(
             for (uint64_t m = kept; m; m &= m - 1, ++j) {
                 const float gk = w_s[0][__builtin_ctzll(m)];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) tot[r] = fmaf(gk, y_s[j][f][g][r], tot[r]);
+                for (int r = 0; r < 4; ++r) {
+                    float y = y_s[j * parts][f][g][r];
+                    for (int p = 1; p < parts; ++p) y += y_s[j * parts + p][f][g][r];
+                    tot[r] = fmaf(gk, y, tot[r]);
+                }
             }
             uint2 q;
             q.x = (uint32_t)f32_to_bf16(tot[0]) | ((uint32_t)f32_to_bf16(tot[1]) << 16);
@@ -744,13 +761,28 @@ __global__ __launch_bounds__(256) void down_combine_token_packed_kernel(
         if (num_pairs_opt && lane == 0) atomicAdd(num_pairs_opt, __popcll(kept));
     }
     const int ksteps = I >> 4;
+    // One or two kept slots and a long reduction (a few experts with a wide FFN): the
+    // wavefronts that would idle take parts of the reduction instead, four parts of one
+    // slot or two parts of each of two; the parts are added in order below.  (A short
+    // reduction stays whole, which keeps this path bit-identical to the staged one there.)
+    const int nkept = __popcll(kept);
+    int parts = 1;
+    if (I >= 4096 && nkept >= 1 && nkept <= 2 && ksteps % ((4 / nkept) * CH) == 0) parts = 4 / nkept;
+    const int len = ksteps / parts;
     int ord = 0;
     for (uint64_t m = kept; m; m &= m - 1, ++ord) {
-        if ((ord & 3) != wave) continue;  // wave-uniform
+        int part = 0;
+        if (parts == 1) {
+            if ((ord & 3) != wave) continue;  // wave-uniform
+        } else {
+            if (wave % nkept != ord) continue;
+            part = wave / nkept;
+        }
         const int k = __builtin_ctzll(m);
         const int e = masked_s[wave][k];
-        const bf16_t *hp = hidden + ((size_t)t * slots + k) * I + kh * 8;
-        const bf16_t *wp = w_down + (((size_t)e * (H >> 5) + rb) * ksteps) * 512 + lane * 8;
+        const bf16_t *hp = hidden + ((size_t)t * slots + k) * I + kh * 8 + (size_t)part * len * 16;
+        const bf16_t *wp = w_down + (((size_t)e * (H >> 5) + rb) * ksteps + (size_t)part * len) * 512 +
+                           lane * 8;
         f32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
@@ -771,7 +803,7 @@ __global__ __launch_bounds__(256) void down_combine_token_packed_kernel(
         };
         load(0, 0);
         int kk = 0;
-        for (; kk + 2 * CH < ksteps; kk += 2 * CH) {
+        for (; kk + 2 * CH < len; kk += 2 * CH) {
             load(1, kk + CH);
             __builtin_amdgcn_sched_barrier(0);
             mma(0);
@@ -781,7 +813,7 @@ __global__ __launch_bounds__(256) void down_combine_token_packed_kernel(
             mma(1);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (kk + CH < ksteps) {
+        if (kk + CH < len) {
             load(1, kk + CH);
             __builtin_amdgcn_sched_barrier(0);
             mma(0);
@@ -791,7 +823,7 @@ __global__ __launch_bounds__(256) void down_combine_token_packed_kernel(
         }
         if (l32 == 0) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) y_s[ord][kh][r] = acc[r];
+            for (int r = 0; r < 16; ++r) y_s[ord * parts + part][kh][r] = acc[r];
         }
     }
     __syncthreads();
@@ -812,7 +844,11 @@ __global__ __launch_bounds__(256) void down_combine_token_packed_kernel(
             for (uint64_t m = kept; m; m &= m - 1, ++j) {
                 const float gk = w_s[0][__builtin_ctzll(m)];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) tot[i] = fmaf(gk, y_s[j][kh][rg * 4 + i], tot[i]);
+                for (int i = 0; i < 4; ++i) {
+                    float y = y_s[j * parts][kh][rg * 4 + i];
+                    for (int p = 1; p < parts; ++p) y += y_s[j * parts + p][kh][rg * 4 + i];
+                    tot[i] = fmaf(gk, y, tot[i]);
+                }
             }
             uint2 q;
             q.x = (uint32_t)f32_to_bf16(tot[0]) | ((uint32_t)f32_to_bf16(tot[1]) << 16);
