@@ -30,6 +30,7 @@ import json
 import os
 import re
 import subprocess
+import sys
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 CSRC = "paper_2605_14438_amd/csrc"
@@ -70,9 +71,12 @@ def sha16(paths):
 
 def one_csv(run, sub, suffix):
     hits = glob.glob(os.path.join(run, sub, "**", "*" + suffix), recursive=True)
-    if len(hits) != 1:
-        raise SystemExit(f"{run}/{sub}: expected one *{suffix}, found {len(hits)}")
-    return hits[0]
+    if not hits:
+        raise SystemExit(f"{run}/{sub}: no *{suffix}")
+    if len(hits) > 1:      # output of an earlier run left in the folder: the newest file counts
+        hits.sort(key=os.path.getmtime)
+        print(f"{run}/{sub}: {len(hits)} files *{suffix}, taking the newest", file=sys.stderr)
+    return hits[-1]
 
 
 def short(kernel):
