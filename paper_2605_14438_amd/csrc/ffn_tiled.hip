@@ -5,8 +5,9 @@
 // Each segment is cut into row tiles of BM = 128 rows (the work list; this is
 // the "block alignment" of App. A.4 without padding the index array: rows past
 // the end of a segment are clamped on load and masked on store).  One workgroup
-// of 4 wavefronts (WM x 4/WM) computes a BM x 256 output tile, each wavefront a
-// (BM/WM) x (64*WM) sub-tile of 32x32 MFMA tiles, K-loop in steps of 16*KS:
+// of NW = 4 or 8 wavefronts side by side computes a BM x (64 NW) output tile, each
+// wavefront all BM rows of 64 columns as 32x32 MFMA tiles, K-loop in steps of 16*KS
+// (column counts below are for NW = 4; with eight wavefronts a tile is twice as wide):
 //
 //   GATE_UP:  A = x rows gathered through perm (token = perm[row] / K),
 //             B = 128 gate rows and the 128 matching up rows of W_gate_up[e],
@@ -40,7 +41,8 @@
 //
 // Work order.  Workgroups are handed to the 8 XCDs round-robin by linear id,
 // and each XCD has its own L2.  The grid is persistent: 512 workgroups, two per
-// CU, workgroup b on XCD b % 8 as its member b / 8.  The (row tile, column
+// CU (256 of eight wavefronts, one per CU, in the wide schedule), workgroup b on XCD
+// b % 8 as its member b / 8.  The (row tile, column
 // tile) items are ordered by groups of up to four row tiles of one expert,
 // inside a group by column tile, then by row tile, and this sequence
 // is cut into chunks of 64 consecutive items; chunk c goes to XCD c % 8, one
@@ -107,18 +109,20 @@ struct TileItem {
 // slice_stride (elements).  With few, long items (a handful of experts with a
 // long reduction) this is what fills the chip and evens out its last round;
 // the aggregation adds the parts in slice order.
-template <int BM, int WM, int KS, bool GATE_UP, bool PACKED, bool CHAIN, bool COL_GUARD,
+template <int BM, int WM, int KS, bool GATE_UP, bool PACKED, bool CHAIN, bool COL_GUARD, int NW,
           typename NextItem>
 __device__ __forceinline__ void ffn_tile_run(
     u32x4 *As, const bf16_t *__restrict__ a_src, const bf16_t *__restrict__ w,
     const int32_t *__restrict__ perm, bf16_t *__restrict__ hidden_out, float *__restrict__ y_out,
     int H, int K, int I, bool stream_out, int k_split, size_t slice_stride, NextItem next_item) {
     constexpr int PR = 2 * KS;           // 16-byte pieces per LDS row (K-step of 16*KS indices)
-    constexpr int RPP = 256 / PR;        // tile rows copied per pass of the 256 threads
+    constexpr int NT = 64 * NW;          // threads; NW wavefronts, each 64 columns wide with WM == 1
+    constexpr int TN = kTileN * NW / 4;  // columns of the output tile
+    constexpr int RPP = NT / PR;         // tile rows copied per pass of the workgroup's threads
     constexpr int AP = BM / RPP;         // A rows per thread
-    constexpr int WN = 4 / WM;
+    constexpr int WN = NW / WM;
     constexpr int WTM = BM / WM / 32;    // MFMA row tiles per wavefront
-    constexpr int WTN = 8 / WN;          // MFMA column tiles per wavefront (256 columns in all)
+    constexpr int WTN = (TN / 32) / WN;  // MFMA column tiles per wavefront (TN columns in all)
     static_assert(WM == 1 || WM == 2, "wavefront grid is 1x4 or 2x2");
     constexpr int kStage = BM * PR;      // uint4 per LDS stage
 
@@ -163,14 +167,14 @@ __device__ __forceinline__ void ffn_tile_run(
         if constexpr (PACKED) {                                                                 \
             /* 32-row block rb of this expert: (kdim/16) fragments of 512 elements */           \
             const int rows32 = (GATE_UP ? 2 * I : H) >> 5;                                      \
-            const int rb = (it).col_tile * 8 + nb;                                              \
+            const int rb = (it).col_tile * (TN / 32) + nb;                                      \
             bp[n] = w + ((size_t)(it).e * rows32 + rb) * (size_t)(kdim >> 4) * 512 + lane * 8;  \
         } else if constexpr (GATE_UP) {                                                         \
-            const int feat = (it).col_tile * (kTileN / 2) + (nb >> 1) * 32 + l32;               \
+            const int feat = (it).col_tile * (TN / 2) + (nb >> 1) * 32 + l32;                   \
             const int wrow = (nb & 1) ? I + feat : feat;                                        \
             bp[n] = w + ((size_t)(it).e * 2 * I + wrow) * H + kh * (8 * KS);                    \
         } else {                                                                                \
-            bp[n] = w + ((size_t)(it).e * H + (it).col_tile * kTileN + nb * 32 + l32) * I +     \
+            bp[n] = w + ((size_t)(it).e * H + (it).col_tile * TN + nb * 32 + l32) * I +         \
                     kh * (8 * KS);                                                              \
         }                                                                                       \
         if constexpr (!GATE_UP) bp[n] += (size_t)(it).slice * nk * kBKStep;                     \
@@ -307,7 +311,7 @@ __device__ __forceinline__ void ffn_tile_run(
         }
 
         // Epilogue of item `done`.
-        const int n0 = done.col_tile * (GATE_UP ? kTileN / 2 : kTileN);
+        const int n0 = done.col_tile * (GATE_UP ? TN / 2 : TN);
         if constexpr (GATE_UP) {
             // The weights were the MFMA A operand and the activations the B operand,
             // so in a 32x32 result tile lane l holds activation row l & 31 and, in
@@ -387,9 +391,10 @@ __device__ __forceinline__ void ffn_tile_run(
 // per CU, each walking (row tile, column tile) items.  Two 128-row workgroups
 // per CU measured faster than one 256-row workgroup (the second workgroup's
 // MFMAs cover the first one's prologue, epilogue and barriers) and than three
-// 64-row ones (more weight traffic per flop).
-template <int WM, int KS, int OCC, bool GATE_UP, bool PACKED>
-__global__ __launch_bounds__(256, OCC) void ffn_tile_kernel(
+// 64-row ones (more weight traffic per flop).  NW = 8: the two workgroups fused into
+// one of eight wavefronts on a tile twice as wide (see launch_tile).
+template <int WM, int KS, int OCC, bool GATE_UP, bool PACKED, int NW>
+__global__ __launch_bounds__(64 * NW, OCC) void ffn_tile_kernel(
     const bf16_t *__restrict__ a_src,   // GATE_UP: x [T,H];  DOWN: hidden [P,I]
     const bf16_t *__restrict__ w,       // GATE_UP: w_gate_up [N,2I,H];  DOWN: w_down [N,H,I]
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm,
@@ -437,7 +442,7 @@ __global__ __launch_bounds__(256, OCC) void ffn_tile_kernel(
     };
     // more rows of y_pairs than the last-level cache can hold until they are read again
     const bool stream_out = !GATE_UP && (size_t)n_tiles * kTileM * H * sizeof(float) > kStreamBytes;
-    ffn_tile_run<kTileM, WM, KS, GATE_UP, PACKED, OCC == 1, false>(
+    ffn_tile_run<kTileM, WM, KS, GATE_UP, PACKED, OCC == 1 && NW == 4, false, NW>(
         As, a_src, w, perm, hidden_out, y_out, H, K, I, stream_out, k_split, slice_stride,
         next_item);
 }
@@ -454,10 +459,10 @@ static void launch_tile(const beam_shape &s, const bf16_t *a, const bf16_t *w,
                         bf16_t *hidden, float *y, int nct, int k_split, hipStream_t st, int want) {
     const bool packed = s.weight_layout == BEAM_WEIGHTS_PACKED;
 #define BEAM_LAUNCH_TILE(KS_, OCC_, PK)                                                        \
-    ffn_tile_kernel<kWavesM, KS_, OCC_, GATE_UP, PK><<<256 * OCC_, 256, 0, st>>>(              \
+    ffn_tile_kernel<kWavesM, KS_, OCC_, GATE_UP, PK, 4><<<256 * OCC_, 256, 0, st>>>(           \
         a, w, offsets, perm, wl.hdr, wl.tile_expert, wl.tile_row0, hidden, y, s.H, s.K, s.I, nct, \
         k_split, (size_t)s.T * s.K * s.H, want)
-    // Two schedules of the same tile body.  "Dense": 64-wide K-steps, two
+    // Three schedules of the same tile body.  "Dense": 64-wide K-steps, two
     // workgroups per CU, whose MFMAs cover each other's prologue, epilogue and
     // barriers; the faster one when the reduction is short and the work MFMA
     // bound.  "Deep": 128-wide K-steps, one workgroup per CU with twice the
@@ -471,6 +476,19 @@ static void launch_tile(const beam_shape &s, const bf16_t *a, const bf16_t *w,
             BEAM_LAUNCH_TILE(8, 1, true);
             return;
         }
+    }
+    // "Wide": where the output width allows, the two workgroups of a CU become one of eight
+    // wavefronts side by side on a 128 x 512 tile: the same registers, LDS and MFMA work per
+    // CU, but the activation tile is loaded (and gathered) once for twice the columns, a sixth
+    // fewer load bytes per MFMA, which is what the K-step's time follows.  Measured against
+    // the dense schedule (Qwen3 shape): gate/up 799 -> 767 us at T = 16384 with every pair
+    // kept, 210 -> 197 at 15 %, 456 -> 441 at T = 8192; down 317 -> 305 at T = 8192,
+    // Mixtral shape T = 2048 419 -> 391, large layer T = 8192 349 -> 330.
+    if (packed && k_split == 1 && (GATE_UP ? (2 * s.I) % 512 == 0 : s.H % 512 == 0)) {
+        ffn_tile_kernel<kWavesM, kKSteps, 1, GATE_UP, true, 8><<<256, 512, 0, st>>>(
+            a, w, offsets, perm, wl.hdr, wl.tile_expert, wl.tile_row0, hidden, y, s.H, s.K, s.I,
+            nct / 2, k_split, (size_t)s.T * s.K * s.H, want);
+        return;
     }
     if (packed) BEAM_LAUNCH_TILE(kKSteps, kWorkgroupsPerCU, true);
     else BEAM_LAUNCH_TILE(kKSteps, kWorkgroupsPerCU, false);
@@ -553,7 +571,7 @@ __global__ __launch_bounds__(256, 2) void logits_tile_kernel(
         return true;
     };
     // down-GEMM roles: output width N2, reduction length H, a single expert
-    ffn_tile_run<kLogitsM, kWavesM, kLogitsKS, false, true, true, true>(
+    ffn_tile_run<kLogitsM, kWavesM, kLogitsKS, false, true, true, true, 4>(
         As, x, packed_heads, nullptr, nullptr, logits2, N2, 1, H, false, k_split,
         (size_t)Tn * N2, next_item);
 }
