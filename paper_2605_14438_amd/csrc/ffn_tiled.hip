@@ -244,6 +244,74 @@ __device__ __forceinline__ void ffn_tile_run(
             }
         }
     };
+    // The same K-step for an item whose tile holds at most 32*MT rows (the ragged last tile
+    // of an expert; MT = 1 or 2): only the first MT row tiles are multiplied, one fragment
+    // set per k-step, double buffered at k-step granularity.  The other accumulators stay
+    // at zero and their rows are masked on store.
+    auto compute_short = [&](int st, auto mt_c, auto prefetch, int kt_next) {
+        constexpr int MT = decltype(mt_c)::value;
+        constexpr bool PF = decltype(prefetch)::value;
+        u32x4 af[2][MT];
+        auto read_s = [&](int j, u32x4 *f) {
+            const int pc = PACKED ? j * 2 + kh : kh * KS + j;
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                const int r = wm * (BM / WM) + m * 32 + l32;
+                f[m] = As[st * kStage + r * PR + (pc ^ (r & 7))];
+            }
+        };
+        read_s(0, af[0]);
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+            if (j + 1 < KS) read_s(j + 1, af[(j + 1) & 1]);
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int n = 0; n < WTN; ++n)
+                    if constexpr (GATE_UP)
+                        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, bq[n][j]),
+                            __builtin_bit_cast(bf16x8, af[j & 1][m]), acc[m][n], 0, 0, 0);
+                    else
+                        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, af[j & 1][m]),
+                            __builtin_bit_cast(bf16x8, bq[n][j]), acc[m][n], 0, 0, 0);
+            if constexpr (PF) {
+#pragma unroll
+                for (int n = 0; n < WTN; ++n)
+                    bq[n][j] = *(const u32x4 *)(bp[n] + kt_next * kBKStep + j * kBStep);
+            }
+        }
+    };
+    // K-loop of such an item: only the rows that can hold data are loaded and stored
+    // (the prologue has filled the whole first stage).
+    auto k_loop_short = [&](auto mt_c, int par_) {
+        constexpr int MT = decltype(mt_c)::value;
+        constexpr int APS = (32 * MT + RPP - 1) / RPP < AP ? (32 * MT + RPP - 1) / RPP : AP;
+        for (int kt = 0; kt + 1 < nk; ++kt) {
+            const int st = (par_ + kt) & 1;
+#pragma unroll
+            for (int p = 0; p < APS; ++p)
+                ra[p] = *(const u32x4 *)(a_src + ao[p] + (kt + 1) * (16 * KS));
+            compute_short(st, mt_c, std::true_type{}, kt + 1);
+#pragma unroll
+            for (int p = 0; p < APS; ++p) {
+                const int r_ = lr + p * RPP;
+                As[(st ^ 1) * kStage + r_ * PR + (piece ^ (r_ & 7))] = ra[p];
+            }
+            __builtin_amdgcn_sched_group_barrier(0x020, APS, 0);           // VMEM read
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * MT, 0);        // DS read
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                __builtin_amdgcn_sched_group_barrier(0x008, MT * WTN, 0);  // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x020, WTN, 0);       // refill
+                if (j < KS - 2) __builtin_amdgcn_sched_group_barrier(0x100, MT, 0);
+                if (j >= KS - APS) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+            }
+            __syncthreads();
+        }
+        compute_short((par_ + nk - 1) & 1, mt_c, std::false_type{}, 0);
+    };
 // The order the scheduler is to build for one K-step (left alone it sinks every
 // load to just before its first use to save registers): per half k-step the
 // MFMAs, the refill of the weight registers they consumed and the LDS fragment
@@ -272,8 +340,13 @@ __device__ __forceinline__ void ffn_tile_run(
         int seq_next = seq + 1;
         const bool has_next = next_item(seq_next, nxt);
 
+        // ragged last tiles of an expert with at most 64 / 32 rows: a quarter or half of the MFMAs
+        const int valid_rows = cur.row_end - cur.row0;
+        const int short_mt = (CHAIN || WM != 1 || valid_rows > 64) ? 0 : (valid_rows > 32 ? 2 : 1);
+        if (short_mt == 1) k_loop_short(std::integral_constant<int, 1>{}, par);
+        else if (short_mt == 2) k_loop_short(std::integral_constant<int, 2>{}, par);
         // steady state without conditionals, so each wait counts only older loads
-        for (int kt = 0; kt + 1 < nk; ++kt) {
+        for (int kt = 0; short_mt == 0 && kt + 1 < nk; ++kt) {
             const int st = (par + kt) & 1;
             BEAM_GLOAD_A((kt + 1) * (16 * KS))
             compute(st, std::true_type{}, kt + 1);
@@ -306,7 +379,7 @@ __device__ __forceinline__ void ffn_tile_run(
 #pragma unroll
             for (int hs = 0; hs < 2 * KS; ++hs) { BEAM_SCHED_HALF_STEP(hs) }
             __builtin_amdgcn_sched_group_barrier(0x020, AP, 0);
-        } else {
+        } else if (short_mt == 0) {
             compute(lst, std::false_type{}, 0);
         }
 
