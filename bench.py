@@ -128,8 +128,9 @@ def measure_point(cfg, d, g, weight_sets, steps, warmup, torch, beam, hp, packed
     layer_flops = P * 6 * H * I + 4 * T * H * N
     gate_up_bytes = U * 2 * H * I * esz + T * H * esz
     gate_up_flops = P * 4 * H * I
-    # down: the touched experts' H x I weights, the hidden rows in, the fp32 pair rows out
-    down_bytes = U * H * I * esz + P * I * esz + P * H * 4
+    # down: the touched experts' H x I weights, the hidden rows in, the pair rows out
+    ybytes = beam.beam_fused_pair_row_bits(s, S) // 8      # fp32, or half precision for large batches
+    down_bytes = U * H * I * esz + P * I * esz + P * H * ybytes
     down_flops = P * 2 * H * I
     t_roof_us = max(layer_bytes / (HBM_PEAK_GBS * 1e3), layer_flops / (MFMA_BF16_PEAK_TFLOPS * 1e6))
     return {

@@ -185,8 +185,10 @@ beam_status beam_combine(const beam_shape *shape, const float *y_pairs, const fl
  * masked_ids_opt [T,K], num_pairs_opt [1] (device).
  * Same indices as the staged calls; the output may differ from theirs in the
  * last bits where the fused call orders its fp32 sums differently (few experts
- * with a long reduction: the down projection is summed in four parts), within
- * the same tolerance, and is the same on every run.
+ * with a long reduction: the down projection is summed in four parts) or keeps
+ * the pair rows of a very large batch in half precision between the down
+ * projection and the aggregation (beam_fused_pair_row_bits), within the same
+ * tolerance, and is the same on every run.
  */
 beam_status beam_moe_forward(const beam_shape *shape, const void *x, const void *w_router,
                              const float *router_bias, const void *w_mask, const float *mask_bias,
@@ -298,6 +300,18 @@ size_t beam_block_workspace_bytes(const beam_shape *shape, int32_t num_shared);
 beam_status beam_workspace_logits_region(const beam_shape *shape, int32_t num_shared,
                                          size_t *offset_host, size_t *bytes_host,
                                          int32_t *parts_host);
+/*
+ * Host-only query: the width in bits of the pair rows E_e(x_t) (Eq. 3, the terms of the sum
+ * in Eq. 8) that the FUSED entry points (beam_moe_forward and its variants,
+ * beam_moe_block_forward) keep in the workspace between the down projection and the
+ * aggregation for this shape.  32: fp32.  16: IEEE half precision (11 significant bits,
+ * saturating at +-65504), which the fused layer uses where the rows of a full batch exceed
+ * the GPU's 256 MiB last-level cache and their traffic bounds both kernels; the sum over a
+ * token's slots is fp32, in slot order, rounded once, in either case.  The staged
+ * beam_expert_ffn / beam_combine always exchange fp32 rows.  0: invalid or unsupported
+ * shape.  Nothing is enqueued.
+ */
+int32_t beam_fused_pair_row_bits(const beam_shape *shape, int32_t num_shared);
 beam_status beam_moe_block_forward(const beam_shape *shape, int32_t num_shared, const void *x,
                                    const void *w_router, const float *router_bias,
                                    const void *w_mask, const float *mask_bias,

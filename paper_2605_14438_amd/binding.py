@@ -32,7 +32,7 @@ EXPORTS = ("beam_abi_version", "beam_status_string", "beam_workspace_bytes", "be
            "beam_moe_block_forward", "beam_moe_block_forward_timed", "beam_route_rule",
            "beam_moe_forward_rule", "beam_mask_router_backward", "beam_probe_stream_read",
            "beam_probe_mfma", "beam_workspace_logits_region",
-           "beam_moe_forward_noalloc")
+           "beam_moe_forward_noalloc", "beam_fused_pair_row_bits")
 BEAM_NOALLOC_WORKSPACE_BYTES = 32 << 20
 BEAM_RULE_MASK = 0
 BEAM_RULE_CUMPROB = 1
@@ -106,6 +106,8 @@ def load() -> ctypes.CDLL:
         lib.beam_workspace_logits_region.argtypes = [sp, ctypes.c_int32, ctypes.POINTER(sz),
                                                      ctypes.POINTER(sz),
                                                      ctypes.POINTER(ctypes.c_int32)]
+        lib.beam_fused_pair_row_bits.restype = ctypes.c_int32
+        lib.beam_fused_pair_row_bits.argtypes = [sp, ctypes.c_int32]
         lib.beam_moe_block_forward.restype = ctypes.c_int
         lib.beam_moe_block_forward.argtypes = [sp, ctypes.c_int32] + [vp] * 15 + [sz, vp]
         lib.beam_moe_block_forward_timed.restype = ctypes.c_int
@@ -236,6 +238,12 @@ def beam_workspace_logits_region(shape, num_shared: int, check: bool = True):
     st = load().beam_workspace_logits_region(ctypes.byref(s), int(num_shared), ctypes.byref(off),
                                              ctypes.byref(nb), ctypes.byref(parts))
     return _check("beam_workspace_logits_region", st, check), off.value, nb.value, parts.value
+
+
+def beam_fused_pair_row_bits(shape, num_shared: int = 0) -> int:
+    """32 or 16: width of the pair rows inside the fused entry points; 0 = unsupported shape."""
+    s = _shape(shape)
+    return int(load().beam_fused_pair_row_bits(ctypes.byref(s), int(num_shared)))
 
 
 def beam_moe_block_forward(shape, num_shared, x, w_router, router_bias, w_mask, mask_bias,

@@ -28,7 +28,7 @@ hipError_t launch_gate_up_tiled(const beam_shape &s, const void *x, const void *
                                 void *hidden, hipStream_t st, int want);
 hipError_t launch_down_tiled(const beam_shape &s, const void *hidden, const void *w_down,
                              const int32_t *offsets, const WorkList &wl, float *y_pairs,
-                             hipStream_t st, int k_split, int want);
+                             hipStream_t st, int k_split, int want, bool y16 = false);
 hipError_t launch_pack_weights(const beam_shape &s, const void *w_gate_up, const void *w_down,
                                void *w_gate_up_packed, void *w_down_packed, hipStream_t st);
 
@@ -155,6 +155,21 @@ Regime ffn_regime(const beam_shape &s) {
 
 static bool use_tiled(const beam_shape &s) { return ffn_regime(s) == Regime::Tiled; }
 
+// Precision of the pair rows y = E_e(x_t) between the down GEMM and the aggregation INSIDE
+// the fused entry points.  The staged beam_expert_ffn / beam_combine always exchange fp32.
+// Where the rows of a full batch exceed the 256 MiB last-level cache (so that the down GEMM
+// writes them to HBM and the aggregation reads them back from there, which is what bounds
+// both kernels at a high keep rate: 2 x 1.07 GB for the Qwen3-shaped layer at 16384 tokens)
+// the fused layer keeps them in IEEE half precision: 11 significant bits, a rounding eight
+// times finer than that of the bf16 output and of the bf16 hidden activation h before it,
+// saturating at +-65504.  The sum over a token's slots is still fp32, in slot order, rounded
+// once.  Decided from the shape alone (the aggregation must know the format when it is
+// enqueued): the tiled GEMM on the host's word, whole reduction, bf16 layer.
+static bool pair_rows_16bit(const beam_shape &s) {
+    return s.dtype == BEAM_BF16 && use_tiled(s) && down_split_k_if_tiled(s) == 1 &&
+           s.H % 256 == 0 && (size_t)s.T * s.K * s.H * sizeof(float) > kStreamBytes;
+}
+
 hipError_t launch_gate_up(const beam_shape &s, const void *x, const void *w_gate_up,
                           const int32_t *offsets, const int32_t *perm, const int32_t *num_pairs,
                           const WorkList &wl, void *hidden, hipStream_t st) {
@@ -177,11 +192,12 @@ hipError_t launch_gate_up(const beam_shape &s, const void *x, const void *w_gate
 
 hipError_t launch_down(const beam_shape &s, const void *hidden, const void *w_down,
                        const int32_t *offsets, const int32_t *num_pairs, const WorkList &wl,
-                       float *y_pairs, hipStream_t st, int k_split) {
+                       float *y_pairs, hipStream_t st, int k_split, bool y16) {
+    if (y16 && ffn_regime(s) != Regime::Tiled) return hipErrorInvalidValue;
     switch (ffn_regime(s)) {
         case Regime::Tiled:
             return launch_down_tiled(s, hidden, w_down, offsets, wl, y_pairs, st, k_split,
-                                     kRegimeAny);
+                                     kRegimeAny, y16);
         case Regime::Stream:
             return launch_down_stream(s, hidden, w_down, offsets, wl, y_pairs, st, kRegimeAny);
         case Regime::Auto: {
@@ -517,10 +533,12 @@ static beam_status moe_forward_impl(const beam_shape *shape, int S, const beam_r
     BEAM_TRY_HIP(launch_gate_up(se, x, w_gate_up, offsets, perm, np, wl, ws + L.hidden, stream));
     BEAM_STAGE_MARK(4);
     const int k_split = down_split_k(se);
+    const bool y16 = pair_rows_16bit(se);
     BEAM_TRY_HIP(launch_down(se, ws + L.hidden, w_down, offsets, np, wl, y_pairs, stream,
-                             k_split));
+                             k_split, y16));
     BEAM_STAGE_MARK(5);
-    BEAM_TRY_HIP(launch_combine(se, y_pairs, gw, mids, inv, residual, out, stream, np, k_split));
+    BEAM_TRY_HIP(launch_combine(se, y_pairs, gw, mids, inv, residual, out, stream, np, k_split,
+                                y16));
     BEAM_STAGE_MARK(6);
 #undef BEAM_STAGE_MARK
     return BEAM_OK;
@@ -620,6 +638,14 @@ beam_status beam_workspace_logits_region(const beam_shape *shape, int32_t num_sh
     *bytes_host = L.router_logits_bytes;
     *parts_host = L.logit_parts;
     return BEAM_OK;
+}
+
+int32_t beam_fused_pair_row_bits(const beam_shape *shape, int32_t num_shared) {
+    if (beam_block_workspace_bytes(shape, num_shared) == 0) return 0;
+    beam_shape se = *shape;
+    se.N += num_shared;
+    se.K += num_shared;
+    return pair_rows_16bit(se) ? 16 : 32;
 }
 
 beam_status beam_moe_block_forward(const beam_shape *shape, int32_t num_shared, const void *x,

@@ -191,13 +191,14 @@ hipError_t launch_gate_up(const beam_shape &s, const void *x, const void *w_gate
                           const int32_t *offsets, const int32_t *perm, const int32_t *num_pairs,
                           const WorkList &wl, void *hidden, hipStream_t st);
 // k_split > 1 (tiled path only): y_pairs is k_split arrays [T*K,H] of partial sums
+// y16 (tiled path with k_split == 1 only): y_pairs is an array of half-precision rows
 hipError_t launch_down(const beam_shape &s, const void *hidden, const void *w_down,
                        const int32_t *offsets, const int32_t *num_pairs, const WorkList &wl,
-                       float *y_pairs, hipStream_t st, int k_split = 1);
+                       float *y_pairs, hipStream_t st, int k_split = 1, bool y16 = false);
 // num_pairs (device, may be NULL): lets the kernel see how large y_pairs is
 hipError_t launch_combine(const beam_shape &s, const float *y_pairs, const float *topk_w,
                           const int32_t *masked_ids, const int32_t *inv_perm,
                           const void *residual, void *out, hipStream_t st,
-                          const int32_t *num_pairs = nullptr, int k_split = 1);
+                          const int32_t *num_pairs = nullptr, int k_split = 1, bool y16 = false);
 
 }  // namespace beam

@@ -104,6 +104,9 @@ struct TileItem {
 // COL_GUARD (down roles only): the output is narrower than the last column tile;
 // columns >= H are computed from zero padding and not stored.
 // stream_out (down roles only, uniform): the output goes past the caches.
+// y16 (down roles only, uniform, k_split == 1): the output rows are stored as IEEE half
+// precision (11 significant bits, saturating at +-65504) instead of fp32; y_out then points
+// to an array of that type.
 // k_split (down roles only): the reduction is cut into k_split equal parts; an
 // item multiplies part `slice` and writes its partial sums to y_out + slice *
 // slice_stride (elements).  With few, long items (a handful of experts with a
@@ -114,7 +117,8 @@ template <int BM, int WM, int KS, bool GATE_UP, bool PACKED, bool CHAIN, bool CO
 __device__ __forceinline__ void ffn_tile_run(
     u32x4 *As, const bf16_t *__restrict__ a_src, const bf16_t *__restrict__ w,
     const int32_t *__restrict__ perm, bf16_t *__restrict__ hidden_out, float *__restrict__ y_out,
-    int H, int K, int I, bool stream_out, int k_split, size_t slice_stride, NextItem next_item) {
+    int H, int K, int I, bool stream_out, bool y16, int k_split, size_t slice_stride,
+    NextItem next_item) {
     constexpr int PR = 2 * KS;           // 16-byte pieces per LDS row (K-step of 16*KS indices)
     constexpr int NT = 64 * NW;          // threads; NW wavefronts, each 64 columns wide with WM == 1
     constexpr int TN = kTileN * NW / 4;  // columns of the output tile
@@ -417,7 +421,8 @@ __device__ __forceinline__ void ffn_tile_run(
             // Activations were the A operand: register r of lane l is row
             // 8*(r >> 2) + 4*(l >> 5) + (r & 3), column l & 31 of the tile, so each
             // store instruction writes two full 128-byte row segments of fp32.
-            auto store_tile = [&](auto stream) {
+            auto store_tile = [&](auto stream, auto half) {
+                using Y = std::conditional_t<decltype(half)::value, _Float16, float>;
 #pragma unroll
                 for (int m = 0; m < WTM; ++m) {
 #pragma unroll
@@ -425,21 +430,27 @@ __device__ __forceinline__ void ffn_tile_run(
                         const int trow = wm * (BM / WM) + m * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
                         const int grow = done.row0 + trow;
                         if (grow >= done.row_end) continue;
-                        float *orow = y_out + done.slice * slice_stride + (size_t)grow * H + n0 + l32;
+                        Y *orow = (Y *)y_out + done.slice * slice_stride + (size_t)grow * H + n0 + l32;
 #pragma unroll
                         for (int n = 0; n < WTN; ++n) {
                             if (COL_GUARD && n0 + l32 + (wn * WTN + n) * 32 >= H) continue;
-                            if constexpr (decltype(stream)::value)
-                                __builtin_nontemporal_store(acc[m][n][r],
-                                                            &orow[(wn * WTN + n) * 32]);
+                            Y v;
+                            if constexpr (decltype(half)::value)
+                                v = (Y)fminf(fmaxf(acc[m][n][r], -65504.0f), 65504.0f);
                             else
-                                orow[(wn * WTN + n) * 32] = acc[m][n][r];
+                                v = acc[m][n][r];
+                            if constexpr (decltype(stream)::value)
+                                __builtin_nontemporal_store(v, &orow[(wn * WTN + n) * 32]);
+                            else
+                                orow[(wn * WTN + n) * 32] = v;
                         }
                     }
                 }
             };
-            if (stream_out) store_tile(std::true_type{});
-            else store_tile(std::false_type{});
+            if (y16 && stream_out) store_tile(std::true_type{}, std::true_type{});
+            else if (y16) store_tile(std::false_type{}, std::true_type{});
+            else if (stream_out) store_tile(std::true_type{}, std::false_type{});
+            else store_tile(std::false_type{}, std::false_type{});
         }
         if (!has_next) break;
         cur = nxt;
@@ -474,7 +485,7 @@ __global__ __launch_bounds__(64 * NW, OCC) void ffn_tile_kernel(
     const int32_t *__restrict__ wl_hdr, const int32_t *__restrict__ tile_expert,
     const int32_t *__restrict__ tile_row0, bf16_t *__restrict__ hidden_out,
     float *__restrict__ y_out, int H, int K, int I, int n_col_tiles, int k_split,
-    size_t slice_stride, int want) {
+    size_t slice_stride, int want, int y16) {
     __shared__ u32x4 As[2 * kTileM * 2 * KS];
     // Item order: the row tiles of an expert in groups of up to kRowGroup (a group
     // never spans two experts); inside a group the column tile is the slow index
@@ -514,9 +525,11 @@ __global__ __launch_bounds__(64 * NW, OCC) void ffn_tile_kernel(
         return true;
     };
     // more rows of y_pairs than the last-level cache can hold until they are read again
-    const bool stream_out = !GATE_UP && (size_t)n_tiles * kTileM * H * sizeof(float) > kStreamBytes;
+    const bool stream_out =
+        !GATE_UP && (size_t)n_tiles * kTileM * H * (y16 ? 2 : sizeof(float)) > kStreamBytes;
     ffn_tile_run<kTileM, WM, KS, GATE_UP, PACKED, OCC == 1 && NW == 4, false, NW>(
-        As, a_src, w, perm, hidden_out, y_out, H, K, I, stream_out, k_split, slice_stride,
+        As, a_src, w, perm, hidden_out, y_out, H, K, I, stream_out, !GATE_UP && y16 != 0, k_split,
+        slice_stride,
         next_item);
 }
 
@@ -529,12 +542,13 @@ bool tiled_ffn_supported(const beam_shape &s) {
 template <bool GATE_UP>
 static void launch_tile(const beam_shape &s, const bf16_t *a, const bf16_t *w,
                         const int32_t *offsets, const int32_t *perm, const WorkList &wl,
-                        bf16_t *hidden, float *y, int nct, int k_split, hipStream_t st, int want) {
+                        bf16_t *hidden, float *y, int nct, int k_split, hipStream_t st, int want,
+                        int y16 = 0) {
     const bool packed = s.weight_layout == BEAM_WEIGHTS_PACKED;
 #define BEAM_LAUNCH_TILE(KS_, OCC_, PK)                                                        \
     ffn_tile_kernel<kWavesM, KS_, OCC_, GATE_UP, PK, 4><<<256 * OCC_, 256, 0, st>>>(           \
         a, w, offsets, perm, wl.hdr, wl.tile_expert, wl.tile_row0, hidden, y, s.H, s.K, s.I, nct, \
-        k_split, (size_t)s.T * s.K * s.H, want)
+        k_split, (size_t)s.T * s.K * s.H, want, y16)
     // Three schedules of the same tile body.  "Dense": 64-wide K-steps, two
     // workgroups per CU, whose MFMAs cover each other's prologue, epilogue and
     // barriers; the faster one when the reduction is short and the work MFMA
@@ -560,7 +574,7 @@ static void launch_tile(const beam_shape &s, const bf16_t *a, const bf16_t *w,
     if (packed && k_split == 1 && (GATE_UP ? (2 * s.I) % 512 == 0 : s.H % 512 == 0)) {
         ffn_tile_kernel<kWavesM, kKSteps, 1, GATE_UP, true, 8><<<256, 512, 0, st>>>(
             a, w, offsets, perm, wl.hdr, wl.tile_expert, wl.tile_row0, hidden, y, s.H, s.K, s.I,
-            nct / 2, k_split, (size_t)s.T * s.K * s.H, want);
+            nct / 2, k_split, (size_t)s.T * s.K * s.H, want, y16);
         return;
     }
     if (packed) BEAM_LAUNCH_TILE(kKSteps, kWorkgroupsPerCU, true);
@@ -578,11 +592,13 @@ hipError_t launch_gate_up_tiled(const beam_shape &s, const void *x, const void *
 
 // k_split > 1: y_pairs holds k_split arrays [T*K,H] of partial sums, one per part of
 // the reduction; I / (16 * kKSteps) must be a multiple of k_split.
+// y16 (with k_split == 1 only): y_pairs is an array of half-precision rows.
 hipError_t launch_down_tiled(const beam_shape &s, const void *hidden, const void *w_down,
                              const int32_t *offsets, const WorkList &wl, float *y_pairs,
-                             hipStream_t st, int k_split, int want) {
+                             hipStream_t st, int k_split, int want, bool y16) {
+    if (y16 && k_split != 1) return hipErrorInvalidValue;
     launch_tile<false>(s, (const bf16_t *)hidden, (const bf16_t *)w_down, offsets, nullptr, wl,
-                       nullptr, y_pairs, s.H / kTileN, k_split, st, want);
+                       nullptr, y_pairs, s.H / kTileN, k_split, st, want, y16 ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -645,7 +661,7 @@ __global__ __launch_bounds__(256, 2) void logits_tile_kernel(
     };
     // down-GEMM roles: output width N2, reduction length H, a single expert
     ffn_tile_run<kLogitsM, kWavesM, kLogitsKS, false, true, true, true, 4>(
-        As, x, packed_heads, nullptr, nullptr, logits2, N2, 1, H, false, k_split,
+        As, x, packed_heads, nullptr, nullptr, logits2, N2, 1, H, false, false, k_split,
         (size_t)Tn * N2, next_item);
 }
 

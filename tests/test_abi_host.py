@@ -118,6 +118,28 @@ def test_logits_region_holds_the_parts_of_the_routed_shape(lib):
     assert beam.beam_workspace_logits_region(bad, 0, check=False)[0] == binding.BEAM_ERR_INVALID_ARG
 
 
+def test_fused_pair_row_bits_follow_the_documented_rule(lib):
+    """Half-precision pair rows inside the fused layer exactly where the header says: bf16, the
+    tiled GEMM on the host's word (more than 256 rows per expert in the worst case), a whole
+    down reduction, and T*K*H fp32 rows beyond the 256 MiB last-level cache."""
+    mk = beam.make_shape
+    q = dict(H=2048, N=128, K=8, I=768)
+    def bits(T, S=0, dtype=beam.BEAM_BF16, layout=beam.BEAM_WEIGHTS_PACKED, **kw):
+        d = {**q, **kw}
+        return beam.beam_fused_pair_row_bits(mk(T, d["H"], d["N"], d["K"], d["I"], dtype, layout), S)
+    assert bits(16384) == 16 and bits(4097) == 16           # 4097 * 8 * 2048 * 4 B > 256 MiB
+    assert bits(4096) == 32                                 # exactly 256 MiB, and 256 rows per expert
+    assert bits(64) == 32 and bits(1) == 32
+    assert bits(16384, layout=beam.BEAM_WEIGHTS_PLAIN) == 16
+    assert bits(16384, dtype=beam.BEAM_F32, layout=beam.BEAM_WEIGHTS_PLAIN) == 32
+    assert bits(4000, S=1) == 16                            # 9 slots per token with a shared block
+    assert bits(8192, H=4096, I=1536) == 16 and bits(2048, H=4096, I=1536) == 32
+    # few experts with a long reduction: the fused layer splits the down reduction, fp32 parts
+    assert bits(2048, H=4096, N=8, K=2, I=14336) == 32
+    assert bits(16384, H=320, N=60, K=4, I=136, layout=beam.BEAM_WEIGHTS_PLAIN) == 32   # generic kernels
+    assert bits(4, K=9, N=8) == 0 and bits(16384, S=200) == 0                           # invalid shapes
+
+
 def test_residual_must_not_overlap_the_output(lib):
     s = beam.make_shape(4, 256, 8, 2, 512, beam.BEAM_F32)
     ok, big = 0x100000, 1 << 40
