@@ -305,8 +305,8 @@ beam_status beam_workspace_logits_region(const beam_shape *shape, int32_t num_sh
  * in Eq. 8) that the FUSED entry points (beam_moe_forward and its variants,
  * beam_moe_block_forward) keep in the workspace between the down projection and the
  * aggregation for this shape.  32: fp32.  16: IEEE half precision (11 significant bits,
- * saturating at +-65504), which the fused layer uses where the rows of a full batch exceed
- * the GPU's 256 MiB last-level cache and their traffic bounds both kernels; the sum over a
+ * saturating at +-65504), which the fused layer uses where the rows of a full batch fill the
+ * GPU's 256 MiB last-level cache or more and their traffic bounds both kernels; the sum over a
  * token's slots is fp32, in slot order, rounded once, in either case.  The staged
  * beam_expert_ffn / beam_combine always exchange fp32 rows.  0: invalid or unsupported
  * shape.  Nothing is enqueued.

@@ -124,7 +124,7 @@ WorkList work_list(void *base, const beam_shape &s, int max_tiles) {
 }
 
 // What the shape alone says about the expert GEMMs.  Decode-sized batches (a handful of
-// rows per expert whatever the keep rate) stream; beyond 256 rows per expert in the worst
+// rows per expert whatever the keep rate) stream; from 256 rows per expert in the worst
 // case the tiled GEMM it is; in between the right family depends on the keep rate and the
 // routing skew, which only the device knows after grouping (work list hdr[2]): both
 // families are enqueued and the one not chosen leaves at once (measured: a batch of 512
@@ -148,7 +148,7 @@ Regime ffn_regime(const beam_shape &s) {
                                                                           : Regime::Generic;
     if (!tiled_ok) return Regime::Stream;
     if (TK <= kChunk || TK <= 8L * s.N) return Regime::Stream;   // a few rows per expert at most
-    if (TK > 256L * s.N) return Regime::Tiled;
+    if (TK >= 256L * s.N) return Regime::Tiled;
     if (down_split_k_if_tiled(s) > 1) return TK > 32L * s.N ? Regime::Tiled : Regime::Stream;
     return Regime::Auto;
 }
@@ -157,7 +157,7 @@ static bool use_tiled(const beam_shape &s) { return ffn_regime(s) == Regime::Til
 
 // Precision of the pair rows y = E_e(x_t) between the down GEMM and the aggregation INSIDE
 // the fused entry points.  The staged beam_expert_ffn / beam_combine always exchange fp32.
-// Where the rows of a full batch exceed the 256 MiB last-level cache (so that the down GEMM
+// Where the rows of a full batch fill the 256 MiB last-level cache or more (so that the down GEMM
 // writes them to HBM and the aggregation reads them back from there, which is what bounds
 // both kernels at a high keep rate: 2 x 1.07 GB for the Qwen3-shaped layer at 16384 tokens)
 // the fused layer keeps them in IEEE half precision: 11 significant bits, a rounding eight
@@ -167,7 +167,7 @@ static bool use_tiled(const beam_shape &s) { return ffn_regime(s) == Regime::Til
 // enqueued): the tiled GEMM on the host's word, whole reduction, bf16 layer.
 static bool pair_rows_16bit(const beam_shape &s) {
     return s.dtype == BEAM_BF16 && use_tiled(s) && down_split_k_if_tiled(s) == 1 &&
-           s.H % 256 == 0 && (size_t)s.T * s.K * s.H * sizeof(float) > kStreamBytes;
+           s.H % 256 == 0 && (size_t)s.T * s.K * s.H * sizeof(float) >= kStreamBytes;
 }
 
 hipError_t launch_gate_up(const beam_shape &s, const void *x, const void *w_gate_up,

@@ -120,15 +120,15 @@ def test_logits_region_holds_the_parts_of_the_routed_shape(lib):
 
 def test_fused_pair_row_bits_follow_the_documented_rule(lib):
     """Half-precision pair rows inside the fused layer exactly where the header says: bf16, the
-    tiled GEMM on the host's word (more than 256 rows per expert in the worst case), a whole
-    down reduction, and T*K*H fp32 rows beyond the 256 MiB last-level cache."""
+    tiled GEMM on the host's word (256 rows per expert or more in the worst case), a whole
+    down reduction, and T*K*H fp32 rows that fill the 256 MiB last-level cache or more."""
     mk = beam.make_shape
     q = dict(H=2048, N=128, K=8, I=768)
     def bits(T, S=0, dtype=beam.BEAM_BF16, layout=beam.BEAM_WEIGHTS_PACKED, **kw):
         d = {**q, **kw}
         return beam.beam_fused_pair_row_bits(mk(T, d["H"], d["N"], d["K"], d["I"], dtype, layout), S)
-    assert bits(16384) == 16 and bits(4097) == 16           # 4097 * 8 * 2048 * 4 B > 256 MiB
-    assert bits(4096) == 32                                 # exactly 256 MiB, and 256 rows per expert
+    assert bits(16384) == 16 and bits(4096) == 16           # 4096 * 8 * 2048 * 4 B = 256 MiB
+    assert bits(4095) == 32
     assert bits(64) == 32 and bits(1) == 32
     assert bits(16384, layout=beam.BEAM_WEIGHTS_PLAIN) == 16
     assert bits(16384, dtype=beam.BEAM_F32, layout=beam.BEAM_WEIGHTS_PLAIN) == 32
