@@ -70,8 +70,6 @@ WsLayout ws_layout(const beam_shape &s, int S) {
     const size_t T = (size_t)s.T, N = (size_t)s.N, K = (size_t)s.K;
     const size_t TK = T * K;
     const size_t esz = s.dtype == BEAM_BF16 ? 2 : 4;
-    L.nchunk = (int)((TK + kChunk - 1) / kChunk);
-    if (L.nchunk < 1) L.nchunk = 1;
     L.max_tiles = (int)(TK / kTileM + N);  // sum over experts of ceil(c_e / kTileM)
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -96,8 +94,7 @@ WsLayout ws_layout(const beam_shape &s, int S) {
     L.topk_w = take(TK * 4);
     L.masked_ids = take(TK * 4);
     L.g_shared = take(T * 4);
-    L.blk_counts = take((size_t)L.nchunk * N * 4);
-    L.blk_base = take((size_t)L.nchunk * N * 4);
+    L.slice_counts = take((size_t)permute_slices((long)TK) * N * 4);
     L.counts = take(N * 4);
     L.offsets = take((N + 1) * 4);
     L.num_pairs = take(4);
@@ -372,8 +369,7 @@ beam_status beam_permute(const beam_shape *shape, const int32_t *masked_ids, int
     const WorkList wl = work_list(ws + L.work, s, L.max_tiles);
     // T == 0 still defines the outputs: no pairs
     BEAM_TRY_HIP(launch_permute(s, masked_ids, expert_counts, expert_offsets, perm, inv_perm,
-                                num_pairs, (int32_t *)(ws + L.blk_counts),
-                                (int32_t *)(ws + L.blk_base), L.nchunk, wl,
+                                num_pairs, (int32_t *)(ws + L.slice_counts), wl,
                                 (hipStream_t)hip_stream, !use_tiled(s)));
     return BEAM_OK;
 }
@@ -526,8 +522,7 @@ static beam_status moe_forward_impl(const beam_shape *shape, int S, const beam_r
     BEAM_STAGE_MARK(2);
     if (!grouped)
         BEAM_TRY_HIP(launch_permute(se, mids, counts, offsets, perm, inv, np,
-                                    (int32_t *)(ws + L.blk_counts),
-                                    (int32_t *)(ws + L.blk_base), L.nchunk, wl, stream,
+                                    (int32_t *)(ws + L.slice_counts), wl, stream,
                                     !use_tiled(se)));
     BEAM_STAGE_MARK(3);
     BEAM_TRY_HIP(launch_gate_up(se, x, w_gate_up, offsets, perm, np, wl, ws + L.hidden, stream));

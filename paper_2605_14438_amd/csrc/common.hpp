@@ -12,8 +12,8 @@ namespace beam {
 
 constexpr int kWave = 64;
 
-// Pairs handled by one workgroup of the grouping kernels (one wavefront walks
-// kGroupsPerChunk groups of 64 flat pair indices in order).
+// Pairs handled by the one workgroup of the decode grouping kernel (one wavefront
+// walks kGroupsPerChunk groups of 64 flat pair indices in order).
 constexpr int kGroupsPerChunk = 8;
 constexpr int kChunk = kWave * kGroupsPerChunk;
 
@@ -73,8 +73,7 @@ struct WsLayout {
     size_t topk_w;         // [T,K] f32
     size_t masked_ids;     // [T,K] i32
     size_t g_shared;       // [T] f32 : weight of the shared-expert slots (block entry point)
-    size_t blk_counts;     // [nchunk,N] i32 : kept pairs per (chunk, expert)
-    size_t blk_base;       // [nchunk,N] i32 : exclusive prefix over chunks
+    size_t slice_counts;   // [slices,N] i32 : kept pairs per (slice of the pair list, expert)
     size_t counts;         // [N] i32
     size_t offsets;        // [N+1] i32
     size_t num_pairs;      // [1] i32
@@ -87,7 +86,6 @@ struct WsLayout {
     size_t total;
     size_t router_logits_bytes;  // size of the logits region (router + mask, every part)
     int logit_parts;             // [T,2N] arrays the region has room for
-    int nchunk;
     int max_tiles;
 };
 WsLayout ws_layout(const beam_shape &s, int S = 0);
@@ -170,8 +168,9 @@ hipError_t launch_logits_tiled(const beam_shape &s, const void *x, const void *w
                                hipStream_t st);
 hipError_t launch_permute(const beam_shape &s, const int32_t *masked_ids, int32_t *counts,
                           int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *num_pairs,
-                          int32_t *blk_counts, int32_t *blk_base, int nchunk, const WorkList &wl,
-                          hipStream_t st, bool longest_first = false);
+                          int32_t *slice_counts, const WorkList &wl, hipStream_t st,
+                          bool longest_first = false);
+int permute_slices(long TK);   // rows of slice_counts the grouping of TK pairs needs
 bool route_permute_supported(const beam_shape &s, const RouteOpts &opt, const float *router_logits,
                              const float *mask_logits);
 hipError_t launch_route_permute(const beam_shape &s, const float *router_logits,

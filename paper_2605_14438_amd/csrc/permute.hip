@@ -1,27 +1,34 @@
 // Expert-wise grouping of the kept (token, expert) pairs (paper App. A.4: ids
 // equal to -1 are skipped when tokens are grouped by expert).  A stable
-// counting sort of the flat pair index f = t*K+k by expert id:
-//   1. count    per chunk of kChunk pairs, an LDS histogram over experts
-//   2. scan     per expert, exclusive prefix over chunks (one workgroup per
-//               expert); then exclusive prefix over experts plus the work list
-//               the FFN kernels walk (one workgroup)
-//   3. scatter  every chunk re-reads its ids and places each kept pair at
-//               offset[e] + base[chunk][e] + (rank among equal ids so far)
-// Placement uses only prefix sums and wavefront ballots, never atomics on the
-// destination, so the result is the same on every run.  When the whole input
-// is one chunk (decode batches) the three steps run as one launch.
+// counting sort of the flat pair index f = t*K+k by expert id.  The pair list is
+// cut into slices of 2048 to 8192 pairs, one workgroup of 16 wavefronts each,
+// every wavefront a contiguous run of pairs:
+//   1. count    per slice, the kept pairs per expert (per-wavefront LDS rows,
+//               summed over the wavefronts)
+//   2. scatter  every slice counts its wavefronts' pairs again, adds up the
+//               slices' counts per expert (all of them for the expert's start,
+//               the earlier ones for its own start inside the expert) and
+//               places each kept pair at start + (rank among equal ids so far);
+//               one more workgroup writes the per-expert arrays and the work
+//               list the FFN kernels walk
+// Placement uses only prefix sums and wavefront ballots, never atomics, so the
+// result is the same on every run.  Up to one slice the two steps are one launch
+// of one workgroup; decode batches (up to 512 pairs) have a shorter kernel still.
 
 #include "common.hpp"
 #include "topk.hpp"
 
 namespace beam {
 
-// Lanes of the wavefront that hold the same id (ids < 256), restricted to
-// valid lanes: eight ballots, one per id bit.
-__device__ __forceinline__ uint64_t match_id(int id, bool valid) {
+// Lanes of the wavefront that hold the same id (ids < 2^nbits <= 256), restricted
+// to valid lanes: one ballot per id bit.
+__device__ __forceinline__ int id_bits(int N) { return N > 1 ? 32 - __builtin_clz(N - 1) : 0; }
+
+__device__ __forceinline__ uint64_t match_id(int id, bool valid, int nbits) {
     uint64_t peers = __ballot(valid);
 #pragma unroll
     for (int b = 0; b < 8; ++b) {
+        if (b >= nbits) break;   // uniform
         const bool bit = (id >> b) & 1;
         const uint64_t m = __ballot(valid && bit);
         peers &= bit ? m : ~m;
@@ -57,29 +64,6 @@ __device__ __forceinline__ int block_exclusive_scan_256(int v, int *scratch /*[>
     *total = sum;
     __syncthreads();   // scratch may be written again
     return tid < 256 ? run : 0;
-}
-
-// One wavefront counts the kept pairs of one chunk per expert.
-__global__ __launch_bounds__(64) void count_kernel(const int32_t *__restrict__ masked_ids,
-                                                   int32_t *__restrict__ blk_counts, int TK,
-                                                   int N) {
-    __shared__ int hist[256];
-    const int lane = threadIdx.x;
-    for (int e = lane; e < 256; e += 64) hist[e] = 0;
-    __syncthreads();
-    const int f0 = blockIdx.x * kChunk;
-#pragma unroll
-    for (int gidx = 0; gidx < kGroupsPerChunk; ++gidx) {
-        const int f = f0 + gidx * 64 + lane;
-        const int id = f < TK ? masked_ids[f] : -1;
-        const bool valid = id >= 0 && id < N;
-        const uint64_t peers = match_id(id, valid);
-        // the lowest lane of every group of equal ids adds the group size
-        if (valid && (peers & ((1ull << lane) - 1ull)) == 0) hist[id] += __popcll(peers);
-        __syncthreads();
-    }
-    // expert-major [N][nchunk], so the scan reads each expert's chunk counts contiguously
-    for (int e = lane; e < N; e += 64) blk_counts[(size_t)e * gridDim.x + blockIdx.x] = hist[e];
 }
 
 // Work list from the per-expert counts (thread e < 256 owns expert e; threads past
@@ -148,62 +132,6 @@ __device__ __forceinline__ void emit_work_list(int e, int N, int count, int offs
     if (threadIdx.x == 0) wl.hdr[1] = total;
 }
 
-// Exclusive prefix over the chunks of one expert (expert-major histograms): one
-// workgroup per expert, each thread a run of consecutive chunks, wavefront
-// shuffles plus four wave totals.  Writes the expert's total to counts[e].
-__global__ __launch_bounds__(256) void chunk_prefix_kernel(const int32_t *__restrict__ blk_counts,
-                                                           int32_t *__restrict__ blk_base,
-                                                           int32_t *__restrict__ counts,
-                                                           int nchunk) {
-    __shared__ int wtot[4];
-    const int e = blockIdx.x;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int per = (nchunk + 255) >> 8;  // chunks per thread
-    const int32_t *src = blk_counts + (size_t)e * nchunk;
-    int32_t *dst = blk_base + (size_t)e * nchunk;
-    const int b0 = tid * per;
-    int mine = 0;
-    for (int i = 0; i < per; ++i) mine += (b0 + i < nchunk) ? src[b0 + i] : 0;
-    int incl = mine;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int t = __shfl_up(incl, off);
-        if (lane >= off) incl += t;
-    }
-    if (lane == 63) wtot[wave] = incl;
-    __syncthreads();
-    int run = incl - mine;
-    for (int w = 0; w < wave; ++w) run += wtot[w];
-    for (int i = 0; i < per; ++i) {
-        if (b0 + i < nchunk) {
-            const int c = src[b0 + i];
-            dst[b0 + i] = run;
-            run += c;
-        }
-    }
-    if (tid == 255) counts[e] = run;
-}
-
-// Prefix over the experts and the work list, from the per-expert totals.
-__global__ __launch_bounds__(256) void scan_kernel(int32_t *__restrict__ counts,
-                                                   int32_t *__restrict__ offsets,
-                                                   int32_t *__restrict__ num_pairs, int N,
-                                                   WorkList wl, int longest_first) {
-    __shared__ int scratch[256];
-    const int e = threadIdx.x;
-    const int run = e < N ? counts[e] : 0;
-    int total;
-    const int excl = block_exclusive_scan_256(run, scratch, &total);
-    if (e < N) offsets[e] = excl;
-    if (e == 0) {
-        offsets[N] = total;
-        *num_pairs = total;
-    }
-    emit_work_list(e, N, run, excl, wl, scratch, longest_first != 0);
-}
-
 // Work list alone, for callers that hand in expert_offsets directly.
 __global__ __launch_bounds__(256) void work_list_kernel(const int32_t *__restrict__ offsets, int N,
                                                         WorkList wl, int longest_first) {
@@ -216,41 +144,6 @@ __global__ __launch_bounds__(256) void work_list_kernel(const int32_t *__restric
         if (cnt < 0) cnt = 0;
     }
     emit_work_list(e, N, cnt, off, wl, scratch, longest_first != 0);
-}
-
-__global__ __launch_bounds__(64) void scatter_kernel(const int32_t *__restrict__ masked_ids,
-                                                     const int32_t *__restrict__ offsets,
-                                                     const int32_t *__restrict__ blk_base,
-                                                     int32_t *__restrict__ perm,
-                                                     int32_t *__restrict__ inv_perm, int TK, int N) {
-    __shared__ int run[256];
-    const int lane = threadIdx.x;
-    for (int e = lane; e < N; e += 64)
-        run[e] = offsets[e] + blk_base[(size_t)e * gridDim.x + blockIdx.x];
-    __syncthreads();
-    const int P = offsets[N];
-    const int f0 = blockIdx.x * kChunk;
-#pragma unroll
-    for (int gidx = 0; gidx < kGroupsPerChunk; ++gidx) {
-        const int f = f0 + gidx * 64 + lane;
-        const int id = f < TK ? masked_ids[f] : -1;
-        const bool valid = id >= 0 && id < N;
-        const uint64_t peers = match_id(id, valid);
-        const int rank = __popcll(peers & ((1ull << lane) - 1ull));
-        const int base = valid ? run[id] : 0;
-        __syncthreads();
-        if (valid && rank == 0) run[id] = base + __popcll(peers);
-        __syncthreads();
-        if (f < TK) {
-            if (valid) {
-                perm[base + rank] = f;
-                inv_perm[f] = base + rank;
-            } else {
-                inv_perm[f] = -1;
-            }
-            if (f >= P) perm[f] = -1;  // rows [P, T*K) carry no pair
-        }
-    }
 }
 
 // Decode batches: the whole pair list is one chunk (T*K <= kChunk).  The first
@@ -289,7 +182,7 @@ __device__ __forceinline__ void permute_chunk_body(const int32_t *ids, ChunkShar
             const int f = g * 64 + lane;
             const int id = f < TK ? ids[f] : -1;
             const bool valid = id >= 0 && id < N;
-            const uint64_t peers = match_id(id, valid);
+            const uint64_t peers = match_id(id, valid, id_bits(N));
             id2[q] = valid ? id : -1;
             rank2[q] = __popcll(peers & ((1ull << lane) - 1ull));
             if (valid && rank2[q] == 0) sh.grp[g][id] = __popcll(peers);
@@ -457,18 +350,80 @@ hipError_t launch_route_permute(const beam_shape &s, const float *router_logits,
     return hipGetLastError();
 }
 
-// A few thousand pairs (prefill chunks of up to about 2000 tokens): the whole counting
-// sort in one launch of one workgroup of 16 wavefronts instead of four launches, which
-// at this size are four times a launch's fixed cost.  Wavefront w owns a contiguous run
-// of 64-pair groups; it counts its pairs per expert into its own LDS row, thread e then
-// turns the rows into start positions (prefix over the wavefronts, prefix over the
-// experts, work list), and every wavefront walks its run again in order, placing each
-// kept pair at its expert's running position: stable, no atomics, same result as the
-// four-launch path.
+// One slice of the pair list in a workgroup of 16 wavefronts.  Wavefront w owns a
+// contiguous run of `per_wave` 64-pair groups starting at pair f0 - lane; it counts its
+// pairs per expert into its own LDS row (slice_count), thread e then turns the rows into
+// start positions, and every wavefront walks its run again in order, placing each kept
+// pair at its expert's running position (slice_place): stable, no atomics.
 constexpr int kOneWgWaves = 16;
 constexpr int kOneWgGroups = 8;   // 64-pair groups per wavefront, held in registers
 constexpr int kOneWgMaxPairs = 64 * kOneWgWaves * kOneWgGroups;
 
+struct SlicePairs {
+    int ids[kOneWgGroups];          // -1: masked, past the run or past the input
+    uint64_t peers[kOneWgGroups];   // lanes of the group with the same id
+};
+
+// Every thread of the workgroup must call it (two barriers).  Afterwards pos[w][e] is the
+// number of kept pairs of expert e in wavefront w's run.
+__device__ __forceinline__ void slice_count(const int32_t *__restrict__ masked_ids, int TK, int N,
+                                            int f0, int per_wave, int (*pos)[256],
+                                            SlicePairs &sp) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    // all loads of the run in flight at once
+#pragma unroll
+    for (int q = 0; q < kOneWgGroups; ++q) {
+        const int f = f0 + q * 64;
+        const int id = (q < per_wave && f < TK) ? masked_ids[f] : -1;
+        sp.ids[q] = (id >= 0 && id < N) ? id : -1;
+    }
+    for (int i = tid; i < kOneWgWaves * 256; i += 64 * kOneWgWaves) (&pos[0][0])[i] = 0;
+    __syncthreads();
+    const int nbits = id_bits(N);
+#pragma unroll
+    for (int q = 0; q < kOneWgGroups; ++q) {
+        sp.peers[q] = 0;
+        if (q >= per_wave) continue;   // uniform: small inputs use the first groups only
+        const bool valid = sp.ids[q] >= 0;
+        sp.peers[q] = match_id(sp.ids[q], valid, nbits);
+        if (valid && (sp.peers[q] & ((1ull << lane) - 1ull)) == 0)
+            pos[wave][sp.ids[q]] += __popcll(sp.peers[q]);
+    }
+    __syncthreads();
+}
+
+// pos[w][e] holds the position of the first pair of expert e in wavefront w's run; `total`
+// is the number of kept pairs of the whole input (rows from there on carry no pair).
+__device__ __forceinline__ void slice_place(const SlicePairs &sp, int TK, int f0, int per_wave,
+                                            int total, int (*pos)[256],
+                                            int32_t *__restrict__ perm,
+                                            int32_t *__restrict__ inv_perm) {
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int q = 0; q < kOneWgGroups; ++q) {
+        if (q >= per_wave) continue;
+        const int f = f0 + q * 64;
+        const bool valid = sp.ids[q] >= 0;
+        const int rank = __popcll(sp.peers[q] & ((1ull << lane) - 1ull));
+        const int base = valid ? pos[wave][sp.ids[q]] : 0;
+        if (valid && rank == 0) pos[wave][sp.ids[q]] = base + __popcll(sp.peers[q]);
+        if (f < TK) {
+            if (valid) {
+                perm[base + rank] = f;
+                inv_perm[f] = base + rank;
+            } else {
+                inv_perm[f] = -1;
+            }
+            if (f >= total) perm[f] = -1;  // rows [P, T*K) carry no pair
+        }
+    }
+}
+
+// A few thousand pairs (prefill chunks of up to about 1000 tokens): the whole counting
+// sort in one launch of one workgroup.
 __global__ __launch_bounds__(64 * kOneWgWaves) void permute_one_workgroup_kernel(
     const int32_t *__restrict__ masked_ids, int32_t *__restrict__ counts,
     int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm,
@@ -476,32 +431,11 @@ __global__ __launch_bounds__(64 * kOneWgWaves) void permute_one_workgroup_kernel
     __shared__ int pos[kOneWgWaves][256];   // per wavefront and expert: count, then next position
     __shared__ int scratch[256];
     const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
     const int groups = (TK + 63) >> 6;
     const int per_wave = (groups + kOneWgWaves - 1) / kOneWgWaves;   // <= kOneWgGroups
-    const int f0 = wave * per_wave * 64 + lane;
-    // this wavefront's ids, all loads in flight at once; -1 past its run or past the input
-    int ids[kOneWgGroups];
-#pragma unroll
-    for (int q = 0; q < kOneWgGroups; ++q) {
-        const int f = f0 + q * 64;
-        int id = (q < per_wave && f < TK) ? masked_ids[f] : -1;
-        ids[q] = (id >= 0 && id < N) ? id : -1;
-    }
-    for (int i = tid; i < kOneWgWaves * 256; i += 64 * kOneWgWaves) (&pos[0][0])[i] = 0;
-    __syncthreads();
-    uint64_t peers[kOneWgGroups];
-#pragma unroll
-    for (int q = 0; q < kOneWgGroups; ++q) {
-        peers[q] = 0;
-        if (q >= per_wave) continue;   // uniform: small inputs use the first groups only
-        const bool valid = ids[q] >= 0;
-        peers[q] = match_id(ids[q], valid);
-        if (valid && (peers[q] & ((1ull << lane) - 1ull)) == 0)
-            pos[wave][ids[q]] += __popcll(peers[q]);
-    }
-    __syncthreads();
+    const int f0 = (tid >> 6) * per_wave * 64 + (tid & 63);
+    SlicePairs sp;
+    slice_count(masked_ids, TK, N, f0, per_wave, pos, sp);
     int cnt = 0;
     if (tid < 256) {   // thread e: exclusive prefix of expert e's counts over the wavefronts
 #pragma unroll
@@ -527,33 +461,104 @@ __global__ __launch_bounds__(64 * kOneWgWaves) void permute_one_workgroup_kernel
     }
     emit_work_list(tid, N, cnt, excl, wl, scratch, longest_first != 0);
     __syncthreads();
+    slice_place(sp, TK, f0, per_wave, total, pos, perm, inv_perm);
+}
+
+// More than one workgroup's worth of pairs: slices of 16 * per_wave groups, short ones while
+// that keeps the slices few (the ballots that rank equal ids are scalar work, which the
+// wavefronts of a compute unit do one after the other: many short slices on many compute
+// units finish sooner than a few long ones).
+static int slice_groups_per_wave(long TK) {
+    int g = 2;
+    while (g < kOneWgGroups && TK > 128L * 64 * kOneWgWaves * g) g *= 2;
+    return g;
+}
+
+// First launch: slice_counts[slice][e] = kept pairs of expert e.
+__global__ __launch_bounds__(64 * kOneWgWaves) void slice_count_kernel(
+    const int32_t *__restrict__ masked_ids, int32_t *__restrict__ slice_counts, int TK, int N,
+    int per_wave) {
+    __shared__ int pos[kOneWgWaves][256];
+    const int tid = threadIdx.x;
+    const int f0 = (blockIdx.x * kOneWgWaves + (tid >> 6)) * per_wave * 64 + (tid & 63);
+    SlicePairs sp;
+    slice_count(masked_ids, TK, N, f0, per_wave, pos, sp);
+    if (tid < N) {
+        int cnt = 0;
 #pragma unroll
-    for (int q = 0; q < kOneWgGroups; ++q) {
-        if (q >= per_wave) continue;
-        const int f = f0 + q * 64;
-        const bool valid = ids[q] >= 0;
-        const int rank = __popcll(peers[q] & ((1ull << lane) - 1ull));
-        const int base = valid ? pos[wave][ids[q]] : 0;
-        if (valid && rank == 0) pos[wave][ids[q]] = base + __popcll(peers[q]);
-        if (f < TK) {
-            if (valid) {
-                perm[base + rank] = f;
-                inv_perm[f] = base + rank;
-            } else {
-                inv_perm[f] = -1;
-            }
-            if (f >= total) perm[f] = -1;  // rows [P, T*K) carry no pair
+        for (int w = 0; w < kOneWgWaves; ++w) cnt += pos[w][tid];
+        slice_counts[(size_t)blockIdx.x * N + tid] = cnt;
+    }
+}
+
+// Second launch, nslice + 1 workgroups.  Workgroup b < nslice places the pairs of slice b:
+// thread e adds up expert e's counts over all slices (the expert's total) and over the
+// slices before b, a scan of the totals gives the expert's first row, and the wavefronts'
+// own counts, taken again from the ids, give every wavefront its first row inside that.
+// Workgroup nslice reads no ids: it writes the per-expert arrays and the work list.
+__global__ __launch_bounds__(64 * kOneWgWaves) void slice_scatter_kernel(
+    const int32_t *__restrict__ masked_ids, const int32_t *__restrict__ slice_counts,
+    int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ perm,
+    int32_t *__restrict__ inv_perm, int32_t *__restrict__ num_pairs, int TK, int N, int nslice,
+    int per_wave, WorkList wl, int longest_first) {
+    __shared__ int pos[kOneWgWaves][256];
+    __shared__ int scratch[256];
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x;
+    const bool lister = b == nslice;   // uniform over the workgroup
+    const int f0 = (b * kOneWgWaves + (tid >> 6)) * per_wave * 64 + (tid & 63);
+    // the other slices' counts are requested first: their latency passes under the counting
+    int cnt = 0, before = 0;
+    if (tid < N) {
+#pragma unroll 8
+        for (int sl = 0; sl < nslice; ++sl) {
+            const int c = slice_counts[(size_t)sl * N + tid];
+            before += sl < b ? c : 0;
+            cnt += c;
         }
     }
+    SlicePairs sp;
+    if (!lister) slice_count(masked_ids, TK, N, f0, per_wave, pos, sp);
+    int total;
+    const int excl = block_exclusive_scan_256(cnt, scratch, &total);
+    if (lister) {
+        if (tid < N) {
+            counts[tid] = cnt;
+            offsets[tid] = excl;
+        }
+        if (tid == 0) {
+            offsets[N] = total;
+            *num_pairs = total;
+        }
+        emit_work_list(tid, N, cnt, excl, wl, scratch, longest_first != 0);
+        return;
+    }
+    if (tid < 256) {
+        int run = excl + before;
+#pragma unroll
+        for (int w = 0; w < kOneWgWaves; ++w) {
+            const int c = pos[w][tid];
+            pos[w][tid] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+    slice_place(sp, TK, f0, per_wave, total, pos, perm, inv_perm);
+}
+
+int permute_slices(long TK) {
+    const long slice = 64L * kOneWgWaves * slice_groups_per_wave(TK);
+    const long n = (TK + slice - 1) / slice;
+    return n < 1 ? 1 : (int)n;
 }
 
 hipError_t launch_permute(const beam_shape &s, const int32_t *masked_ids, int32_t *counts,
                           int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *num_pairs,
-                          int32_t *blk_counts, int32_t *blk_base, int nchunk, const WorkList &wl,
-                          hipStream_t st, bool longest_first) {
+                          int32_t *slice_counts, const WorkList &wl, hipStream_t st,
+                          bool longest_first) {
     const int TK = s.T * s.K;
     const int lf = longest_first ? 1 : 0;
-    if (nchunk == 1) {
+    if (TK <= kChunk) {
         permute_single_chunk_kernel<<<1, 256, 0, st>>>(masked_ids, counts, offsets, perm, inv_perm,
                                                        num_pairs, TK, s.N, wl);
         return hipGetLastError();
@@ -563,13 +568,14 @@ hipError_t launch_permute(const beam_shape &s, const int32_t *masked_ids, int32_
             masked_ids, counts, offsets, perm, inv_perm, num_pairs, TK, s.N, wl, lf);
         return hipGetLastError();
     }
-    count_kernel<<<nchunk, 64, 0, st>>>(masked_ids, blk_counts, TK, s.N);
+    const int nslice = permute_slices(TK);
+    const int per_wave = slice_groups_per_wave(TK);
+    slice_count_kernel<<<nslice, 64 * kOneWgWaves, 0, st>>>(masked_ids, slice_counts, TK, s.N,
+                                                             per_wave);
     BEAM_CHECK_LAUNCH();
-    chunk_prefix_kernel<<<s.N, 256, 0, st>>>(blk_counts, blk_base, counts, nchunk);
-    BEAM_CHECK_LAUNCH();
-    scan_kernel<<<1, 256, 0, st>>>(counts, offsets, num_pairs, s.N, wl, lf);
-    BEAM_CHECK_LAUNCH();
-    scatter_kernel<<<nchunk, 64, 0, st>>>(masked_ids, offsets, blk_base, perm, inv_perm, TK, s.N);
+    slice_scatter_kernel<<<nslice + 1, 64 * kOneWgWaves, 0, st>>>(
+        masked_ids, slice_counts, counts, offsets, perm, inv_perm, num_pairs, TK, s.N, nslice,
+        per_wave, wl, lf);
     return hipGetLastError();
 }
 

@@ -141,6 +141,8 @@ def _run_permute(m_host, N, K):
     # around the largest pair count of the single-workgroup sort (8192) and twice that, ragged last group
     (1024, 8, 128, 0.3), (1025, 8, 128, 0.3), (629, 13, 200, 0.5), (2730, 3, 7, 1.0),
     (2048, 8, 128, 0.3), (2049, 8, 128, 0.3), (5461, 3, 7, 1.0), (1261, 13, 200, 0.5),
+    # pair counts at which the slices of the two-launch sort double in length, and past them
+    (32768, 8, 128, 0.3), (32769, 8, 128, 0.3), (40001, 8, 60, 0.15), (70003, 8, 256, 0.5),
 ])
 def test_permute(T, K, N, keep):
     _log(f"permute T={T} K={K} N={N} keep={keep}")
