@@ -421,29 +421,51 @@ __device__ __forceinline__ void ffn_tile_run(
             // Activations were the A operand: register r of lane l is row
             // 8*(r >> 2) + 4*(l >> 5) + (r & 3), column l & 31 of the tile, so each
             // store instruction writes two full 128-byte row segments of fp32.
+            // The address is split into a part that is the same for the whole wavefront (one
+            // 64-bit pointer per item), a 32-bit part per lane and a multiple of the row pitch
+            // per register, so that a store costs one 32-bit add; blocks of 32 rows that lie
+            // inside the expert's segment are stored without the per-row test.
             auto store_tile = [&](auto stream, auto half) {
                 using Y = std::conditional_t<decltype(half)::value, _Float16, float>;
+                constexpr uint32_t ysz = sizeof(Y);
+                char *base = (char *)y_out +
+                             ((size_t)done.slice * slice_stride +
+                              (size_t)(done.row0 + wm * (BM / WM)) * H + n0 + wn * WTN * 32) * ysz;
+                const uint32_t pitch = (uint32_t)H * ysz;
+                const int rows = done.row_end - done.row0 - wm * (BM / WM);   // uniform
+                const int lane_rows = rows - kh * 4;
+                const uint32_t lane_off = (uint32_t)(kh * 4) * pitch + (uint32_t)l32 * ysz;
+                auto store_row = [&](int m, int r, uint32_t pitch_m) {
+                    const uint32_t off =
+                        lane_off + (uint32_t)(m * 32 + (r >> 2) * 8 + (r & 3)) * pitch_m;
+#pragma unroll
+                    for (int n = 0; n < WTN; ++n) {
+                        if (COL_GUARD && n0 + l32 + (wn * WTN + n) * 32 >= H) continue;
+                        Y v;
+                        if constexpr (decltype(half)::value)
+                            v = (Y)__builtin_amdgcn_fmed3f(acc[m][n][r], -65504.0f, 65504.0f);
+                        else
+                            v = acc[m][n][r];
+                        Y *dst = (Y *)(base + off) + n * 32;
+                        if constexpr (decltype(stream)::value) __builtin_nontemporal_store(v, dst);
+                        else *dst = v;
+                    }
+                };
 #pragma unroll
                 for (int m = 0; m < WTM; ++m) {
+                    if (m * 32 >= rows) break;   // uniform
+                    // The pitch passes through an empty asm per block so that the row offsets
+                    // are formed where they are used, one scalar multiply and one add each; left
+                    // alone the compiler forms all of them ahead of the item and spills them.
+                    uint32_t pitch_m = pitch;
+                    asm volatile("" : "+s"(pitch_m));
+                    if ((m + 1) * 32 <= rows) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int trow = wm * (BM / WM) + m * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
-                        const int grow = done.row0 + trow;
-                        if (grow >= done.row_end) continue;
-                        Y *orow = (Y *)y_out + done.slice * slice_stride + (size_t)grow * H + n0 + l32;
+                        for (int r = 0; r < 16; ++r) store_row(m, r, pitch_m);
+                    } else {
 #pragma unroll
-                        for (int n = 0; n < WTN; ++n) {
-                            if (COL_GUARD && n0 + l32 + (wn * WTN + n) * 32 >= H) continue;
-                            Y v;
-                            if constexpr (decltype(half)::value)
-                                v = (Y)fminf(fmaxf(acc[m][n][r], -65504.0f), 65504.0f);
-                            else
-                                v = acc[m][n][r];
-                            if constexpr (decltype(stream)::value)
-                                __builtin_nontemporal_store(v, &orow[(wn * WTN + n) * 32]);
-                            else
-                                orow[(wn * WTN + n) * 32] = v;
-                        }
+                        for (int r = 0; r < 16; ++r)
+                            if (m * 32 + (r >> 2) * 8 + (r & 3) < lane_rows) store_row(m, r, pitch_m);
                     }
                 }
             };
