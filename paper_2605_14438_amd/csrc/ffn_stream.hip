@@ -510,7 +510,10 @@ __device__ __forceinline__ void gate_up_rows_packed(const bf16_t *__restrict__ x
     const int kh = lane >> 5;
     const int ksteps = H >> 4;
     const int kper = ksteps >> 2;  // k-steps of this wavefront
-    const int k0 = ks4 * kper;
+    // The wavefronts take the chunks of CH k-steps in turn (wavefront w: chunks w, w + 4,
+    // ...), so the workgroup reads each of its two row blocks as one sequential stream
+    // instead of four streams a quarter of the block apart.
+    const int k0 = ks4 * CH;
     // blocks 2q (gate) and 2q + 1 (up) of this expert's 2I/32 row blocks
     const bf16_t *gp =
         w_gate_up + (((size_t)e * ((2 * I) >> 5) + 2 * q) * ksteps + k0) * 512 + lane * 8;
@@ -528,15 +531,15 @@ __device__ __forceinline__ void gate_up_rows_packed(const bf16_t *__restrict__ x
 #pragma unroll
             for (int j = 0; j < CH; ++j) {
                 if constexpr (STREAM) {
-                    wg[b][j] = load_weights16v(gp + (size_t)(k + j) * 512);
-                    wu[b][j] = load_weights16v(up + (size_t)(k + j) * 512);
+                    wg[b][j] = load_weights16v(gp + (size_t)(4 * k + j) * 512);
+                    wu[b][j] = load_weights16v(up + (size_t)(4 * k + j) * 512);
                 } else {
-                    wg[b][j] = *(const u32x4s *)(gp + (size_t)(k + j) * 512);
-                    wu[b][j] = *(const u32x4s *)(up + (size_t)(k + j) * 512);
+                    wg[b][j] = *(const u32x4s *)(gp + (size_t)(4 * k + j) * 512);
+                    wu[b][j] = *(const u32x4s *)(up + (size_t)(4 * k + j) * 512);
                 }
             }
 #pragma unroll
-            for (int j = 0; j < CH; ++j) xv[b][j] = *(const u32x4s *)(xp + (k + j) * 16);
+            for (int j = 0; j < CH; ++j) xv[b][j] = *(const u32x4s *)(xp + (4 * k + j) * 16);
         };
         auto mma = [&](int b) {
 #pragma unroll
