@@ -507,7 +507,7 @@ __global__ __launch_bounds__(64 * NW, OCC) void ffn_tile_kernel(
     const int32_t *__restrict__ wl_hdr, const int32_t *__restrict__ tile_expert,
     const int32_t *__restrict__ tile_row0, bf16_t *__restrict__ hidden_out,
     float *__restrict__ y_out, int H, int K, int I, int n_col_tiles, int k_split,
-    size_t slice_stride, int want, int y16) {
+    size_t slice_stride, int want, int y16, int tiles_lo, int tiles_hi) {
     __shared__ u32x4 As[2 * kTileM * 2 * KS];
     // Item order: the row tiles of an expert in groups of up to kRowGroup (a group
     // never spans two experts); inside a group the column tile is the slow index
@@ -517,7 +517,10 @@ __global__ __launch_bounds__(64 * NW, OCC) void ffn_tile_kernel(
     // with F the list index of its first row tile, so item / n_col_tiles is always
     // a row tile of the item's own group, from which the group is reconstructed.
     // not the regime chosen on the device: no tiles for this kernel, every workgroup leaves
-    const int n_tiles = (want != kRegimeAny && wl_hdr[2] != want) ? 0 : wl_hdr[1];
+    // tiles_lo, tiles_hi: the kernel runs for work lists of tiles_lo .. tiles_hi row tiles only
+    // (two schedules enqueued for one GEMM: the tile count, known on the device, picks one)
+    int n_tiles = (want != kRegimeAny && wl_hdr[2] != want) ? 0 : wl_hdr[1];
+    if (n_tiles < tiles_lo || n_tiles > tiles_hi) n_tiles = 0;
     // with a split reduction: all items of part 0, then all of part 1, ...
     const int n_base = n_tiles * n_col_tiles;
     const int n_work = n_base * k_split;
@@ -567,10 +570,11 @@ static void launch_tile(const beam_shape &s, const bf16_t *a, const bf16_t *w,
                         bf16_t *hidden, float *y, int nct, int k_split, hipStream_t st, int want,
                         int y16 = 0) {
     const bool packed = s.weight_layout == BEAM_WEIGHTS_PACKED;
+    int tiles_lo = 0, tiles_hi = 0x7fffffff;
 #define BEAM_LAUNCH_TILE(KS_, OCC_, PK)                                                        \
     ffn_tile_kernel<kWavesM, KS_, OCC_, GATE_UP, PK, 4><<<256 * OCC_, 256, 0, st>>>(           \
         a, w, offsets, perm, wl.hdr, wl.tile_expert, wl.tile_row0, hidden, y, s.H, s.K, s.I, nct, \
-        k_split, (size_t)s.T * s.K * s.H, want, y16)
+        k_split, (size_t)s.T * s.K * s.H, want, y16, tiles_lo, tiles_hi)
     // Three schedules of the same tile body.  "Dense": 64-wide K-steps, two
     // workgroups per CU, whose MFMAs cover each other's prologue, epilogue and
     // barriers; the faster one when the reduction is short and the work MFMA
@@ -580,8 +584,27 @@ static void launch_tile(const beam_shape &s, const bf16_t *a, const bf16_t *w,
     // when the reduction is long (H >= 4096) or when there are so few rows per
     // expert that the kernel can only be bound by streaming the weights
     // (at most 256 per expert even with every pair kept).
+    const bool wide_fits = packed && k_split == 1 &&
+                           (GATE_UP ? (2 * s.I) % 512 == 0 : s.H % 512 == 0);
     if constexpr (GATE_UP) {
-        if (packed && (s.H >= 4096 || (long)s.T * s.K <= 256L * s.N)) {
+        const long TK = (long)s.T * s.K;
+        if (packed && s.H < 4096 && wide_fits && TK >= 64L * s.N && TK <= 512L * s.N) {
+            // In between, which of the deep and the wide schedule is faster follows the number
+            // of row tiles, which depends on the keep rate and the routing skew: the wide one
+            // needs more than about 1.25 items per workgroup to fill the chip evenly (Qwen3
+            // shape, deep / wide gate/up in us: T = 4096 keep 15 %, 103 tiles, 124 / 143;
+            // keep 25 % 153 / 144, keep 100 % 292 / 269; T = 2048 keep 50 % 157 / 145;
+            // T = 1024 keep 50 % 130 / 149, keep 100 % 158 / 148).  Both are enqueued and the
+            // one whose range the tile count is not in leaves at once (whole layer, deep /
+            // wide / both enqueued: T = 4096 keep 15 % 232 / 246 / 232, keep 25 % 280 / 264 /
+            // 266, keep 100 % 517 / 486 / 489; T = 2048 keep 50 % 299 / 278 / 281).
+            const int max_deep = 640 / nct;   // nct column tiles of 256; the wide tile spans two
+            tiles_hi = max_deep;
+            BEAM_LAUNCH_TILE(8, 1, true);
+            if (hipPeekAtLastError() != hipSuccess) return;   // the caller reads and reports it
+            tiles_lo = max_deep + 1;
+            tiles_hi = 0x7fffffff;
+        } else if (packed && (s.H >= 4096 || TK <= 256L * s.N)) {
             BEAM_LAUNCH_TILE(8, 1, true);
             return;
         }
@@ -593,10 +616,10 @@ static void launch_tile(const beam_shape &s, const bf16_t *a, const bf16_t *w,
     // the dense schedule (Qwen3 shape): gate/up 799 -> 767 us at T = 16384 with every pair
     // kept, 210 -> 197 at 15 %, 456 -> 441 at T = 8192; down 317 -> 305 at T = 8192,
     // Mixtral shape T = 2048 419 -> 391, large layer T = 8192 349 -> 330.
-    if (packed && k_split == 1 && (GATE_UP ? (2 * s.I) % 512 == 0 : s.H % 512 == 0)) {
+    if (wide_fits) {
         ffn_tile_kernel<kWavesM, kKSteps, 1, GATE_UP, true, 8><<<256, 512, 0, st>>>(
             a, w, offsets, perm, wl.hdr, wl.tile_expert, wl.tile_row0, hidden, y, s.H, s.K, s.I,
-            nct / 2, k_split, (size_t)s.T * s.K * s.H, want, y16);
+            nct / 2, k_split, (size_t)s.T * s.K * s.H, want, y16, tiles_lo, tiles_hi);
         return;
     }
     if (packed) BEAM_LAUNCH_TILE(kKSteps, kWorkgroupsPerCU, true);
