@@ -350,6 +350,51 @@ def test_expert_ffn_row_counts_at_the_tile_boundaries(wide, packed):
     _log(f"  P={P} worst row error / rms = {worst.max():.3e}")
 
 
+@pytest.mark.parametrize("tiles", [320, 321])
+def test_expert_ffn_on_both_sides_of_the_tile_count_that_picks_the_schedule(tiles):
+    """For batches of 64 to 512 rows per expert in the worst case two schedules of the gate/up
+    GEMM are enqueued and the number of row tiles in the work list decides on the device which
+    of them runs: up to 640 / (I / 128) tiles the deep one, from there on the wide one, whose
+    short K-loop serves ragged tiles of at most 32 / 64 rows.  Here I = 256 puts the limit at
+    320 tiles; the crafted counts give 320 and 321, boundary row counts included, and every
+    row is compared with the oracle's."""
+    boundary = [1, 31, 32, 33, 63, 64, 65, 127, 128, 129]          # 11 tiles
+    counts = boundary + [129] * 150 + [100] * (tiles - 311)         # + 300 + 9 or 10
+    N, K = len(counts), 1
+    assert sum((c + 127) // 128 for c in counts) == tiles
+    T = int(np.sum(counts)) + 5
+    assert 64 * N <= T * K <= 512 * N
+    cfg = synth.LayerConfig("tile_count", 23, T=T, H=512, N=N, K=K, I=256, dtype="bf16", keep=1.0)
+    _log(f"expert_ffn tile count {tiles} {cfg}")
+    d = synth.make_layer(cfg)
+    rng = np.random.default_rng(tiles)
+    ids = np.concatenate([np.repeat(np.arange(N, dtype=np.int32), counts),
+                          np.full(5, -1, dtype=np.int32)])
+    rng.shuffle(ids)
+    msk = ids.reshape(T, K)
+    cnt_o, offsets, perm, inv, P = oracle.permute(msk, N)
+    assert list(cnt_o) == counts
+    y_slots, _ = oracle.pair_outputs(d["x"], d["w_gate_up"], d["w_down"], msk)
+    g = hp.upload(cfg, d)
+    s = hp.shape_of(cfg, packed=True)
+    g["w_gate_up"], g["w_down"] = hp.pack_weights(cfg, g["w_gate_up"], g["w_down"])
+    ws, nb = hp.workspace(s)
+    y_pairs = torch.full((T * K, cfg.H), float("nan"), dtype=torch.float32, device="cuda")
+    beam.beam_expert_ffn(s, g["x"], g["w_gate_up"], g["w_down"], torch.from_numpy(offsets).cuda(),
+                         torch.from_numpy(perm).cuda(),
+                         torch.tensor([P], dtype=torch.int32, device="cuda"), y_pairs, ws, nb,
+                         hp.stream_ptr())
+    torch.cuda.synchronize()
+    y_h = y_pairs.cpu().numpy().astype(np.float64)
+    assert np.isnan(y_h[P:]).all()
+    ref_rows = y_slots[perm[:P]]
+    rms = np.sqrt(np.mean(ref_rows ** 2))
+    worst = np.abs(y_h[:P] - ref_rows).max(axis=1) / rms
+    assert not np.isnan(worst).any()
+    assert worst.max() < 2e-2, (int(worst.argmax()), float(worst.max()))
+    _log(f"  P={P} worst row error / rms = {worst.max():.3e}")
+
+
 FWD_CASES = [
     CFG["tiny"], CFG["tiny"].with_(T=1), CFG["tiny"].with_(T=130, keep=1.0), SMALL_BF16, ODD_BF16,
     # the envelope's corners: most experts (N = 256, 16 slots), K = N (softmax over all
