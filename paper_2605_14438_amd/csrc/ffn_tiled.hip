@@ -604,6 +604,22 @@ static void launch_tile(const beam_shape &s, const bf16_t *a, const bf16_t *w,
             if (hipPeekAtLastError() != hipSuccess) return;   // the caller reads and reports it
             tiles_lo = max_deep + 1;
             tiles_hi = 0x7fffffff;
+        } else if (packed && s.H >= 4096 && wide_fits && TK >= 64L * s.N) {
+            // Long reduction: the deep schedule's 128-wide K-steps halve the barriers per
+            // byte, and it keeps the lead while the wide schedule's items make fewer than
+            // about five rounds over the workgroups, i.e. while what the last, partial round
+            // wastes outweighs the wide tile's fewer load bytes.  Measured gate/up, deep / wide
+            // in us, by rounds of the wide items: large layer T = 4096 (128 tiles, 3.0 rounds)
+            // 566 / 567, T = 8192 (131 tiles, 3.1) 626 / 648, T = 16384 (256 tiles, 6.0)
+            // 858 / 785; Mixtral shape T = 2048 (24 tiles of 56 column tiles, 5.25) 650 / 613,
+            // with every pair kept (7.0) 1000 / 895, T = 4096 1127 / 1028.  Both are enqueued
+            // and the tile count picks one, as above.
+            const int max_deep = (5 * 256 - 1) * 2 / nct;
+            tiles_hi = max_deep;
+            BEAM_LAUNCH_TILE(8, 1, true);
+            if (hipPeekAtLastError() != hipSuccess) return;   // the caller reads and reports it
+            tiles_lo = max_deep + 1;
+            tiles_hi = 0x7fffffff;
         } else if (packed && (s.H >= 4096 || TK <= 256L * s.N)) {
             BEAM_LAUNCH_TILE(8, 1, true);
             return;
