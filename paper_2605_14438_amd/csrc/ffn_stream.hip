@@ -495,7 +495,10 @@ constexpr int kPackedChunk = 8;
 constexpr int kGateUpPackedChunk = 4;
 
 // hidden rows [row_beg, row_end) x the 32 features of block q of expert e; the 4
-// wavefronts split the reduction over H.  red: LDS, 3 * 32 * 64 floats.
+// wavefronts share the reduction over H, chunk by chunk in turn (measured against four
+// contiguous quarters, Qwen3-shaped decode layer at T = 64: this kernel 66.9 -> 59.7 us,
+// 0.74 -> 0.83 of the HBM peak; with eight read points per workgroup instead of two the
+// chip kept four times as many streams open in DRAM).  red: LDS, 3 * 32 * 64 floats.
 // STREAM: weights with the non-temporal hint (not for the single-token kernels, where
 // it measured 2 us slower per layer: a handful of workgroups, nothing to displace).
 template <int CH, bool STREAM, typename TokenOf>
